@@ -1,0 +1,51 @@
+"""Host-side accounting pinned to the figures the paper prints."""
+import pytest
+
+from paper_2510_25977_amd import costmodel as cm
+from tests.conftest import read_golden
+
+
+def test_table1_flop_counts():
+    for M, K, r, N, B_N, seq, naive in read_golden("paper_table1_flops.txt"):
+        M, K, r, N, B_N = map(int, (M, K, r, N, B_N))
+        assert round(cm.xuv_flops(M, K, r, N) / 1e9, 2) == seq
+        assert round(cm.xuv_naive_fused_flops(M, K, r, N, B_N) / 1e9, 2) == naive
+        # the recompute factor of Sec. 3.2: ceil(8192 / 512) = 16, a 4x increase in FLOPs
+        assert cm.xuv_naive_fused_flops(M, K, r, N, B_N) / cm.xuv_flops(M, K, r, N) == pytest.approx(4.0)
+
+
+def test_table3_arithmetic_intensity_eq10():
+    M, K, N = 4096, 7168, 18432
+    for B_M, r, s, printed in read_golden("paper_table3_intensity.txt"):
+        B_M, r, s = int(B_M), int(r), int(s)
+        ai = cm.xuv_arithmetic_intensity(r, B_M, s)
+        assert abs(ai - printed) <= 0.035          # the paper truncates / rounds to two decimals
+        # closed form == ratio of the two models
+        assert ai == pytest.approx(cm.xuv_flops(M, K, r, N) / cm.xuv_hbm_bytes(M, K, r, N, B_M, s))
+
+
+def test_eq11_is_max_of_two_phases():
+    B_M, B_K, B_r, B_N, r = 1024, 512, 128, 256, 4096
+    p1 = (B_M * r + B_M * B_K + B_K * B_r) * 2
+    p2 = (B_M * r + B_r * B_N + B_M * B_N) * 2
+    # the paper's closed form bounds both phases from above
+    assert cm.peak_sbuf_bytes(B_M, B_K, B_r, B_N, r) >= max(p1, p2)
+    assert cm.peak_sbuf_bytes(B_M, B_K, B_r, B_N, r) == (B_M * r + (B_M + B_r) * max(B_K, B_N)) * 2
+
+
+def test_rank_rule_eq5():
+    # k n (1-ratio) / ((k+n) block) = 2048*8192*0.8/(10240*128) = 10.24 -> floor(10.74) = 10 blocks
+    assert cm.block_aligned_rank(2048, 8192, 0.2, 128) == 1280
+    # 4096*14336*0.95/(18432*128) = 23.64 -> floor(24.14) = 24 blocks
+    assert cm.block_aligned_rank(4096, 14336, 0.05, 128) == 3072
+    assert cm.block_aligned_rank(64, 64, 0.99, 128) == 128          # never zero blocks
+    r = cm.block_aligned_rank(4096, 14336, 0.05, 128)
+    assert abs(cm.compression_ratio(4096, 14336, r) - 0.05) < 0.02
+
+
+def test_gated_mlp_totals():
+    M, d, ffn, r = 4096, 4096, 14336, 512
+    assert cm.gated_mlp_flops(M, d, ffn, r) == 6 * M * r * (d + ffn)
+    assert cm.gated_mlp_bytes(M, d, ffn, r) == 2 * (3 * r * (d + ffn) + 2 * M * d)
+    assert cm.dense_mlp_flops(M, d, ffn) == 6 * M * d * ffn
+    assert cm.gated_mlp_flops(16, d, ffn, r, r_down=256) == 2 * 2 * 16 * r * (d + ffn) + 2 * 16 * 256 * (d + ffn)
