@@ -1,0 +1,122 @@
+/*
+ * svdmlp.h — C ABI of the fused SVD-factored MLP forward for AMD MI355X (gfx950).
+ *
+ * The library evaluates, for a gated MLP block whose gate / up / down weights
+ * are rank-r factor pairs (paper Alg. 2 "SVD-compressed MLP layer", with the
+ * on-chip SiLU-gate epilogue of Alg. 3):
+ *
+ *     Y = ( ( SiLU( (X Ug) Vg )  .*  ( (X Uu) Vu ) ) Ud ) Vd
+ *
+ * and, as kind LINEAR, the single fused low-rank linear layer the MLP kernels
+ * are derived from (paper Sec. 4.2.1, "XUV NKI kernel"; block form Eq. 1):
+ *
+ *     O = (X U) V
+ *
+ * Shapes follow the "Require" line of Alg. 2 (paper names K = d, N = ffn,
+ * r2 = r_down):  X[M,d]  Ug,Uu[d,r]  Vg,Vu[r,ffn]  Ud[ffn,r_down]
+ * Vd[r_down,d]  Y[M,d].  LINEAR uses Ug as U[d,r] and Vg as V[r,ffn] and
+ * produces O[M,ffn]; the other four factor pointers are ignored.
+ *
+ * Everything is dense row-major (leading dimension = number of columns).
+ * All data pointers are DEVICE pointers on the current HIP device, 16-byte
+ * aligned; they are borrowed, never owned or freed by the library.
+ *
+ * Plain C: no C++ types and no exceptions cross this boundary.
+ */
+#ifndef SVDMLP_H
+#define SVDMLP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct svdmlp_ctx svdmlp_ctx; /* opaque; host memory only */
+
+/* Storage type of X, the six factors and Y.
+ *   BF16: bf16 in HBM, fp32 accumulation on the matrix cores, intermediates
+ *         (the rank-r strips and the ffn-wide activation) rounded to bf16
+ *         round-to-nearest-even, mirroring the paper's 16-bit cached strip
+ *         with 4-byte accumulation (Sec. 2.2 "Matmul tiling", Sec. 4.2.1 "Caching").
+ *   F32 : debug path, fp32 storage and fp32 arithmetic everywhere, no matrix cores. */
+enum { SVDMLP_BF16 = 0, SVDMLP_F32 = 1 };
+
+/* GATED: Alg. 2.  LINEAR: Sec. 4.2.1 (fp32 debug path only). */
+enum { SVDMLP_GATED = 0, SVDMLP_LINEAR = 1 };
+
+/* Status codes (0 = success, negative = failure). */
+enum {
+  SVDMLP_OK = 0,
+  SVDMLP_INVALID_ARGUMENT = -1,   /* null pointer, non-positive extent, M > max_M, misaligned pointer, r > min(d,ffn) */
+  SVDMLP_UNSUPPORTED = -2,        /* dtype / kind / extent combination the kernels do not cover */
+  SVDMLP_WORKSPACE_TOO_SMALL = -3,
+  SVDMLP_HIP_ERROR = -4,          /* a HIP runtime call failed; see svdmlp_last_hip_error */
+  SVDMLP_NO_DEVICE = -5           /* no HIP device, or the current device is not gfx950 */
+};
+
+/* Bits of svdmlp_desc.flags (testing and benchmarking aids; 0 = automatic choice). */
+enum {
+  SVDMLP_FLAG_FORCE_TILED = 1u << 0,    /* bf16: always take the MFMA-tiled (prefill) path */
+  SVDMLP_FLAG_FORCE_STREAM = 1u << 1,   /* bf16: always take the weight-streaming (decode) path; needs M <= 32 */
+  SVDMLP_FLAG_SKIP_ARCH_CHECK = 1u << 2 /* do not require gfx950 (host-only unit tests of argument handling) */
+};
+
+typedef struct {
+  int32_t kind;             /* SVDMLP_GATED or SVDMLP_LINEAR */
+  int32_t dtype;            /* SVDMLP_BF16 or SVDMLP_F32 */
+  int64_t max_M;            /* largest row count svdmlp_forward will be called with (sizes the workspace) */
+  int64_t d, ffn, r, r_down;/* extents; r_down is the rank of the down projection (ignored for LINEAR) */
+  const void *Ug, *Vg;      /* gate factors [d,r], [r,ffn]   (LINEAR: U and V) */
+  const void *Uu, *Vu;      /* up factors   [d,r], [r,ffn] */
+  const void *Ud, *Vd;      /* down factors [ffn,r_down], [r_down,d] */
+  void *workspace;          /* device memory, caller-owned, 256-byte aligned, >= svdmlp_workspace_bytes() */
+  size_t workspace_bytes;
+  uint32_t flags;
+} svdmlp_desc;
+
+/* Bytes of device workspace a context for this description needs.  Pure host function (touches no
+ * device).  Returns 0 if the description is invalid or unsupported (svdmlp_create reports why).
+ * For BF16 the workspace holds a one-time re-tiled copy of the six factors (the weights are
+ * invariant at inference time, paper Sec. 2.1, so they are laid out once for the matrix cores),
+ * the rank-r intermediates, split-K partial sums and a few counters.  For F32 it holds the fp32
+ * intermediates including the ffn-wide activation. */
+size_t svdmlp_workspace_bytes(const svdmlp_desc *desc);
+
+/* Validate the description, lay the factors out in the workspace (BF16: device work on the NULL
+ * stream, completed before returning) and return a context in *out.  *out is written only on
+ * success.  The factor buffers must stay valid and unchanged until svdmlp_destroy for F32; for
+ * BF16 they are not read again after create returns.  The workspace belongs to the context until
+ * svdmlp_destroy. */
+int svdmlp_create(const svdmlp_desc *desc, svdmlp_ctx **out);
+
+/* Enqueue Y = MLP(X) (or O = (X U) V) for the first M rows on hip_stream (a hipStream_t passed as
+ * void*; NULL = the default stream).  X is [M,d]; Y is [M,d] (LINEAR: [M,ffn]); both of the context's
+ * dtype, row-major, 16-byte aligned device pointers; Y must not alias X.  Never synchronises with
+ * the host and allocates nothing.  1 <= M <= max_M; M == 0 is accepted and does nothing.  At most one
+ * forward per context may be in flight at a time (the workspace holds its intermediates), so
+ * successive calls must be ordered on one stream or by events. */
+int svdmlp_forward(svdmlp_ctx *ctx, const void *X, int64_t M, void *Y, void *hip_stream);
+
+/* Release the context's host memory.  Does not free or touch device memory; the caller must make
+ * sure no forward is still running.  svdmlp_destroy(NULL) returns SVDMLP_OK. */
+int svdmlp_destroy(svdmlp_ctx *ctx);
+
+/* Static, never-NULL description of a status code. */
+const char *svdmlp_status_string(int status);
+
+/* The hipError_t (as int) of the last failing HIP call made for this context (0 if none). */
+int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
+
+/* Which path the last svdmlp_forward on this context took: 0 none yet, 1 fp32 debug,
+ * 2 bf16 MFMA-tiled (prefill), 3 bf16 weight-streaming (decode). */
+int svdmlp_last_path(const svdmlp_ctx *ctx);
+
+/* ABI version of this header (bumped on any incompatible change). */
+int svdmlp_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVDMLP_H */

@@ -1,0 +1,171 @@
+"""Thin ctypes binding of ``libsvdmlp.so`` (same names as ``include/svdmlp.h``).
+
+Argument marshalling only: PyTorch supplies device memory and streams, every step of the forward
+runs in the library's HIP kernels.  There is no CPU or PyTorch fallback: if the library is missing
+or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional
+
+import torch
+
+HERE = Path(__file__).resolve().parent
+LIB_PATH = HERE / "libsvdmlp.so"
+
+SVDMLP_BF16, SVDMLP_F32 = 0, 1
+SVDMLP_GATED, SVDMLP_LINEAR = 0, 1
+SVDMLP_OK = 0
+SVDMLP_INVALID_ARGUMENT, SVDMLP_UNSUPPORTED, SVDMLP_WORKSPACE_TOO_SMALL, SVDMLP_HIP_ERROR, SVDMLP_NO_DEVICE = -1, -2, -3, -4, -5
+FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK = 1, 2, 4
+
+EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_status_string",
+           "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version"]
+
+
+class svdmlp_desc(ctypes.Structure):
+    _fields_ = [
+        ("kind", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("max_M", ctypes.c_int64), ("d", ctypes.c_int64), ("ffn", ctypes.c_int64), ("r", ctypes.c_int64),
+        ("r_down", ctypes.c_int64),
+        ("Ug", ctypes.c_void_p), ("Vg", ctypes.c_void_p), ("Uu", ctypes.c_void_p), ("Vu", ctypes.c_void_p),
+        ("Ud", ctypes.c_void_p), ("Vd", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("flags", ctypes.c_uint32),
+    ]
+
+
+class SvdMlpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the built library (raises if it has not been built: ``python -m paper_2510_25977_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(f"{LIB_PATH} not found: build it with `python -m paper_2510_25977_amd.build`")
+        L = ctypes.CDLL(str(LIB_PATH))
+        L.svdmlp_workspace_bytes.argtypes = [ctypes.POINTER(svdmlp_desc)]
+        L.svdmlp_workspace_bytes.restype = ctypes.c_size_t
+        L.svdmlp_create.argtypes = [ctypes.POINTER(svdmlp_desc), ctypes.POINTER(ctypes.c_void_p)]
+        L.svdmlp_create.restype = ctypes.c_int
+        L.svdmlp_forward.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        L.svdmlp_forward.restype = ctypes.c_int
+        L.svdmlp_destroy.argtypes = [ctypes.c_void_p]
+        L.svdmlp_destroy.restype = ctypes.c_int
+        L.svdmlp_status_string.argtypes = [ctypes.c_int]
+        L.svdmlp_status_string.restype = ctypes.c_char_p
+        L.svdmlp_last_hip_error.argtypes = [ctypes.c_void_p]
+        L.svdmlp_last_hip_error.restype = ctypes.c_int
+        L.svdmlp_last_path.argtypes = [ctypes.c_void_p]
+        L.svdmlp_last_path.restype = ctypes.c_int
+        L.svdmlp_abi_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().svdmlp_status_string(int(status)).decode()
+
+
+def svdmlp_workspace_bytes(desc: svdmlp_desc) -> int:
+    return int(lib().svdmlp_workspace_bytes(ctypes.byref(desc)))
+
+
+def svdmlp_create(desc: svdmlp_desc) -> ctypes.c_void_p:
+    out = ctypes.c_void_p()
+    st = lib().svdmlp_create(ctypes.byref(desc), ctypes.byref(out))
+    if st != SVDMLP_OK:
+        raise SvdMlpError(st, "svdmlp_create")
+    return out
+
+
+def svdmlp_forward(ctx, X_ptr: int, M: int, Y_ptr: int, stream_ptr: int = 0) -> None:
+    st = lib().svdmlp_forward(ctx, ctypes.c_void_p(X_ptr), int(M), ctypes.c_void_p(Y_ptr), ctypes.c_void_p(stream_ptr))
+    if st != SVDMLP_OK:
+        raise SvdMlpError(st, "svdmlp_forward")
+
+
+def svdmlp_destroy(ctx) -> None:
+    lib().svdmlp_destroy(ctx)
+
+
+_TORCH_DTYPE = {torch.bfloat16: SVDMLP_BF16, torch.float32: SVDMLP_F32}
+
+
+class SvdMlp:
+    """A context plus the torch tensors that back it (factors and workspace stay referenced here so
+    the device memory outlives the context)."""
+
+    def __init__(self, *, max_M: int, Ug: torch.Tensor, Vg: torch.Tensor, Uu: Optional[torch.Tensor] = None,
+                 Vu: Optional[torch.Tensor] = None, Ud: Optional[torch.Tensor] = None, Vd: Optional[torch.Tensor] = None,
+                 kind: int = SVDMLP_GATED, flags: int = 0):
+        self.kind = kind
+        self.tensors = [t for t in (Ug, Vg, Uu, Vu, Ud, Vd) if t is not None]
+        for t in self.tensors:
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == Ug.dtype):
+                raise ValueError("factors must be contiguous device tensors of one dtype")
+        self.dtype = Ug.dtype
+        self.d, self.r = Ug.shape
+        self.ffn = Vg.shape[1]
+        self.r_down = Ud.shape[1] if Ud is not None else 0
+        self.max_M = int(max_M)
+        de = svdmlp_desc()
+        de.kind, de.dtype = kind, _TORCH_DTYPE[self.dtype]
+        de.max_M, de.d, de.ffn, de.r, de.r_down = self.max_M, self.d, self.ffn, self.r, self.r_down
+        de.Ug, de.Vg = Ug.data_ptr(), Vg.data_ptr()
+        for name, t in (("Uu", Uu), ("Vu", Vu), ("Ud", Ud), ("Vd", Vd)):
+            setattr(de, name, t.data_ptr() if t is not None else None)
+        de.flags = flags
+        nbytes = svdmlp_workspace_bytes(de)
+        if nbytes == 0:
+            # let create report the precise reason
+            de.workspace, de.workspace_bytes = None, 0
+            svdmlp_create(de)
+            raise SvdMlpError(SVDMLP_UNSUPPORTED, "svdmlp_workspace_bytes")
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=Ug.device)
+        base = self.workspace.data_ptr()
+        de.workspace = (base + 255) // 256 * 256
+        de.workspace_bytes = nbytes
+        self.workspace_bytes = nbytes
+        self.desc = de
+        torch.cuda.synchronize(Ug.device)
+        self.ctx = svdmlp_create(de)
+
+    def out_features(self) -> int:
+        return self.d if self.kind == SVDMLP_GATED else self.ffn
+
+    def forward(self, X: torch.Tensor, Y: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+        if not (X.is_cuda and X.is_contiguous() and X.dtype == self.dtype and X.dim() == 2 and X.shape[1] == self.d):
+            raise ValueError("X must be a contiguous [M, d] device tensor of the context's dtype")
+        M = X.shape[0]
+        if Y is None:
+            Y = torch.empty((M, self.out_features()), dtype=self.dtype, device=X.device)
+        s = stream if stream is not None else torch.cuda.current_stream(X.device)
+        svdmlp_forward(self.ctx, X.data_ptr(), M, Y.data_ptr(), s.cuda_stream)
+        return Y
+
+    __call__ = forward
+
+    @property
+    def last_path(self) -> int:
+        return int(lib().svdmlp_last_path(self.ctx))
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            svdmlp_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,195 @@
+// C ABI of the svdmlp library: argument checking, workspace planning, path dispatch.
+// Host code only; every arithmetic step of the forward runs in the kernels of the other files.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+namespace svdmlp {
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int tiled_splits(int64_t mtiles128, int64_t nchunks) {
+  // Enough (row tile, ffn range) pairs to give each of the 256 CUs one workgroup, never more
+  // ranges than there are ffn chunks.
+  int64_t s = (256 + mtiles128 - 1) / mtiles128;
+  if (s > nchunks) s = nchunks;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+static bool pow2_upto16(int64_t x) { return x == 2 || x == 4 || x == 8 || x == 16; }
+
+int make_plan(const svdmlp_desc* de, Plan* p) {
+  if (!de || !p) return SVDMLP_INVALID_ARGUMENT;
+  std::memset(p, 0, sizeof(*p));
+  if (de->kind != SVDMLP_GATED && de->kind != SVDMLP_LINEAR) return SVDMLP_INVALID_ARGUMENT;
+  if (de->dtype != SVDMLP_BF16 && de->dtype != SVDMLP_F32) return SVDMLP_INVALID_ARGUMENT;
+  const bool gated = de->kind == SVDMLP_GATED;
+  if (de->max_M <= 0 || de->d <= 0 || de->ffn <= 0 || de->r <= 0) return SVDMLP_INVALID_ARGUMENT;
+  if (gated && de->r_down <= 0) return SVDMLP_INVALID_ARGUMENT;
+  const int64_t lim = de->d < de->ffn ? de->d : de->ffn;
+  if (de->r > lim || (gated && de->r_down > lim)) return SVDMLP_INVALID_ARGUMENT;
+  if (de->max_M > (int64_t(1) << 24) || de->d > (int64_t(1) << 20) || de->ffn > (int64_t(1) << 20))
+    return SVDMLP_UNSUPPORTED;
+  if ((de->flags & SVDMLP_FLAG_FORCE_TILED) && (de->flags & SVDMLP_FLAG_FORCE_STREAM)) return SVDMLP_INVALID_ARGUMENT;
+
+  p->max_M = de->max_M; p->d = de->d; p->ffn = de->ffn; p->r = de->r;
+  p->rd = gated ? de->r_down : 0;
+  p->kind = de->kind; p->dtype = de->dtype; p->flags = de->flags;
+
+  if (de->dtype == SVDMLP_F32) {
+    // fp32 intermediates: T [M, 2r] (LINEAR: [M, r]), H [M, ffn], Td [M, rd]
+    size_t off = 0;
+    p->f32_T = off;  off += (size_t)de->max_M * (gated ? 2 : 1) * de->r;
+    if (gated) {
+      p->f32_H = off;  off += (size_t)de->max_M * de->ffn;
+      p->f32_Td = off; off += (size_t)de->max_M * p->rd;
+    }
+    p->total_bytes = align_up(off * sizeof(float), 256);
+    return SVDMLP_OK;
+  }
+
+  // ---- bf16 ----
+  if (!gated) return SVDMLP_UNSUPPORTED;  // the single factored linear layer is offered on the fp32 path only
+  const int64_t d = de->d, ffn = de->ffn, r = de->r, rd = p->rd;
+  if (d % 128 || ffn % 128 || r % 64) return SVDMLP_UNSUPPORTED;
+  const int64_t nq = rd / 32;
+  if (rd % 64 || !(pow2_upto16(nq) || rd % 512 == 0)) return SVDMLP_UNSUPPORTED;
+
+  p->Mpad = (de->max_M + 127) / 128 * 128;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  p->off_wU = take((size_t)2 * r * d * 2);
+  p->off_wVg = take((size_t)ffn * r * 2);
+  p->off_wVu = take((size_t)ffn * r * 2);
+  p->off_wUd = take((size_t)rd * ffn * 2);
+  p->off_wVd = take((size_t)d * rd * 2);
+  p->off_T = take((size_t)p->Mpad * 2 * r * 2);
+  // split-K partial sums of Td: rows = splits(M) * padded M, maximised over M <= max_M
+  int64_t rows = 0;
+  const int64_t nchunks = ffn / 64;
+  for (int64_t mt = 1; mt <= p->Mpad / 128; ++mt) {
+    int64_t rws = (int64_t)tiled_splits(mt, nchunks) * mt * 128;
+    if (rws > rows) rows = rws;
+  }
+  p->part_rows = rows;
+  p->off_Tdp = take((size_t)rows * rd * 4);
+  p->off_Td = take((size_t)p->Mpad * rd * 2);
+  p->off_H = take((size_t)32 * ffn * 2);            // streaming path: the ffn-wide activation of <= 32 rows
+  p->off_part = take((size_t)8 << 20);              // streaming path: split-K partial tiles
+  p->off_cnt = take(16384);                          // streaming path: arrival counters (zero between calls)
+  p->total_bytes = off;
+  return SVDMLP_OK;
+}
+
+static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+}  // namespace svdmlp
+
+using namespace svdmlp;
+
+extern "C" {
+
+int svdmlp_abi_version(void) { return 1; }
+
+const char* svdmlp_status_string(int status) {
+  switch (status) {
+    case SVDMLP_OK: return "ok";
+    case SVDMLP_INVALID_ARGUMENT: return "invalid argument";
+    case SVDMLP_UNSUPPORTED: return "unsupported dtype / kind / extents";
+    case SVDMLP_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case SVDMLP_HIP_ERROR: return "HIP runtime error";
+    case SVDMLP_NO_DEVICE: return "no gfx950 device";
+    default: return "unknown status";
+  }
+}
+
+size_t svdmlp_workspace_bytes(const svdmlp_desc* desc) {
+  Plan p;
+  if (make_plan(desc, &p) != SVDMLP_OK) return 0;
+  return p.total_bytes;
+}
+
+int svdmlp_create(const svdmlp_desc* desc, svdmlp_ctx** out) {
+  if (!desc || !out) return SVDMLP_INVALID_ARGUMENT;
+  Plan p;
+  int st = make_plan(desc, &p);
+  if (st != SVDMLP_OK) return st;
+  const bool gated = desc->kind == SVDMLP_GATED;
+  if (!desc->Ug || !desc->Vg) return SVDMLP_INVALID_ARGUMENT;
+  if (gated && (!desc->Uu || !desc->Vu || !desc->Ud || !desc->Vd)) return SVDMLP_INVALID_ARGUMENT;
+  const void* ptrs[6] = {desc->Ug, desc->Vg, desc->Uu, desc->Vu, desc->Ud, desc->Vd};
+  for (int i = 0; i < (gated ? 6 : 2); ++i)
+    if (!aligned16(ptrs[i])) return SVDMLP_INVALID_ARGUMENT;
+  if (p.total_bytes > 0) {
+    if (!desc->workspace) return SVDMLP_INVALID_ARGUMENT;
+    if (reinterpret_cast<uintptr_t>(desc->workspace) & 255u) return SVDMLP_INVALID_ARGUMENT;
+    if (desc->workspace_bytes < p.total_bytes) return SVDMLP_WORKSPACE_TOO_SMALL;
+  }
+  if (!(desc->flags & SVDMLP_FLAG_SKIP_ARCH_CHECK)) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return SVDMLP_NO_DEVICE; }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return SVDMLP_NO_DEVICE; }
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return SVDMLP_NO_DEVICE;
+  }
+  Ctx* c = new (std::nothrow) Ctx;
+  if (!c) return SVDMLP_INVALID_ARGUMENT;
+  c->desc = *desc;
+  c->plan = p;
+  c->ws = static_cast<char*>(desc->workspace);
+  c->last_hip_error = 0;
+  c->last_path = 0;
+  if (desc->dtype == SVDMLP_BF16 && !(desc->flags & SVDMLP_FLAG_SKIP_ARCH_CHECK)) {
+    // One-time re-tiling of the invariant factors into matrix-core fragments.
+    int e = (int)hipDeviceSynchronize();
+    if (e == 0) e = bf16_repack_all(c, nullptr);
+    if (e == 0) e = (int)hipStreamSynchronize(nullptr);
+    if (e != 0) { (void)hipGetLastError(); delete c; return SVDMLP_HIP_ERROR; }
+  }
+  *out = reinterpret_cast<svdmlp_ctx*>(c);
+  return SVDMLP_OK;
+}
+
+int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip_stream) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c || M < 0) return SVDMLP_INVALID_ARGUMENT;
+  if (M == 0) return SVDMLP_OK;
+  if (!X || !Y || X == Y || M > c->plan.max_M) return SVDMLP_INVALID_ARGUMENT;
+  if (!aligned16(X) || !aligned16(Y)) return SVDMLP_INVALID_ARGUMENT;
+  if (c->desc.flags & SVDMLP_FLAG_SKIP_ARCH_CHECK) return SVDMLP_NO_DEVICE;  // host-only context: nothing to run on
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int e;
+  if (c->plan.dtype == SVDMLP_F32) {
+    c->last_path = 1;
+    e = f32_forward(c, X, M, Y, st);
+  } else {
+    bool stream_path = M <= 32;
+    if (c->plan.flags & SVDMLP_FLAG_FORCE_TILED) stream_path = false;
+    if (c->plan.flags & SVDMLP_FLAG_FORCE_STREAM) {
+      if (M > 32) return SVDMLP_UNSUPPORTED;
+      stream_path = true;
+    }
+    c->last_path = stream_path ? 3 : 2;
+    e = stream_path ? bf16_stream_forward(c, X, M, Y, st) : bf16_tiled_forward(c, X, M, Y, st);
+  }
+  if (e != 0) {
+    c->last_hip_error = e;
+    (void)hipGetLastError();
+    return SVDMLP_HIP_ERROR;
+  }
+  return SVDMLP_OK;
+}
+
+int svdmlp_destroy(svdmlp_ctx* ctx) {
+  delete reinterpret_cast<Ctx*>(ctx);
+  return SVDMLP_OK;
+}
+
+int svdmlp_last_hip_error(const svdmlp_ctx* ctx) { return ctx ? reinterpret_cast<const Ctx*>(ctx)->last_hip_error : 0; }
+int svdmlp_last_path(const svdmlp_ctx* ctx) { return ctx ? reinterpret_cast<const Ctx*>(ctx)->last_path : 0; }
+
+}  // extern "C"

@@ -1,0 +1,119 @@
+// Shared declarations of the svdmlp HIP library (gfx950 only).
+//
+// Fragment layout ("frag") used for every matrix-core operand that lives in HBM
+// ----------------------------------------------------------------------------
+// v_mfma_f32_32x32x16_bf16 takes, per lane, eight bf16 of one operand row:
+// lane l supplies row (l % 32) and the eight contraction indices of half h = l / 32.
+// A frag is the 1 KiB image of one such operand (32 rows x 16 contraction indices)
+// exactly as the 64 lanes hold it: lane-major, 16 bytes per lane.  A wave loads a
+// frag with one perfectly coalesced 16-byte-per-lane access and LDS copies of it are
+// read back conflict-free with ds_read_b128 at lane * 16.
+//
+// Which eight contraction indices (out of the 16 of a frag) a lane holds:
+//   natural order: k = 8 h + s            (s = slot 0..7)   -- data that comes from row-major memory
+//   chain order  : k = 8 (s / 4) + 4 h + s % 4               -- data that comes out of a previous MFMA
+// The chain order is what a lane of the 32x32 accumulator tile already owns when the
+// product was computed transposed (lane = activation row m, registers = output index):
+// registers 8t .. 8t+7 of the accumulator, rounded to bf16, ARE the frag for contraction
+// block t of the next product.  This is the matrix-core form of the paper's "implicit
+// transposition" (Sec. 4.2.1): the intermediate is born in the layout its consumer needs.
+// Both operands of an MFMA use the same order, so any order is valid as long as the
+// weight frags were built with the order of the activation they meet.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/svdmlp.h"
+
+namespace svdmlp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+constexpr int FRAG_ELEMS = 512;  // 32 rows x 16 k, bf16
+constexpr int FRAG_BYTES = 1024;
+constexpr int UNIT_BYTES = 16384;  // one LDS ring slot: 16 frags, filled by 4 waves x 4 loads x 64 lanes x 16 B
+
+enum FragOrder { ORDER_NATURAL = 0, ORDER_CHAIN = 1 };
+enum TileOrder { TILE_MAJOR = 0 /* [tile][kb] */, KB_MAJOR = 1 /* [kb][tile] */ };
+
+// ---- device helpers -----------------------------------------------------------------------
+#ifdef __HIPCC__
+// 16-byte asynchronous copy global -> LDS: lane l's 16 bytes land at lds_wave_base + 16 l.
+// (Measured on gfx950: placement is lane-linear; the instruction's immediate offset is not used.)
+__device__ __forceinline__ void dma16(const void* gsrc_lane, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc_lane,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt left at their maxima).  gfx9 encoding:
+// vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14, expcnt bits 6:4, lgkmcnt bits 11:8.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | ((N >> 4) << 14));
+}
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Registers 8t..8t+7 of a 32x32 accumulator tile, rounded RNE to bf16: a chain-order frag.
+__device__ __forceinline__ bf16x8 pack_chain(const f32x16& c, int t) {
+  bf16x8 r;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) r[s] = (__bf16)c[8 * t + s];
+  return r;
+}
+
+__device__ __forceinline__ float silu_f32(float x) { return x / (1.0f + __expf(-x)); }
+
+// XCD-aware block numbering: consecutive hardware block ids go round-robin over the 8 XCDs,
+// so logical id = (hw % 8) * (n / 8) + hw / 8 puts a contiguous range of logical ids on one XCD
+// (and its private L2).  Requires n % 8 == 0; otherwise the identity is used.
+__device__ __forceinline__ int xcd_contiguous_id(int hw, int n) {
+  return (n % 8 == 0) ? (hw % 8) * (n / 8) + hw / 8 : hw;
+}
+#endif
+
+// ---- host-side plan -------------------------------------------------------------------------
+struct Plan {
+  // extents
+  int64_t max_M, d, ffn, r, rd;
+  int kind, dtype;
+  uint32_t flags;
+  // bf16: byte offsets into the workspace (all 256-byte aligned)
+  size_t off_wU, off_wVg, off_wVu, off_wUd, off_wVd;  // re-tiled factors
+  size_t off_T, off_Tdp, off_Td, off_H, off_part, off_cnt;
+  size_t total_bytes;
+  int64_t Mpad;       // max_M rounded up to 128
+  int64_t part_rows;  // rows reserved for split-K partial sums of Td
+  // f32: element offsets
+  size_t f32_T, f32_H, f32_Td;
+};
+
+int make_plan(const svdmlp_desc* desc, Plan* plan);  // returns a status code
+
+// number of ffn splits the tiled path uses for a given number of 128-row tiles
+int tiled_splits(int64_t mtiles128, int64_t nchunks);
+
+// ---- launchers (each returns hipError_t as int; 0 = success) ---------------------------------
+struct Ctx;
+int f32_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
+int bf16_repack_all(const Ctx* c, hipStream_t st);
+int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
+int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
+
+struct Ctx {
+  svdmlp_desc desc;
+  Plan plan;
+  char* ws;
+  int last_hip_error;
+  int last_path;
+};
+
+}  // namespace svdmlp

@@ -1,0 +1,209 @@
+// bf16 weight-streaming (decode) path: M <= 32 rows, weight-bandwidth bound.
+//
+// Each of the four products of the factored MLP (paper Alg. 2) is one launch of k_stream:
+//   D1  T^T  = [Ug|Uu]^T X^T          split-K over d
+//   D2  H^T  = SiLU(Vg^T Tg^T) .* (Vu^T Tu^T)
+//   D4  Td^T = Ud^T H^T               split-K over ffn
+//   D5  Y^T  = Vd^T Td^T
+// Every weight frag (common.h) is read exactly once, straight from HBM into registers with one
+// coalesced 16-byte-per-lane load, and multiplied against the (tiny, L2-resident) activation frag on
+// the matrix cores with the activation rows padded to one 32-row tile.  The contraction range of a
+// workgroup is split over its 8 waves; their partial tiles are summed through LDS, and, when the
+// contraction is also split over workgroups, through a partial buffer in which the last workgroup to
+// arrive (an atomic ticket, no spinning) adds the partials in a fixed order, so results are
+// bit-reproducible.  Products are computed transposed (lane = activation row), so each output tile is
+// already the chain-order frag the next product consumes.
+#include "common.h"
+
+namespace svdmlp {
+
+enum { PH_D1 = 0, PH_D2 = 1, PH_D4 = 2, PH_D5 = 3 };
+constexpr int SW = 8;  // waves per workgroup
+
+struct StreamArgs {
+  const char* W0;       // weight frags (D2: gate)
+  const char* W1;       // D2: up frags
+  const void* act;      // D1: X row-major bf16; otherwise activation frags [kb] (D2: Tg at 0, Tu at KB frags)
+  void* out;            // D1: T frags; D2: H frags; D4: Td frags; D5: Y row-major
+  float* part;          // split-K partial tiles [tile][split][16][64]
+  int* cnt;             // arrival counters [tile]
+  int M, KB, tiles, S;  // contraction blocks, output tiles, workgroup-level splits
+  int ldx;              // D1: row length of X (= d); D5: row length of Y (= d)
+  int r;                // D1: rank (separates gate tiles from up tiles)
+  int kb_major;         // weight frag order (1 for Ud)
+};
+
+template <int PH>
+__global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
+  constexpr int NACC = (PH == PH_D2) ? 2 : 1;
+  __shared__ float red[NACC][SW][16][64];
+  __shared__ int s_last;
+  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+  const int tile = blockIdx.x / a.S, sp = blockIdx.x % a.S;
+  const int kbs = (a.KB + a.S - 1) / a.S;                 // contraction blocks of this workgroup
+  const int kw = (kbs + SW - 1) / SW;                     // ... of each wave
+  int k0 = sp * kbs + w * kw;
+  int k1 = k0 + kw;
+  const int kend = (sp + 1) * kbs < a.KB ? (sp + 1) * kbs : a.KB;
+  if (k1 > kend) k1 = kend;
+
+  const int il = lane % 32, h = lane / 32;
+  f32x16 acc[NACC];
+#pragma unroll
+  for (int n = 0; n < NACC; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+
+  const size_t wstride = a.kb_major ? (size_t)a.tiles * FRAG_BYTES : (size_t)FRAG_BYTES;
+  const char* wp0 = a.W0 + (a.kb_major ? (size_t)tile : (size_t)tile * a.KB) * FRAG_BYTES + lane * 16;
+  const char* wp1 = (PH == PH_D2) ? a.W1 + (size_t)tile * a.KB * FRAG_BYTES + lane * 16 : nullptr;
+  const uint16_t* xrow = nullptr;
+  if (PH == PH_D1) xrow = static_cast<const uint16_t*>(a.act) + (size_t)(il < a.M ? il : a.M - 1) * a.ldx + 8 * h;
+  const char* af = static_cast<const char*>(a.act) + lane * 16;
+
+#pragma unroll 4
+  for (int kb = k0; kb < k1; ++kb) {
+    bf16x8 wv = *reinterpret_cast<const bf16x8*>(wp0 + (size_t)kb * wstride);
+    bf16x8 av;
+    if (PH == PH_D1) av = *reinterpret_cast<const bf16x8*>(xrow + 16 * kb);
+    else av = *reinterpret_cast<const bf16x8*>(af + (size_t)kb * FRAG_BYTES);
+    acc[0] = mfma32(wv, av, acc[0]);
+    if (PH == PH_D2) {
+      bf16x8 wu = *reinterpret_cast<const bf16x8*>(wp1 + (size_t)kb * FRAG_BYTES);
+      bf16x8 au = *reinterpret_cast<const bf16x8*>(af + (size_t)(a.KB + kb) * FRAG_BYTES);
+      acc[NACC - 1] = mfma32(wu, au, acc[NACC - 1]);
+    }
+  }
+
+  // ---- sum the 8 waves' partial tiles through LDS (fixed order) ----
+#pragma unroll
+  for (int n = 0; n < NACC; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) red[n][w][e][lane] = acc[n][e];
+  __syncthreads();
+  // thread (t, lane), t = 0,1: registers 8t..8t+7 of the tile = one chain-order frag
+  const int t = threadIdx.x / 64;  // only t < 2 take part from here on
+  float v[NACC][8];
+  if (t < 2) {
+#pragma unroll
+    for (int n = 0; n < NACC; ++n)
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        float x = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < SW; ++ww) x += red[n][ww][8 * t + s][lane];
+        v[n][s] = x;
+      }
+  }
+  if (a.S > 1) {
+    float* mine = a.part + (((size_t)tile * a.S + sp) * NACC) * 1024;
+    if (t < 2) {
+#pragma unroll
+      for (int n = 0; n < NACC; ++n)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) mine[n * 1024 + (8 * t + s) * 64 + lane] = v[n][s];
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = (atomicAdd(&a.cnt[tile], 1) == a.S - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    if (t < 2) {
+#pragma unroll
+      for (int n = 0; n < NACC; ++n)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          float x = 0.f;
+          for (int q = 0; q < a.S; ++q)
+            x += a.part[(((size_t)tile * a.S + q) * NACC + n) * 1024 + (8 * t + s) * 64 + lane];
+          v[n][s] = x;
+        }
+    }
+    if (threadIdx.x == 0) a.cnt[tile] = 0;  // ready for the next forward
+  }
+  if (t >= 2) return;
+
+  // ---- epilogue ----
+  if (PH == PH_D5) {
+    // lane = row m; slots s <-> columns 32 tile + 16 t + 8 (s / 4) + 4 h + s % 4
+    if (il < a.M) {
+      uint16_t* y = static_cast<uint16_t*>(a.out) + (size_t)il * a.ldx + 32 * tile + 16 * t + 4 * h;
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        bf16x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = (__bf16)v[0][4 * g + i];
+        *reinterpret_cast<bf16x4*>(y + 8 * g) = o;
+      }
+    }
+    return;
+  }
+  bf16x8 o;
+  if (PH == PH_D2) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const float g = v[0][s];
+      o[s] = (__bf16)(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * v[1][s]);
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < 8; ++s) o[s] = (__bf16)v[0][s];
+  }
+  size_t frag;
+  if (PH == PH_D1) {
+    const int p0 = 32 * tile;
+    const int which = p0 >= a.r ? 1 : 0;
+    frag = (size_t)which * (a.r / 16) + (p0 - which * a.r) / 16 + t;
+  } else {
+    frag = (size_t)2 * tile + t;
+  }
+  *reinterpret_cast<bf16x8*>(static_cast<char*>(a.out) + (frag * 64 + lane) * 16) = o;
+}
+
+static int pick_splits(int tiles, int KB) {
+  int s = (256 + tiles - 1) / tiles;      // aim at one workgroup per CU
+  int smax = KB / SW;                     // at least one contraction block per wave
+  if (s > smax) s = smax;
+  if (s > 64) s = 64;
+  return s < 1 ? 1 : s;
+}
+
+int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
+  const Plan& p = c->plan;
+  char* ws = c->ws;
+  int* cnt = reinterpret_cast<int*>(ws + p.off_cnt);
+  float* part = reinterpret_cast<float*>(ws + p.off_part);
+  const size_t part_floats = ((size_t)8 << 20) / 4;
+  int e;
+
+  StreamArgs a;
+  // D1
+  a = StreamArgs{ws + p.off_wU, nullptr, X, ws + p.off_T, part, cnt, (int)M, (int)(p.d / 16), (int)(2 * p.r / 32), 1,
+                 (int)p.d, (int)p.r, 0};
+  a.S = pick_splits(a.tiles, a.KB);
+  while (a.S > 1 && (size_t)a.tiles * a.S * 1024 > part_floats) --a.S;
+  if (a.tiles > 2048) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_stream<PH_D1>, dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+  if ((e = (int)hipGetLastError())) return e;
+  // D2 (never split over workgroups: its contraction is only r long)
+  a = StreamArgs{ws + p.off_wVg, ws + p.off_wVu, ws + p.off_T, ws + p.off_H, part, cnt, (int)M, (int)(p.r / 16),
+                 (int)(p.ffn / 32), 1, 0, (int)p.r, 0};
+  hipLaunchKernelGGL(k_stream<PH_D2>, dim3(a.tiles), dim3(SW * 64), 0, st, a);
+  if ((e = (int)hipGetLastError())) return e;
+  // D4
+  a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048, (int)M, (int)(p.ffn / 16),
+                 (int)(p.rd / 32), 1, 0, (int)p.r, 1};
+  a.S = pick_splits(a.tiles, a.KB);
+  while (a.S > 1 && (size_t)a.tiles * a.S * 1024 > part_floats) --a.S;
+  if (a.tiles > 2048) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_stream<PH_D4>, dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+  if ((e = (int)hipGetLastError())) return e;
+  // D5
+  a = StreamArgs{ws + p.off_wVd, nullptr, ws + p.off_Td, Y, part, cnt, (int)M, (int)(p.rd / 16), (int)(p.d / 32), 1,
+                 (int)p.d, (int)p.r, 0};
+  hipLaunchKernelGGL(k_stream<PH_D5>, dim3(a.tiles), dim3(SW * 64), 0, st, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace svdmlp

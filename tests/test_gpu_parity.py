@@ -1,0 +1,194 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle on the same seeded inputs.
+
+Error metric (the one the target is stated in): max|Y_gpu - Y_ref| / max|Y_ref| over the whole output.
+Bars: bf16 path <= 2e-2, fp32 debug path <= 1e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_25977_amd import binding as B
+from paper_2510_25977_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = 2e-2
+F32_TOL = 1e-5
+
+
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+def relmax(y, ref):
+    return float(np.max(np.abs(y - ref)) / np.max(np.abs(ref)))
+
+
+def relfro(y, ref):
+    return float(np.linalg.norm(y - ref) / np.linalg.norm(ref))
+
+
+def run_gated(gi, flags=0, max_M=None, rows=None):
+    """Forward on the GPU; oracle on `rows` (default all).  Returns (Y_gpu rows, Y_ref rows, path)."""
+    d = dev()
+    f = {k: v.to(d) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=max_M or gi.X.shape[0], flags=flags, **f)
+    Y = mlp(gi.X.to(d))
+    torch.cuda.synchronize()
+    path = mlp.last_path
+    Yh = Y.cpu().to(torch.float64).numpy()
+    mlp.close()
+    a = {k: synth.to_f64(v) for k, v in gi.factors().items()}
+    X = synth.to_f64(gi.X)
+    if rows is not None:
+        X, Yh = X[rows], Yh[rows]
+    ref = oracle.gated(X, **a)
+    return Yh, ref, path
+
+
+# ---------------------------------------------------------------------------------- fp32 debug path
+@pytest.mark.parametrize("r", [16, 256])
+def test_f32_linear_powerlaw(r):
+    """Single factored linear layer, fp32, M=32, d=256, n=1024, W = Q1 diag(i^-0.7) Q2^T."""
+    li = synth.make_linear_powerlaw(r=r)
+    d = dev()
+    mlp = B.SvdMlp(max_M=32, Ug=li.U.to(d), Vg=li.V.to(d), kind=B.SVDMLP_LINEAR)
+    Y = mlp(li.X.to(d)).cpu().to(torch.float64).numpy()
+    assert mlp.last_path == 1
+    ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Y, ref) <= F32_TOL
+    if r == 256:
+        # full rank: the factored product is X W itself (up to the fp32 rounding of the stored factors)
+        assert relmax(Y, synth.to_f64(li.X) @ li.W) <= 1e-5
+
+
+@pytest.mark.parametrize("M,d,ffn,r,rd", [(37, 96, 200, 24, 40), (130, 256, 640, 64, 128), (1, 64, 64, 8, 8)])
+def test_f32_gated_ragged(M, d, ffn, r, rd):
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=11, dtype=torch.float32)
+    Y, ref, path = run_gated(gi)
+    assert path == 1
+    assert relmax(Y, ref) <= F32_TOL
+
+
+# ---------------------------------------------------------------------------------- bf16 tiled path
+@pytest.mark.parametrize("M,d,ffn,r,rd", [
+    (128, 128, 128, 64, 128),      # one tile of everything
+    (200, 256, 384, 64, 128),      # ragged M (two row tiles), several chunks
+    (333, 384, 1152, 192, 256),    # three row tiles, r not a power of two, NQ = 8
+    (40, 512, 512, 128, 512),      # small M forced onto the tiled path, NQ = 16
+    (129, 1024, 1024, 64, 1024),   # down rank split over two workgroups
+])
+def test_bf16_tiled_small(M, d, ffn, r, rd):
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=21)
+    Y, ref, path = run_gated(gi, flags=B.FLAG_FORCE_TILED)
+    assert path == 2
+    assert relmax(Y, ref) <= BF16_TOL, (relmax(Y, ref), relfro(Y, ref))
+    assert relfro(Y, ref) <= 1.5e-2
+
+
+# ---------------------------------------------------------------------------------- bf16 streaming path
+@pytest.mark.parametrize("M", [1, 4, 16, 32, 7])
+@pytest.mark.parametrize("d,ffn,r,rd", [(256, 512, 64, 128), (512, 1408, 128, 256)])
+def test_bf16_stream_small(M, d, ffn, r, rd):
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=31)
+    Y, ref, path = run_gated(gi, max_M=32)
+    assert path == 3
+    assert relmax(Y, ref) <= BF16_TOL, (relmax(Y, ref), relfro(Y, ref))
+    assert relfro(Y, ref) <= 1.5e-2
+
+
+def test_bf16_stream_and_tiled_agree_and_are_deterministic():
+    gi = synth.make_gated(16, 512, 1408, 128, 256, stream=32)
+    d = dev()
+    f = {k: v.to(d) for k, v in gi.factors().items()}
+    X = gi.X.to(d)
+    outs = {}
+    for name, flags in (("stream", B.FLAG_FORCE_STREAM), ("tiled", B.FLAG_FORCE_TILED)):
+        mlp = B.SvdMlp(max_M=16, flags=flags, **f)
+        y1 = mlp(X).clone()
+        y2 = mlp(X).clone()
+        y3 = mlp(X[:5]).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(y1, y2), name            # bitwise reproducible
+        assert torch.equal(y1[:5], y3), name        # rows do not depend on M
+        outs[name] = y1.cpu().to(torch.float64).numpy()
+        mlp.close()
+    assert relmax(outs["stream"], outs["tiled"]) <= BF16_TOL
+
+
+# ---------------------------------------------------------------------------------- full-size workloads
+def test_workload_mlp_small():
+    """d=2048 ffn=8192 r=256 M=128."""
+    gi = synth.make_workload("mlp_small")
+    Y, ref, path = run_gated(gi)
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_workload_decode(M):
+    """d=4096 ffn=14336 r=512, M in {1,4,16}."""
+    gi = synth.make_workload("decode", M=M)
+    Y, ref, path = run_gated(gi)
+    assert path == 3
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+
+
+SAMPLE_ROWS = [0, 1, 31, 32, 127, 128, 1000, 2047]
+
+
+@pytest.mark.parametrize("r", [256, 512, 1024])
+def test_workload_prefill_sampled_rows(r):
+    """d=4096 ffn=14336 M=4096, launch configuration of the benchmark; the oracle evaluates a sample of
+    rows (rows of X are independent, so this is exact for those rows)."""
+    gi = synth.make_workload("prefill", r=r)
+    rows = SAMPLE_ROWS + [4095, 3000]
+    Y, ref, path = run_gated(gi, rows=rows)
+    assert path == 2
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+
+
+def test_workload_wide_sampled_rows():
+    """d=5120 ffn=27648 r=1024 M=2048, power-law U columns, 1 % of X entries x20."""
+    gi = synth.make_workload("wide")
+    Y, ref, path = run_gated(gi, rows=SAMPLE_ROWS)
+    assert path == 2
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+
+
+# ---------------------------------------------------------------------------------- edge cases
+def test_empty_and_invalid_calls():
+    gi = synth.make_gated(8, 128, 128, 64, 128, stream=41)
+    d = dev()
+    f = {k: v.to(d) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=8, **f)
+    X = gi.X.to(d)
+    Y = torch.full((8, 128), 7.0, dtype=torch.bfloat16, device=d)
+    B.svdmlp_forward(mlp.ctx, X.data_ptr(), 0, Y.data_ptr())          # M = 0: nothing happens
+    torch.cuda.synchronize()
+    assert torch.all(Y == 7.0)
+    with pytest.raises(B.SvdMlpError) as ei:
+        B.svdmlp_forward(mlp.ctx, X.data_ptr(), 9, Y.data_ptr())      # M > max_M
+    assert ei.value.status == B.SVDMLP_INVALID_ARGUMENT
+    with pytest.raises(B.SvdMlpError):
+        B.svdmlp_forward(mlp.ctx, X.data_ptr(), 8, X.data_ptr())      # aliasing
+    with pytest.raises(B.SvdMlpError):
+        B.svdmlp_forward(mlp.ctx, X.data_ptr() + 2, 4, Y.data_ptr())  # misaligned
+    # only the first M rows of Y are written
+    B.svdmlp_forward(mlp.ctx, X.data_ptr(), 3, Y.data_ptr())
+    torch.cuda.synchronize()
+    assert torch.all(Y[3:] == 7.0) and not torch.all(Y[:3] == 7.0)
+    mlp.close()
+
+
+def test_zero_input_gives_zero_output():
+    gi = synth.make_gated(64, 128, 256, 64, 128, stream=42)
+    d = dev()
+    f = {k: v.to(d) for k, v in gi.factors().items()}
+    for flags, M in ((B.FLAG_FORCE_TILED, 64), (0, 16)):
+        mlp = B.SvdMlp(max_M=64, flags=flags, **f)
+        Y = mlp(torch.zeros((M, 128), dtype=torch.bfloat16, device=d))
+        torch.cuda.synchronize()
+        assert torch.all(Y == 0)
+        mlp.close()
