@@ -113,6 +113,18 @@ int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
  * 2 bf16 MFMA-tiled (prefill), 3 bf16 weight-streaming (decode). */
 int svdmlp_last_path(const svdmlp_ctx *ctx);
 
+/* Per-kernel timing for benchmarks.  svdmlp_profile_begin creates a pool of HIP events for up to
+ * max_forwards forwards (host allocation; not to be called under graph capture); while the profile is
+ * open every svdmlp_forward on this context records an event before and after each of its kernels on
+ * the stream it launches on (forwards beyond max_forwards are not recorded).  svdmlp_profile_end waits
+ * for the recorded events, writes the average duration in milliseconds of each kernel position into
+ * avg_ms[0 .. *n_kernels) (capacity 8) and the number of forwards averaged into *n_forwards, then
+ * releases the pool.  svdmlp_profile_kernel_name returns the name of kernel position k of the last
+ * recorded forward (NULL if out of range); valid until the context is destroyed. */
+int svdmlp_profile_begin(svdmlp_ctx *ctx, int max_forwards);
+int svdmlp_profile_end(svdmlp_ctx *ctx, float *avg_ms, int *n_kernels, int *n_forwards);
+const char *svdmlp_profile_kernel_name(const svdmlp_ctx *ctx, int k);
+
 /* ABI version of this header (bumped on any incompatible change). */
 int svdmlp_abi_version(void);
 

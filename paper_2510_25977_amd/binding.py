@@ -12,8 +12,11 @@ from typing import Optional
 
 import torch
 
+import os
+
 HERE = Path(__file__).resolve().parent
-LIB_PATH = HERE / "libsvdmlp.so"
+# SVDMLP_LIB lets a developer point the binding at an experimental build of the same ABI.
+LIB_PATH = Path(os.environ["SVDMLP_LIB"]) if os.environ.get("SVDMLP_LIB") else HERE / "libsvdmlp.so"
 
 SVDMLP_BF16, SVDMLP_F32 = 0, 1
 SVDMLP_GATED, SVDMLP_LINEAR = 0, 1
@@ -22,7 +25,8 @@ SVDMLP_INVALID_ARGUMENT, SVDMLP_UNSUPPORTED, SVDMLP_WORKSPACE_TOO_SMALL, SVDMLP_
 FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK = 1, 2, 4
 
 EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_status_string",
-           "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version"]
+           "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
+           "svdmlp_profile_end", "svdmlp_profile_kernel_name"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -68,6 +72,13 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_last_path.argtypes = [ctypes.c_void_p]
         L.svdmlp_last_path.restype = ctypes.c_int
         L.svdmlp_abi_version.restype = ctypes.c_int
+        L.svdmlp_profile_begin.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        L.svdmlp_profile_begin.restype = ctypes.c_int
+        L.svdmlp_profile_end.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int),
+                                         ctypes.POINTER(ctypes.c_int)]
+        L.svdmlp_profile_end.restype = ctypes.c_int
+        L.svdmlp_profile_kernel_name.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        L.svdmlp_profile_kernel_name.restype = ctypes.c_char_p
         _lib = L
     return _lib
 
@@ -98,6 +109,23 @@ def svdmlp_destroy(ctx) -> None:
     lib().svdmlp_destroy(ctx)
 
 
+def svdmlp_profile_begin(ctx, max_forwards: int) -> None:
+    st = lib().svdmlp_profile_begin(ctx, int(max_forwards))
+    if st != SVDMLP_OK:
+        raise SvdMlpError(st, "svdmlp_profile_begin")
+
+
+def svdmlp_profile_end(ctx):
+    """Returns ({kernel name: average ms}, number of forwards averaged)."""
+    ms = (ctypes.c_float * 8)()
+    nk, nf = ctypes.c_int(), ctypes.c_int()
+    st = lib().svdmlp_profile_end(ctx, ms, ctypes.byref(nk), ctypes.byref(nf))
+    if st != SVDMLP_OK:
+        raise SvdMlpError(st, "svdmlp_profile_end")
+    names = [lib().svdmlp_profile_kernel_name(ctx, k).decode() for k in range(nk.value)]
+    return {n: float(ms[k]) for k, n in enumerate(names)}, nf.value
+
+
 _TORCH_DTYPE = {torch.bfloat16: SVDMLP_BF16, torch.float32: SVDMLP_F32}
 
 
@@ -107,7 +135,7 @@ class SvdMlp:
 
     def __init__(self, *, max_M: int, Ug: torch.Tensor, Vg: torch.Tensor, Uu: Optional[torch.Tensor] = None,
                  Vu: Optional[torch.Tensor] = None, Ud: Optional[torch.Tensor] = None, Vd: Optional[torch.Tensor] = None,
-                 kind: int = SVDMLP_GATED, flags: int = 0):
+                 kind: int = SVDMLP_GATED, flags: int = 0, keep_factors: bool = True):
         self.kind = kind
         self.tensors = [t for t in (Ug, Vg, Uu, Vu, Ud, Vd) if t is not None]
         for t in self.tensors:
@@ -139,6 +167,8 @@ class SvdMlp:
         self.desc = de
         torch.cuda.synchronize(Ug.device)
         self.ctx = svdmlp_create(de)
+        if not keep_factors and self.dtype == torch.bfloat16:
+            self.tensors = []       # bf16 contexts do not read the factor buffers again after create
 
     def out_features(self) -> int:
         return self.d if self.kind == SVDMLP_GATED else self.ffn

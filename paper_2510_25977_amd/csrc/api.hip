@@ -184,9 +184,75 @@ int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip
   return SVDMLP_OK;
 }
 
+static void prof_release(Ctx* c) {
+  Prof& p = c->prof;
+  if (p.ev) {
+    for (int i = 0; i < p.cap * PROF_MAXK * 2; ++i) (void)hipEventDestroy(p.ev[i]);
+    delete[] p.ev;
+  }
+  p.ev = nullptr;
+  p.cap = p.nfwd = 0;
+}
+
 int svdmlp_destroy(svdmlp_ctx* ctx) {
-  delete reinterpret_cast<Ctx*>(ctx);
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (c) prof_release(c);
+  delete c;
   return SVDMLP_OK;
+}
+
+int svdmlp_profile_begin(svdmlp_ctx* ctx, int max_forwards) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c || max_forwards <= 0 || max_forwards > 4096) return SVDMLP_INVALID_ARGUMENT;
+  prof_release(c);
+  Prof& p = c->prof;
+  const int n = max_forwards * PROF_MAXK * 2;
+  p.ev = new (std::nothrow) hipEvent_t[n];
+  if (!p.ev) return SVDMLP_INVALID_ARGUMENT;
+  for (int i = 0; i < n; ++i) {
+    if (hipEventCreate(&p.ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(p.ev[j]);
+      delete[] p.ev;
+      p.ev = nullptr;
+      (void)hipGetLastError();
+      return SVDMLP_HIP_ERROR;
+    }
+  }
+  p.cap = max_forwards;
+  p.nfwd = 0;
+  p.nk = 0;
+  return SVDMLP_OK;
+}
+
+int svdmlp_profile_end(svdmlp_ctx* ctx, float* avg_ms, int* n_kernels, int* n_forwards) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c || !avg_ms || !n_kernels || !n_forwards) return SVDMLP_INVALID_ARGUMENT;
+  Prof& p = c->prof;
+  if (!p.ev) return SVDMLP_INVALID_ARGUMENT;
+  int st = SVDMLP_OK;
+  double sum[PROF_MAXK] = {};
+  for (int f = 0; f < p.nfwd && st == SVDMLP_OK; ++f)
+    for (int k = 0; k < p.nk; ++k) {
+      hipEvent_t e0 = p.ev[(f * PROF_MAXK + k) * 2], e1 = p.ev[(f * PROF_MAXK + k) * 2 + 1];
+      float ms = 0.f;
+      if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+        (void)hipGetLastError();
+        st = SVDMLP_HIP_ERROR;
+        break;
+      }
+      sum[k] += ms;
+    }
+  *n_kernels = p.nk;
+  *n_forwards = p.nfwd;
+  for (int k = 0; k < p.nk; ++k) avg_ms[k] = p.nfwd ? (float)(sum[k] / p.nfwd) : 0.f;
+  prof_release(c);
+  return st;
+}
+
+const char* svdmlp_profile_kernel_name(const svdmlp_ctx* ctx, int k) {
+  const Ctx* c = reinterpret_cast<const Ctx*>(ctx);
+  if (!c || k < 0 || k >= c->prof.nk) return nullptr;
+  return c->prof.names[k];
 }
 
 int svdmlp_last_hip_error(const svdmlp_ctx* ctx) { return ctx ? reinterpret_cast<const Ctx*>(ctx)->last_hip_error : 0; }

@@ -58,6 +58,18 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | ((N >> 4) << 14));
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also drain every outstanding
+// global load (s_waitcnt vmcnt(0)), which would serialise the asynchronous global->LDS copies the ring
+// keeps in flight; the copies a step needs are waited for explicitly with wait_vmcnt before this barrier.
+// (A workgroup fence, even one restricted to LDS, makes the compiler drain vmcnt because the copies
+// write LDS; so the barrier is bare, fenced for the compiler only.  Every wave has consumed its LDS
+// reads in MFMAs before it reaches the barrier, so no LDS access is in flight across it.)
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -108,12 +120,37 @@ int bf16_repack_all(const Ctx* c, hipStream_t st);
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 
+// Optional per-kernel timing: HIP events recorded on the caller's stream around every kernel launch of
+// a forward (only while a profile is open; see svdmlp_profile_begin in svdmlp.h).
+constexpr int PROF_MAXK = 8;
+struct Prof {
+  int cap = 0;                 // forwards the event pool can hold
+  int nfwd = 0;                // forwards recorded so far
+  int nk = 0;                  // kernels per forward (set by the path that runs)
+  hipEvent_t* ev = nullptr;    // [cap][PROF_MAXK][2]
+  const char* names[PROF_MAXK] = {};
+};
+
 struct Ctx {
   svdmlp_desc desc;
   Plan plan;
   char* ws;
   int last_hip_error;
   int last_path;
+  mutable Prof prof;
 };
+
+// Bracket one kernel launch with events when a profile is open.  `slot` is the forward's index in the
+// pool (or -1); k is the kernel's position in the forward.
+inline int prof_open_forward(const Ctx* c, int nk, const char* const* names) {
+  Prof& p = c->prof;
+  if (!p.ev || p.nfwd >= p.cap) return -1;
+  p.nk = nk;
+  for (int i = 0; i < nk; ++i) p.names[i] = names[i];
+  return p.nfwd++;
+}
+inline void prof_mark(const Ctx* c, int slot, int k, int end, hipStream_t st) {
+  if (slot >= 0) (void)hipEventRecord(c->prof.ev[(slot * PROF_MAXK + k) * 2 + end], st);
+}
 
 }  // namespace svdmlp

@@ -96,31 +96,51 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
       }
   }
   if (a.S > 1) {
+    // Partials cross workgroups (possibly on different XCDs, whose L2s are not coherent with each other) as
+    // device-scope relaxed atomics: such stores write through to memory and such loads bypass the local L2,
+    // so no cache write-back / invalidate (which a device-scope fence would cost every workgroup) is needed.
+    // Ordering: each thread waits for its own stores to be acknowledged, the workgroup barrier collects
+    // them, then one thread takes the ticket.
     float* mine = a.part + (((size_t)tile * a.S + sp) * NACC) * 1024;
     if (t < 2) {
 #pragma unroll
       for (int n = 0; n < NACC; ++n)
 #pragma unroll
-        for (int s = 0; s < 8; ++s) mine[n * 1024 + (8 * t + s) * 64 + lane] = v[n][s];
+        for (int s = 0; s < 8; ++s)
+          __hip_atomic_store(&mine[n * 1024 + (8 * t + s) * 64 + lane], v[n][s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __threadfence();
+    asm volatile("" ::: "memory");
+    wait_vmcnt<0>();
     __syncthreads();
-    if (threadIdx.x == 0) s_last = (atomicAdd(&a.cnt[tile], 1) == a.S - 1);
+    if (threadIdx.x == 0)
+      s_last = (__hip_atomic_fetch_add(&a.cnt[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.S - 1);
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
     if (t < 2) {
 #pragma unroll
-      for (int n = 0; n < NACC; ++n)
+      for (int n = 0; n < NACC; ++n) {
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          float x = 0.f;
-          for (int q = 0; q < a.S; ++q)
-            x += a.part[(((size_t)tile * a.S + q) * NACC + n) * 1024 + (8 * t + s) * 64 + lane];
-          v[n][s] = x;
+        for (int s = 0; s < 8; ++s) v[n][s] = 0.f;
+        // four partial tiles' worth of loads in flight at a time; the additions stay in split order
+        for (int q0 = 0; q0 < a.S; q0 += 4) {
+          float tmp[4][8];
+#pragma unroll
+          for (int qq = 0; qq < 4; ++qq) {
+            const int q = q0 + qq < a.S ? q0 + qq : a.S - 1;
+            const float* src = a.part + (((size_t)tile * a.S + q) * NACC + n) * 1024 + (8 * t) * 64 + lane;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) tmp[qq][s] = __hip_atomic_load(src + s * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+#pragma unroll
+          for (int qq = 0; qq < 4; ++qq)
+            if (q0 + qq < a.S) {
+#pragma unroll
+              for (int s = 0; s < 8; ++s) v[n][s] += tmp[qq][s];
+            }
         }
+      }
     }
-    if (threadIdx.x == 0) a.cnt[tile] = 0;  // ready for the next forward
+    if (threadIdx.x == 0) __hip_atomic_store(&a.cnt[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next forward
   }
   if (t >= 2) return;
 
@@ -176,6 +196,8 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   float* part = reinterpret_cast<float*>(ws + p.off_part);
   const size_t part_floats = ((size_t)8 << 20) / 4;
   int e;
+  static const char* const names[4] = {"k_stream_d1", "k_stream_d2", "k_stream_d4", "k_stream_d5"};
+  const int ps = prof_open_forward(c, 4, names);
 
   StreamArgs a;
   // D1
@@ -184,12 +206,16 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   a.S = pick_splits(a.tiles, a.KB);
   while (a.S > 1 && (size_t)a.tiles * a.S * 1024 > part_floats) --a.S;
   if (a.tiles > 2048) return (int)hipErrorInvalidValue;
+  prof_mark(c, ps, 0, 0, st);
   hipLaunchKernelGGL(k_stream<PH_D1>, dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+  prof_mark(c, ps, 0, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D2 (never split over workgroups: its contraction is only r long)
   a = StreamArgs{ws + p.off_wVg, ws + p.off_wVu, ws + p.off_T, ws + p.off_H, part, cnt, (int)M, (int)(p.r / 16),
                  (int)(p.ffn / 32), 1, 0, (int)p.r, 0};
+  prof_mark(c, ps, 1, 0, st);
   hipLaunchKernelGGL(k_stream<PH_D2>, dim3(a.tiles), dim3(SW * 64), 0, st, a);
+  prof_mark(c, ps, 1, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D4
   a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048, (int)M, (int)(p.ffn / 16),
@@ -197,12 +223,16 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   a.S = pick_splits(a.tiles, a.KB);
   while (a.S > 1 && (size_t)a.tiles * a.S * 1024 > part_floats) --a.S;
   if (a.tiles > 2048) return (int)hipErrorInvalidValue;
+  prof_mark(c, ps, 2, 0, st);
   hipLaunchKernelGGL(k_stream<PH_D4>, dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+  prof_mark(c, ps, 2, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D5
   a = StreamArgs{ws + p.off_wVd, nullptr, ws + p.off_Td, Y, part, cnt, (int)M, (int)(p.rd / 16), (int)(p.d / 32), 1,
                  (int)p.d, (int)p.r, 0};
+  prof_mark(c, ps, 3, 0, st);
   hipLaunchKernelGGL(k_stream<PH_D5>, dim3(a.tiles), dim3(SW * 64), 0, st, a);
+  prof_mark(c, ps, 3, 1, st);
   return (int)hipGetLastError();
 }
 

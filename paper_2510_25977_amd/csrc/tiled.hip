@@ -21,7 +21,7 @@ constexpr int LDS_BYTES = NU * UNIT_BYTES;
 
 // Ring protocol.  The unit stream is consumed in order; a step that consumes n units does
 //   wait_vmcnt<4*(PD-n)>  -> the n units are in LDS (each wave issues 4 loads per unit, in order)
-//   __syncthreads         -> every wave's part has landed, and every wave has left the previous step
+//   lds_barrier           -> every wave's part has landed, and every wave has left the previous step
 //   issue n more units    -> into the slots the previous step has just released
 //   compute
 // so exactly PD units beyond the current step stay in flight.  Issuing never stops (sources are clamped
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
     const int piece = (lane % 4) ^ ((lane >> 4) & 3);
     srcX[i] = X + (size_t)row * d + 32 * kh + 8 * piece;  // + ks * 64
   }
-  auto issue = [&](int u) {
+  auto issue = [&](int u) __attribute__((always_inline)) {
     int ks = u >> 1;
     ks = ks < nks ? ks : nks - 1;
     char* dst = lds + (u % NU) * UNIT_BYTES + (4 * w) * FRAG_BYTES;
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
   for (int u = 0; u < PD; ++u) issue(u);
   for (int ks = 0; ks < nks; ++ks) {
     wait_vmcnt<4 * (PD - 2)>();
-    __syncthreads();
+    lds_barrier();
     issue(2 * ks + PD);
     issue(2 * ks + PD + 1);
     const int sP = (2 * ks) % NU, sX = (2 * ks + 1) % NU;
@@ -138,6 +138,48 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
 //     H = SiLU(G) .* P  -> bf16 chain frags in registers
 //     B-steps: Td^T[q, m] += Ud^T frags (LDS, shared) x H frags (registers)
 // ------------------------------------------------------------------------------------------------
+// Producer side of the fused kernel's unit stream: per chunk, r/64 A-steps of (BN/64 V units, the Tg unit,
+// the Tu unit) followed by the chunk's Ud units.  All state is wave-uniform.
+template <int NQ, int BN>
+struct FusedProducer {
+  static constexpr int NV = BN / 64, NT = BN / 32, KBC = BN / 16, NB = KBC * NQ / 16;
+  const char *T, *wVg, *wVu, *wUd;
+  char* lds;
+  int KBr, NA, nq_total, qs, mtile, c_end, w;
+  size_t lane16;
+  int pc, pg, pk, pslot;
+  __device__ __forceinline__ void init(const char* T_, const char* wVg_, const char* wVu_, const char* wUd_, char* lds_,
+                                       int r, int nq_total_, int qs_, int mtile_, int c_begin, int c_end_, int w_, int lane) {
+    T = T_; wVg = wVg_; wVu = wVu_; wUd = wUd_; lds = lds_;
+    KBr = r / 16; NA = r / 64; nq_total = nq_total_; qs = qs_; mtile = mtile_; c_end = c_end_; w = w_;
+    lane16 = (size_t)lane * 16;
+    pc = c_begin; pg = 0; pk = 0; pslot = 0;
+  }
+  __device__ __forceinline__ void issue_next() {
+    const int c = pc < c_end ? pc : c_end - 1;  // past the end: keep re-reading the last chunk (never consumed)
+    const char* src;
+    if (pg < NA) {
+      if (pk < NV) {
+        const char* mat = (w < 2) ? wVg : wVu;
+        const int nt = c * NT + 2 * pk + (w & 1);
+        src = mat + ((size_t)nt * KBr + 4 * pg) * FRAG_BYTES;
+      } else {
+        src = T + ((size_t)(mtile * 2 + (pk - NV)) * KBr + 4 * pg) * FRAG_BYTES;
+      }
+      if (++pk == NV + 2) { pk = 0; ++pg; }
+    } else {
+      const int f = 16 * pk + 4 * w;
+      const int kbl = f / NQ, qtl = f % NQ;
+      src = wUd + ((size_t)(c * KBC + kbl) * nq_total + qs * NQ + qtl) * FRAG_BYTES;
+      if (++pk == NB) { pk = 0; pg = 0; ++pc; }
+    }
+    char* dst = lds + pslot * UNIT_BYTES + (4 * w) * FRAG_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dma16(src + i * FRAG_BYTES + lane16, dst + i * FRAG_BYTES);
+    pslot = (pslot + 1 == NU) ? 0 : pslot + 1;
+  }
+};
+
 template <int NQ, int BN>
 __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const char* __restrict__ wVg,
                                                const char* __restrict__ wVu, const char* __restrict__ wUd,
@@ -159,32 +201,8 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
   const int mtile = 4 * mt + w;
 
   // ---- producer cursor over the unit stream (wave-uniform) ----
-  int pc = c_begin, pg = 0, pk = 0;
-  int pslot = 0;
-  const size_t lane16 = (size_t)lane * 16;
-  auto issue_next = [&]() {
-    const int c = pc < c_end ? pc : c_end - 1;
-    const char* src;
-    if (pg < NA) {
-      if (pk < NV) {
-        const char* mat = (w < 2) ? wVg : wVu;
-        const int nt = c * NT + 2 * pk + (w & 1);
-        src = mat + ((size_t)nt * KBr + 4 * pg) * FRAG_BYTES;
-      } else {
-        src = T + ((size_t)(mtile * 2 + (pk - NV)) * KBr + 4 * pg) * FRAG_BYTES;
-      }
-      if (++pk == NV + 2) { pk = 0; ++pg; }
-    } else {
-      const int f = 16 * pk + 4 * w;
-      const int kbl = f / NQ, qtl = f % NQ;
-      src = wUd + ((size_t)(c * KBC + kbl) * nq_total + qs * NQ + qtl) * FRAG_BYTES;
-      if (++pk == NB) { pk = 0; pg = 0; ++pc; }
-    }
-    char* dst = lds + pslot * UNIT_BYTES + (4 * w) * FRAG_BYTES;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(src + i * FRAG_BYTES + lane16, dst + i * FRAG_BYTES);
-    pslot = (pslot + 1 == NU) ? 0 : pslot + 1;
-  };
+  FusedProducer<NQ, BN> prod;
+  prod.init(T, wVg, wVu, wUd, lds, r, nq_total, qs, mtile, c_begin, c_end, w, lane);
 
   f32x16 acc[NQ];
 #pragma unroll
@@ -193,9 +211,9 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
     for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
 
 #pragma unroll
-  for (int u = 0; u < PD; ++u) issue_next();
+  for (int u = 0; u < PD; ++u) prod.issue_next();
   int cslot = 0;  // ring slot of the next unit to consume
-  auto adv = [&](int sl, int n) { sl += n; return sl >= NU ? sl - NU : sl; };
+  auto adv = [&](int sl, int n) __attribute__((always_inline)) { sl += n; return sl >= NU ? sl - NU : sl; };
 
   for (int c = c_begin; c < c_end; ++c) {
     f32x16 G[NT], P[NT];
@@ -206,27 +224,42 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
 
     for (int g = 0; g < NA; ++g) {
       wait_vmcnt<4 * (PD - (NV + 2))>();
-      __syncthreads();
+      lds_barrier();
 #pragma unroll
-      for (int u = 0; u < NV + 2; ++u) issue_next();
+      for (int u = 0; u < NV + 2; ++u) prod.issue_next();
       const int sTg = adv(cslot, NV), sTu = adv(cslot, NV + 1);
+      // All LDS reads of the step are written before its MFMAs and the scheduler is then told to interleave
+      // them (one contraction block of reads ahead), so that ds_read latency hides under the matrix cores.
+      bf16x8 tg[4], tu[4], vf[NV][4][4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        bf16x8 tg = *lds_frag(lds, sTg, 4 * w + j, lane);
-        bf16x8 tu = *lds_frag(lds, sTu, 4 * w + j, lane);
+        tg[j] = *lds_frag(lds, sTg, 4 * w + j, lane);
+        tu[j] = *lds_frag(lds, sTu, 4 * w + j, lane);
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+          for (int k = 0; k < 4; ++k) vf[v][k][j] = *lds_frag(lds, adv(cslot, v), k * 4 + j, lane);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-          const int sV = adv(cslot, v);
-          bf16x8 vg0 = *lds_frag(lds, sV, 0 * 4 + j, lane);
-          bf16x8 vg1 = *lds_frag(lds, sV, 1 * 4 + j, lane);
-          bf16x8 vu0 = *lds_frag(lds, sV, 2 * 4 + j, lane);
-          bf16x8 vu1 = *lds_frag(lds, sV, 3 * 4 + j, lane);
-          G[2 * v] = mfma32(vg0, tg, G[2 * v]);
-          G[2 * v + 1] = mfma32(vg1, tg, G[2 * v + 1]);
-          P[2 * v] = mfma32(vu0, tu, P[2 * v]);
-          P[2 * v + 1] = mfma32(vu1, tu, P[2 * v + 1]);
+          G[2 * v] = mfma32(vf[v][0][j], tg[j], G[2 * v]);
+          G[2 * v + 1] = mfma32(vf[v][1][j], tg[j], G[2 * v + 1]);
+          P[2 * v] = mfma32(vf[v][2][j], tu[j], P[2 * v]);
+          P[2 * v + 1] = mfma32(vf[v][3][j], tu[j], P[2 * v + 1]);
         }
-      }
+      // schedule: reads of block 0; then per MFMA of blocks 0..2 one or two reads of the next block; block 3 bare
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 + 4 * NV, 0);
+#pragma unroll
+      for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int m = 0; m < 4 * NV; ++m) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (m < 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4 * NV, 0);
       cslot = adv(cslot, NV + 2);
     }
 
@@ -247,14 +280,23 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
 #pragma unroll
     for (int blk = 0; blk < NB; ++blk) {
       wait_vmcnt<4 * (PD - 1)>();
-      __syncthreads();
-      issue_next();
+      lds_barrier();
+      prod.issue_next();
+      bf16x8 uf[16];
+#pragma unroll
+      for (int f = 0; f < 16; ++f) uf[f] = *lds_frag(lds, cslot, f, lane);
 #pragma unroll
       for (int f = 0; f < 16; ++f) {
         const int kbl = (16 * blk + f) / NQ, qtl = (16 * blk + f) % NQ;
-        bf16x8 ud = *lds_frag(lds, cslot, f, lane);
-        acc[qtl] = mfma32(ud, Hf[kbl], acc[qtl]);
+        acc[qtl] = mfma32(uf[f], Hf[kbl], acc[qtl]);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int f = 0; f < 12; ++f) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       cslot = adv(cslot, 1);
     }
   }
@@ -309,7 +351,7 @@ __global__ __launch_bounds__(256) void k_s5(const char* __restrict__ Td, const c
   const int KBq = rd / 16, nks = rd / 64;
   const char* srcP = Td + ((size_t)(4 * mt + w) * KBq * 64 + lane) * 16;
   const char* srcQ = wVd + ((size_t)(4 * ct + w) * KBq * 64 + lane) * 16;
-  auto issue = [&](int u) {
+  auto issue = [&](int u) __attribute__((always_inline)) {
     int ks = u >> 1;
     ks = ks < nks ? ks : nks - 1;
     char* dst = lds + (u % NU) * UNIT_BYTES + (4 * w) * FRAG_BYTES;
@@ -328,7 +370,7 @@ __global__ __launch_bounds__(256) void k_s5(const char* __restrict__ Td, const c
   for (int u = 0; u < PD; ++u) issue(u);
   for (int ks = 0; ks < nks; ++ks) {
     wait_vmcnt<4 * (PD - 2)>();
-    __syncthreads();
+    lds_barrier();
     issue(2 * ks + PD);
     issue(2 * ks + PD + 1);
     const int sP = (2 * ks) % NU, sQ = (2 * ks + 1) % NU;
@@ -380,31 +422,41 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   const int MT128 = (int)((M + 127) / 128);
   const int PT = (int)(2 * p.r / 128);
   int e;
+  static const char* const names[4] = {"k_s1", "k_fused", "k_reduce", "k_s5"};
+  const int ps = prof_open_forward(c, 4, names);
+  prof_mark(c, ps, 0, 0, st);
   hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU, (int)p.r,
                      ws + p.off_T, PT);
+  prof_mark(c, ps, 0, 1, st);
   if ((e = (int)hipGetLastError())) return e;
 
   const int nq_total = (int)(p.rd / 32);
   const int NQ = nq_total > 16 ? 16 : nq_total;
   const int QS = nq_total / NQ;
   const int splits = tiled_splits(MT128, p.ffn / 64);
+  prof_mark(c, ps, 1, 0, st);
   switch (NQ) {
     case 16: e = launch_fused<16, 64>(c, MT128, splits, QS, st); break;
     case 8: e = launch_fused<8, 64>(c, MT128, splits, QS, st); break;
     case 4: e = launch_fused<4, 64>(c, MT128, splits, QS, st); break;
     default: return (int)hipErrorInvalidValue;
   }
+  prof_mark(c, ps, 1, 1, st);
   if (e) return e;
 
   const int MT32 = 4 * MT128;
   const long long threads = (long long)MT32 * nq_total * 2 * 64;
+  prof_mark(c, ps, 2, 0, st);
   hipLaunchKernelGGL(k_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
                      reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_Td, splits, MT32, nq_total);
+  prof_mark(c, ps, 2, 1, st);
   if ((e = (int)hipGetLastError())) return e;
 
   const int CT = (int)(p.d / 128);
+  prof_mark(c, ps, 3, 0, st);
   hipLaunchKernelGGL(k_s5, dim3(MT128 * CT), dim3(256), 0, st, ws + p.off_Td, ws + p.off_wVd, (uint16_t*)Y, (int)M, (int)p.d,
                      (int)p.rd, CT);
+  prof_mark(c, ps, 3, 1, st);
   return (int)hipGetLastError();
 }
 

@@ -1,0 +1,130 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and its
+argument validation / workspace planning behave as documented.  No GPU is needed (no compute calls)."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2510_25977_amd import binding as B
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not B.LIB_PATH.exists():
+        from paper_2510_25977_amd import build
+        build.build(force=True)
+    return B.lib()
+
+
+def declared_symbols():
+    text = (ROOT / "include" / "svdmlp.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(svdmlp_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    syms = declared_symbols()
+    assert {"svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_workspace_bytes"} <= set(syms)
+    for s in syms:
+        assert hasattr(lib, s), f"{s} declared in svdmlp.h but not exported"
+    assert sorted(B.EXPORTS) == syms
+    assert lib.svdmlp_abi_version() == 1
+
+
+def desc(**kw):
+    d = B.svdmlp_desc()
+    d.kind, d.dtype = kw.get("kind", B.SVDMLP_GATED), kw.get("dtype", B.SVDMLP_BF16)
+    d.max_M, d.d, d.ffn, d.r, d.r_down = kw.get("max_M", 64), kw.get("d", 256), kw.get("ffn", 512), kw.get("r", 64), kw.get("r_down", 128)
+    for n in ("Ug", "Vg", "Uu", "Vu", "Ud", "Vd"):
+        setattr(d, n, kw.get(n, 0x1000))
+    d.workspace, d.workspace_bytes = kw.get("workspace", 0x100000), kw.get("workspace_bytes", 1 << 40)
+    d.flags = kw.get("flags", B.FLAG_SKIP_ARCH_CHECK)
+    return d
+
+
+def create_status(d):
+    out = ctypes.c_void_p()
+    st = B.lib().svdmlp_create(ctypes.byref(d), ctypes.byref(out))
+    if st == 0:
+        B.lib().svdmlp_destroy(out)
+    return st, out
+
+
+def test_status_strings(lib):
+    for code in (0, -1, -2, -3, -4, -5, 17):
+        s = lib.svdmlp_status_string(code)
+        assert s and len(s) > 1
+    assert b"workspace" in lib.svdmlp_status_string(B.SVDMLP_WORKSPACE_TOO_SMALL)
+
+
+def test_workspace_bytes_formula(lib):
+    d = desc(max_M=4096, d=4096, ffn=14336, r=512, r_down=512)
+    n = B.svdmlp_workspace_bytes(d)
+    factors = 2 * 3 * 512 * (4096 + 14336)
+    assert n >= factors + 4096 * 1024 * 2          # re-tiled factors + rank-r strips
+    assert n < factors + (400 << 20)
+    # fp32: T [M,2r] + H [M,ffn] + Td [M,rd]
+    d32 = desc(dtype=B.SVDMLP_F32, max_M=10, d=96, ffn=200, r=24, r_down=40)
+    assert B.svdmlp_workspace_bytes(d32) >= 4 * 10 * (48 + 200 + 40)
+    dl = desc(dtype=B.SVDMLP_F32, kind=B.SVDMLP_LINEAR, max_M=32, d=256, ffn=1024, r=16, r_down=0)
+    assert 0 < B.svdmlp_workspace_bytes(dl) <= 4 * 32 * 16 + 256
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(max_M=0), B.SVDMLP_INVALID_ARGUMENT),
+    (dict(d=-4), B.SVDMLP_INVALID_ARGUMENT),
+    (dict(r=1024), B.SVDMLP_INVALID_ARGUMENT),                 # r > min(d, ffn)
+    (dict(r_down=0), B.SVDMLP_INVALID_ARGUMENT),
+    (dict(kind=7), B.SVDMLP_INVALID_ARGUMENT),
+    (dict(dtype=9), B.SVDMLP_INVALID_ARGUMENT),
+    (dict(Ug=0), B.SVDMLP_INVALID_ARGUMENT),                   # null factor
+    (dict(Vd=0x1008), B.SVDMLP_INVALID_ARGUMENT),              # misaligned factor
+    (dict(workspace=0), B.SVDMLP_INVALID_ARGUMENT),
+    (dict(workspace=0x100010), B.SVDMLP_INVALID_ARGUMENT),     # workspace not 256-byte aligned
+    (dict(workspace_bytes=1024), B.SVDMLP_WORKSPACE_TOO_SMALL),
+    (dict(d=200), B.SVDMLP_UNSUPPORTED),                       # bf16 needs d % 128 == 0
+    (dict(r=48), B.SVDMLP_UNSUPPORTED),                        # bf16 needs r % 64 == 0
+    (dict(r_down=192), B.SVDMLP_UNSUPPORTED),                  # r_down / 32 must be 2,4,8,16 or r_down % 512 == 0
+    (dict(kind=B.SVDMLP_LINEAR), B.SVDMLP_UNSUPPORTED),        # LINEAR is fp32 only
+    (dict(flags=B.FLAG_SKIP_ARCH_CHECK | B.FLAG_FORCE_TILED | B.FLAG_FORCE_STREAM), B.SVDMLP_INVALID_ARGUMENT),
+])
+def test_create_rejects_bad_descriptions(lib, kw, status):
+    st, out = create_status(desc(**kw))
+    assert st == status
+    assert out.value is None                                   # *out is written only on success
+    if status in (B.SVDMLP_INVALID_ARGUMENT, B.SVDMLP_UNSUPPORTED):
+        if "workspace" not in kw and "Ug" not in kw and "Vd" not in kw:
+            assert B.svdmlp_workspace_bytes(desc(**kw)) == 0
+
+
+def test_host_only_context_lifecycle(lib):
+    """With the architecture check skipped a context can be created without a device; forward then refuses."""
+    out = ctypes.c_void_p()
+    d = desc()
+    assert lib.svdmlp_create(ctypes.byref(d), ctypes.byref(out)) == 0 and out.value
+    assert lib.svdmlp_last_path(out) == 0 and lib.svdmlp_last_hip_error(out) == 0
+    X, Y = ctypes.c_void_p(0x2000), ctypes.c_void_p(0x3000)
+    assert lib.svdmlp_forward(out, X, 0, Y, None) == 0                                 # M = 0 is a no-op
+    assert lib.svdmlp_forward(out, X, -1, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert lib.svdmlp_forward(out, X, 65, Y, None) == B.SVDMLP_INVALID_ARGUMENT        # M > max_M
+    assert lib.svdmlp_forward(out, None, 4, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert lib.svdmlp_forward(out, X, 4, X, None) == B.SVDMLP_INVALID_ARGUMENT         # aliasing
+    assert lib.svdmlp_forward(out, ctypes.c_void_p(0x2002), 4, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert lib.svdmlp_forward(out, X, 4, Y, None) == B.SVDMLP_NO_DEVICE               # nothing to run on
+    assert lib.svdmlp_forward(None, X, 4, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    ms = (ctypes.c_float * 8)()
+    nk, nf = ctypes.c_int(), ctypes.c_int()
+    assert lib.svdmlp_profile_end(out, ms, ctypes.byref(nk), ctypes.byref(nf)) == B.SVDMLP_INVALID_ARGUMENT  # no profile open
+    assert lib.svdmlp_profile_kernel_name(out, 0) is None
+    assert lib.svdmlp_destroy(out) == 0
+    assert lib.svdmlp_destroy(None) == 0
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")
+    with pytest.raises(FileNotFoundError):
+        B.lib()
