@@ -55,7 +55,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   // ---- bf16 ----
   if (!gated) return SVDMLP_UNSUPPORTED;  // the single factored linear layer is offered on the fp32 path only
   const int64_t d = de->d, ffn = de->ffn, r = de->r, rd = p->rd;
-  if (d % 128 || ffn % 128 || r % 64) return SVDMLP_UNSUPPORTED;
+  if (d % 128 || ffn % 128 || r % 64 || r < 128) return SVDMLP_UNSUPPORTED;
   const int64_t nq = rd / 32;
   if (rd % 64 || !(pow2_upto16(nq) || rd % 512 == 0)) return SVDMLP_UNSUPPORTED;
 

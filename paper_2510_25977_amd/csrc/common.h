@@ -70,6 +70,35 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// ---- hand-scheduled LDS reads ---------------------------------------------------------------------
+// With asynchronous global->LDS copies in a loop the compiler waits for ALL outstanding LDS reads
+// (lgkmcnt(0)) before every use and reads only a little ahead, which leaves the matrix cores idle for an
+// LDS round trip every few MFMAs.  The kernels therefore issue their ds_read_b128 themselves and wait with
+// exact counts (LDS reads return in order): lds_read<OFF>(addr) starts a read, lgkm_wait<N>(regs...)
+// blocks until at most N later reads are outstanding and ties the named registers to that point so no use
+// of them can be moved above it.
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+__device__ __forceinline__ unsigned lds_offset_of(const void* p) {
+  return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read(unsigned addr) {
+  static_assert(OFF >= 0 && OFF < 65536, "ds_read offset is 16 bits");
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void lgkm_wait(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void lgkm_wait(u32x4& a, u32x4& b, u32x4& c, u32x4& d, u32x4& e, u32x4& f) {
+  asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e), "+v"(f) : "n"(N));
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
+
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

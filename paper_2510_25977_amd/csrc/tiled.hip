@@ -38,7 +38,8 @@ __device__ __forceinline__ const bf16x8* lds_frag(const char* lds, int slot, int
 __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int M, int d, const char* __restrict__ wU,
                                             int r, char* __restrict__ T, int PT) {
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
-  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+  const int lane = threadIdx.x % 64;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);  // wave index, kept scalar
   const int wp = w / 2, wq = w % 2;
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int mt = id / PT, pt = id % PT;
@@ -133,50 +134,113 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
 // Fused gate/up second stage + SiLU gate + down first stage (paper Alg. 3 second loop nest and
 // epilogue, then the first phase of the down-projection XUV kernel of Alg. 2), for one 128-row tile
 // and one range of ffn chunks.  Wave w owns rows 32w..32w+31 of the tile.
-//   per chunk of BN ffn columns:
+//   per chunk of 64 ffn columns:
 //     A-steps (r / 64 of them): G^T, P^T += V^T frags (LDS, shared) x T frags (LDS, wave-private)
 //     H = SiLU(G) .* P  -> bf16 chain frags in registers
 //     B-steps: Td^T[q, m] += Ud^T frags (LDS, shared) x H frags (registers)
+//
+// Unit stream of a chunk: for each A-step the units V (gate/up frags of the chunk's two ffn tiles, 4
+// contraction blocks), Tg, Tu (each wave's own row tile, 4 contraction blocks); then NB units of Ud frags.
+// The producer runs exactly PD = 6 units (= two A-steps) ahead of the consumer, so which unit has to be issued
+// at any consumer position is known at compile time relative to the end of the chunk; no cursor state machine.
 // ------------------------------------------------------------------------------------------------
-// Producer side of the fused kernel's unit stream: per chunk, r/64 A-steps of (BN/64 V units, the Tg unit,
-// the Tu unit) followed by the chunk's Ud units.  All state is wave-uniform.
-template <int NQ, int BN>
-struct FusedProducer {
-  static constexpr int NV = BN / 64, NT = BN / 32, KBC = BN / 16, NB = KBC * NQ / 16;
-  const char *T, *wVg, *wVu, *wUd;
-  char* lds;
-  int KBr, NA, nq_total, qs, mtile, c_end, w;
-  size_t lane16;
-  int pc, pg, pk, pslot;
-  __device__ __forceinline__ void init(const char* T_, const char* wVg_, const char* wVu_, const char* wUd_, char* lds_,
-                                       int r, int nq_total_, int qs_, int mtile_, int c_begin, int c_end_, int w_, int lane) {
-    T = T_; wVg = wVg_; wVu = wVu_; wUd = wUd_; lds = lds_;
-    KBr = r / 16; NA = r / 64; nq_total = nq_total_; qs = qs_; mtile = mtile_; c_end = c_end_; w = w_;
-    lane16 = (size_t)lane * 16;
-    pc = c_begin; pg = 0; pk = 0; pslot = 0;
-  }
-  __device__ __forceinline__ void issue_next() {
-    const int c = pc < c_end ? pc : c_end - 1;  // past the end: keep re-reading the last chunk (never consumed)
-    const char* src;
-    if (pg < NA) {
-      if (pk < NV) {
-        const char* mat = (w < 2) ? wVg : wVu;
-        const int nt = c * NT + 2 * pk + (w & 1);
-        src = mat + ((size_t)nt * KBr + 4 * pg) * FRAG_BYTES;
-      } else {
-        src = T + ((size_t)(mtile * 2 + (pk - NV)) * KBr + 4 * pg) * FRAG_BYTES;
-      }
-      if (++pk == NV + 2) { pk = 0; ++pg; }
-    } else {
-      const int f = 16 * pk + 4 * w;
-      const int kbl = f / NQ, qtl = f % NQ;
-      src = wUd + ((size_t)(c * KBC + kbl) * nq_total + qs * NQ + qtl) * FRAG_BYTES;
-      if (++pk == NB) { pk = 0; pg = 0; ++pc; }
-    }
-    char* dst = lds + pslot * UNIT_BYTES + (4 * w) * FRAG_BYTES;
+
+// Contraction block J (0..3) of an A-step: this wave's Tg and Tu frags and the four V frags (gate even / odd
+// ffn tile, up even / odd).
+template <int J>
+__device__ __forceinline__ void fused_read_a(u32x4 (&R)[6], unsigned aTg, unsigned aTu, unsigned aV) {
+  R[0] = lds_read<J * FRAG_BYTES>(aTg);
+  R[1] = lds_read<J * FRAG_BYTES>(aTu);
+  R[2] = lds_read<(0 * 4 + J) * FRAG_BYTES>(aV);
+  R[3] = lds_read<(1 * 4 + J) * FRAG_BYTES>(aV);
+  R[4] = lds_read<(2 * 4 + J) * FRAG_BYTES>(aV);
+  R[5] = lds_read<(3 * 4 + J) * FRAG_BYTES>(aV);
+}
+__device__ __forceinline__ void fused_mfma_a(const u32x4 (&R)[6], f32x16* G, f32x16* P) {
+  G[0] = mfma32(as_bf16x8(R[2]), as_bf16x8(R[0]), G[0]);
+  G[1] = mfma32(as_bf16x8(R[3]), as_bf16x8(R[0]), G[1]);
+  P[0] = mfma32(as_bf16x8(R[4]), as_bf16x8(R[1]), P[0]);
+  P[1] = mfma32(as_bf16x8(R[5]), as_bf16x8(R[1]), P[1]);
+}
+// Frags 4 G4 .. 4 G4 + 3 of a B unit.
+template <int G4>
+__device__ __forceinline__ void fused_read_b(u32x4 (&U)[4], unsigned aU) {
+  U[0] = lds_read<(4 * G4 + 0) * FRAG_BYTES>(aU);
+  U[1] = lds_read<(4 * G4 + 1) * FRAG_BYTES>(aU);
+  U[2] = lds_read<(4 * G4 + 2) * FRAG_BYTES>(aU);
+  U[3] = lds_read<(4 * G4 + 3) * FRAG_BYTES>(aU);
+}
+// F0 = index of the first of the four frags within the chunk's Ud stream: frag f is (contraction block f / NQ, q tile f % NQ)
+template <int NQ>
+__device__ __forceinline__ void fused_mfma_b(const u32x4 (&U)[4], const bf16x8* Hf, f32x16* acc, const int F0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(src + i * FRAG_BYTES + lane16, dst + i * FRAG_BYTES);
+  for (int i = 0; i < 4; ++i) acc[(F0 + i) % NQ] = mfma32(as_bf16x8(U[i]), Hf[(F0 + i) / NQ], acc[(F0 + i) % NQ]);
+}
+// SiLU(g) * p for elements [E0, E0 + N) of an accumulator tile
+template <int E0, int N>
+__device__ __forceinline__ void silu_mul(const f32x16& g, const f32x16& p, f32x16& h) {
+#pragma unroll
+  for (int e = E0; e < E0 + N; ++e) h[e] = g[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[e])) * p[e];
+}
+
+template <int NQ>
+struct FusedProducer {
+  static constexpr int KBC = 4, NB = KBC * NQ / 16;
+  const char *vcur, *vnext;   // this wave's V frags (gate | up, even | odd ffn tile) of A-step 0 of the current / next chunk
+  const char* tbase;          // this wave's Tg frags of A-step 0 (the same for every chunk); Tu lies tu_off further
+  const char *ucur;           // Ud frags of the current chunk, offset to this wave's quarter of unit 0
+  size_t tu_off, v_chunk, u_chunk;
+  unsigned lane16, u_unit;    // u_unit: distance between consecutive Ud units of a chunk
+  unsigned m0base;            // LDS byte address of this wave's quarter of ring slot 0
+  int pslot, chunks_left;
+
+  __device__ __forceinline__ void init(const char* T, const char* wVg, const char* wVu, const char* wUd, unsigned lds_off,
+                                       int r, int nq_total, int qs, int mtile, int c_begin, int c_end, int w, int lane) {
+    const size_t KBr = r / 16;
+    lane16 = lane * 16;
+    v_chunk = 2 * KBr * FRAG_BYTES;                     // a chunk is two ffn tile panels
+    vcur = ((w < 2) ? wVg : wVu) + ((size_t)(c_begin * 2 + (w & 1)) * KBr) * FRAG_BYTES;
+    chunks_left = c_end - c_begin;
+    vnext = chunks_left > 1 ? vcur + v_chunk : vcur;    // past the end the last chunk is re-read (never consumed)
+    tbase = T + ((size_t)(mtile * 2) * KBr) * FRAG_BYTES;
+    tu_off = KBr * FRAG_BYTES;
+    // Ud unit b of a chunk = frags 16 b .. 16 b + 15 of [contraction block][q tile]; this wave copies frags 4w .. 4w+3
+    const int f = 4 * w;
+    u_chunk = (size_t)KBC * nq_total * FRAG_BYTES;
+    ucur = wUd + ((size_t)c_begin * KBC * nq_total + qs * NQ + (f / NQ) * nq_total + (f % NQ)) * FRAG_BYTES;
+    u_unit = (unsigned)((16 / NQ) * nq_total * FRAG_BYTES);
+    m0base = lds_off + (4 * w) * FRAG_BYTES;
+    pslot = 0;
+  }
+  __device__ __forceinline__ void put(const char* src) {
+    const unsigned dst = m0base + pslot * UNIT_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + i * FRAG_BYTES + lane16),
+                                       (__attribute__((address_space(3))) void*)(uintptr_t)(dst + i * FRAG_BYTES), 16, 0, 0);
     pslot = (pslot + 1 == NU) ? 0 : pslot + 1;
+  }
+  // unit K (0: V, 1: Tg, 2: Tu) of A-step a of the current chunk
+  template <int K>
+  __device__ __forceinline__ void put_a(int a) {
+    if (K == 0) put(vcur + (size_t)a * (4 * FRAG_BYTES));
+    else put(tbase + (size_t)a * (4 * FRAG_BYTES) + (K == 2 ? tu_off : 0));
+  }
+  // unit at position E past the end of the current chunk's A-steps: E < NB is Ud unit E of this chunk, otherwise
+  // unit (E - NB) % 3 of A-step (E - NB) / 3 of the next chunk
+  template <int E>
+  __device__ __forceinline__ void put_rel() {
+    if (E < NB) put(ucur + (size_t)E * u_unit);
+    else {
+      constexpr int a = (E - NB) / 3, k = (E - NB) % 3;
+      if (k == 0) put(vnext + a * (4 * FRAG_BYTES));
+      else put(tbase + a * (4 * FRAG_BYTES) + (k == 2 ? tu_off : 0));
+    }
+  }
+  __device__ __forceinline__ void next_chunk() {
+    vcur = vnext;
+    if (chunks_left > 1) { --chunks_left; ucur += u_chunk; }
+    if (chunks_left > 1) vnext += v_chunk;
   }
 };
 
@@ -185,24 +249,25 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
                                                const char* __restrict__ wVu, const char* __restrict__ wUd,
                                                float* __restrict__ Tdp, int r, int nq_total, int MT128, int splits,
                                                int QS, int chunks_total) {
-  constexpr int NV = BN / 64;               // V units per A-step
-  constexpr int NT = BN / 32;               // ffn tiles per chunk
-  constexpr int KBC = BN / 16;              // contraction blocks of the chunk in the down product
+  static_assert(BN == 64, "a chunk is 64 ffn columns");
+  constexpr int NT = 2;                     // ffn tiles per chunk
+  constexpr int KBC = 4;                    // contraction blocks of the chunk in the down product
   constexpr int NB = KBC * NQ / 16;         // B-steps (units) per chunk
   static_assert(NB >= 1 && (NQ % 4) == 0, "a B unit is 16 frags = (16 / NQ) contraction blocks x NQ tiles");
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
-  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+  const int lane = threadIdx.x % 64;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);  // wave index, kept scalar
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int mt = id / (splits * QS);
   const int s = (id / QS) % splits, qs = id % QS;
-  const int KBr = r / 16, NA = r / 64;
+  const int NA = r / 64;
   const int c_begin = (int)((long long)chunks_total * s / splits);
   const int c_end = (int)((long long)chunks_total * (s + 1) / splits);
   const int mtile = 4 * mt + w;
+  const unsigned lds_off = lds_offset_of(lds);
 
-  // ---- producer cursor over the unit stream (wave-uniform) ----
-  FusedProducer<NQ, BN> prod;
-  prod.init(T, wVg, wVu, wUd, lds, r, nq_total, qs, mtile, c_begin, c_end, w, lane);
+  FusedProducer<NQ> prod;
+  prod.init(T, wVg, wVu, wUd, lds_off, r, nq_total, qs, mtile, c_begin, c_end, w, lane);
 
   f32x16 acc[NQ];
 #pragma unroll
@@ -210,10 +275,12 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
 
-#pragma unroll
-  for (int u = 0; u < PD; ++u) prod.issue_next();
+  // prologue: A-steps 0 and 1 of the first chunk (PD = 6 units)
+  prod.template put_a<0>(0); prod.template put_a<1>(0); prod.template put_a<2>(0);
+  prod.template put_a<0>(1); prod.template put_a<1>(1); prod.template put_a<2>(1);
   int cslot = 0;  // ring slot of the next unit to consume
   auto adv = [&](int sl, int n) __attribute__((always_inline)) { sl += n; return sl >= NU ? sl - NU : sl; };
+  const unsigned lbase = lds_off + lane * 16;
 
   for (int c = c_begin; c < c_end; ++c) {
     f32x16 G[NT], P[NT];
@@ -223,82 +290,93 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
       for (int e = 0; e < 16; ++e) { G[t][e] = 0.f; P[t][e] = 0.f; }
 
     for (int g = 0; g < NA; ++g) {
-      wait_vmcnt<4 * (PD - (NV + 2))>();
+      wait_vmcnt<4 * (PD - 3)>();
       lds_barrier();
-#pragma unroll
-      for (int u = 0; u < NV + 2; ++u) prod.issue_next();
-      const int sTg = adv(cslot, NV), sTu = adv(cslot, NV + 1);
-      // All LDS reads of the step are written before its MFMAs and the scheduler is then told to interleave
-      // them (one contraction block of reads ahead), so that ds_read latency hides under the matrix cores.
-      bf16x8 tg[4], tu[4], vf[NV][4][4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        tg[j] = *lds_frag(lds, sTg, 4 * w + j, lane);
-        tu[j] = *lds_frag(lds, sTu, 4 * w + j, lane);
-#pragma unroll
-        for (int v = 0; v < NV; ++v)
-#pragma unroll
-          for (int k = 0; k < 4; ++k) vf[v][k][j] = *lds_frag(lds, adv(cslot, v), k * 4 + j, lane);
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-          G[2 * v] = mfma32(vf[v][0][j], tg[j], G[2 * v]);
-          G[2 * v + 1] = mfma32(vf[v][1][j], tg[j], G[2 * v + 1]);
-          P[2 * v] = mfma32(vf[v][2][j], tu[j], P[2 * v]);
-          P[2 * v + 1] = mfma32(vf[v][3][j], tu[j], P[2 * v + 1]);
-        }
-      // schedule: reads of block 0; then per MFMA of blocks 0..2 one or two reads of the next block; block 3 bare
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 + 4 * NV, 0);
-#pragma unroll
-      for (int j = 0; j < 3; ++j)
-#pragma unroll
-        for (int m = 0; m < 4 * NV; ++m) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (m < 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-          else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-      __builtin_amdgcn_sched_group_barrier(0x008, 4 * NV, 0);
-      cslot = adv(cslot, NV + 2);
+      const unsigned aV = lbase + cslot * UNIT_BYTES;
+      const unsigned aTg = lbase + adv(cslot, 1) * UNIT_BYTES + (4 * w) * FRAG_BYTES;
+      const unsigned aTu = lbase + adv(cslot, 2) * UNIT_BYTES + (4 * w) * FRAG_BYTES;
+      cslot = adv(cslot, 3);
+      // LDS reads run two contraction blocks ahead of the MFMAs that consume them; the three units this step
+      // has to issue (two A-steps ahead in the stream) are slipped in between the MFMA groups.
+      u32x4 R0[6], R1[6], R2[6], R3[6];
+      fused_read_a<0>(R0, aTg, aTu, aV);
+      fused_read_a<1>(R1, aTg, aTu, aV);
+      lgkm_wait<6>(R0[0], R0[1], R0[2], R0[3], R0[4], R0[5]);
+      fused_read_a<2>(R2, aTg, aTu, aV);
+      fused_mfma_a(R0, G, P);
+      if (g + 2 < NA) prod.template put_a<0>(g + 2);
+      else if (g + 2 == NA) prod.template put_rel<0>();
+      else prod.template put_rel<3>();
+      __builtin_amdgcn_sched_barrier(0);
+      lgkm_wait<6>(R1[0], R1[1], R1[2], R1[3], R1[4], R1[5]);
+      fused_read_a<3>(R3, aTg, aTu, aV);
+      fused_mfma_a(R1, G, P);
+      if (g + 2 < NA) prod.template put_a<1>(g + 2);
+      else if (g + 2 == NA) prod.template put_rel<1>();
+      else prod.template put_rel<4>();
+      __builtin_amdgcn_sched_barrier(0);
+      lgkm_wait<6>(R2[0], R2[1], R2[2], R2[3], R2[4], R2[5]);
+      fused_mfma_a(R2, G, P);
+      if (g + 2 < NA) prod.template put_a<2>(g + 2);
+      else if (g + 2 == NA) prod.template put_rel<2>();
+      else prod.template put_rel<5>();
+      __builtin_amdgcn_sched_barrier(0);
+      lgkm_wait<0>(R3[0], R3[1], R3[2], R3[3], R3[4], R3[5]);
+      fused_mfma_a(R3, G, P);
+      __builtin_amdgcn_sched_barrier(0);
     }
 
-    // SiLU(gate) .* up on the accumulators, rounded to bf16: Hf[2 t + u] is the frag of contraction block 2t+u
+    // SiLU(gate) .* up on the accumulators, rounded to bf16: Hf[2 t + u] is the frag of contraction block 2t+u.
+    // Tile 0 is needed by the first B-step; tile 1 (when the chunk has more than one B-step) is computed
+    // between the MFMA groups of the first B-step.
     bf16x8 Hf[KBC];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      f32x16 hv;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const float gv = G[t][e];
-        hv[e] = gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv)) * P[t][e];
-      }
-      Hf[2 * t] = pack_chain(hv, 0);
-      Hf[2 * t + 1] = pack_chain(hv, 1);
+    f32x16 h0, h1;
+    silu_mul<0, 16>(G[0], P[0], h0);
+    Hf[0] = pack_chain(h0, 0);
+    Hf[1] = pack_chain(h0, 1);
+    if (NB == 1) {
+      silu_mul<0, 16>(G[1], P[1], h1);
+      Hf[2] = pack_chain(h1, 0);
+      Hf[3] = pack_chain(h1, 1);
     }
 
 #pragma unroll
     for (int blk = 0; blk < NB; ++blk) {
       wait_vmcnt<4 * (PD - 1)>();
       lds_barrier();
-      prod.issue_next();
-      bf16x8 uf[16];
-#pragma unroll
-      for (int f = 0; f < 16; ++f) uf[f] = *lds_frag(lds, cslot, f, lane);
-#pragma unroll
-      for (int f = 0; f < 16; ++f) {
-        const int kbl = (16 * blk + f) / NQ, qtl = (16 * blk + f) % NQ;
-        acc[qtl] = mfma32(uf[f], Hf[kbl], acc[qtl]);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-      for (int f = 0; f < 12; ++f) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      const unsigned aU = lbase + cslot * UNIT_BYTES;
       cslot = adv(cslot, 1);
+      u32x4 U0[4], U1[4], U2[4], U3[4];
+      fused_read_b<0>(U0, aU);
+      fused_read_b<1>(U1, aU);
+      lgkm_wait<4>(U0[0], U0[1], U0[2], U0[3]);
+      fused_read_b<2>(U2, aU);
+      fused_mfma_b<NQ>(U0, Hf, acc, 16 * blk + 0);
+      if (blk == 0) prod.template put_rel<6>();
+      if (blk == 1) prod.template put_rel<7>();
+      if (blk == 2) prod.template put_rel<8>();
+      if (blk == 3) prod.template put_rel<9>();
+      if (NB > 1 && blk == 0) silu_mul<0, 4>(G[1], P[1], h1);
+      __builtin_amdgcn_sched_barrier(0);
+      lgkm_wait<4>(U1[0], U1[1], U1[2], U1[3]);
+      fused_read_b<3>(U3, aU);
+      fused_mfma_b<NQ>(U1, Hf, acc, 16 * blk + 4);
+      if (NB > 1 && blk == 0) silu_mul<4, 4>(G[1], P[1], h1);
+      __builtin_amdgcn_sched_barrier(0);
+      lgkm_wait<4>(U2[0], U2[1], U2[2], U2[3]);
+      fused_mfma_b<NQ>(U2, Hf, acc, 16 * blk + 8);
+      if (NB > 1 && blk == 0) silu_mul<8, 4>(G[1], P[1], h1);
+      __builtin_amdgcn_sched_barrier(0);
+      lgkm_wait<0>(U3[0], U3[1], U3[2], U3[3]);
+      fused_mfma_b<NQ>(U3, Hf, acc, 16 * blk + 12);
+      if (NB > 1 && blk == 0) {
+        silu_mul<12, 4>(G[1], P[1], h1);
+        Hf[2] = pack_chain(h1, 0);
+        Hf[3] = pack_chain(h1, 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
+    prod.next_chunk();
   }
   wait_vmcnt<0>();
 
@@ -344,7 +422,8 @@ __global__ __launch_bounds__(256) void k_reduce(const float* __restrict__ Tdp, c
 __global__ __launch_bounds__(256) void k_s5(const char* __restrict__ Td, const char* __restrict__ wVd, uint16_t* __restrict__ Y,
                                             int M, int d, int rd, int CT) {
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
-  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+  const int lane = threadIdx.x % 64;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);  // wave index, kept scalar
   const int wp = w / 2, wq = w % 2;
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int mt = id / CT, ct = id % CT;

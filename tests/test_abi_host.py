@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
 def desc(**kw):
     d = B.svdmlp_desc()
     d.kind, d.dtype = kw.get("kind", B.SVDMLP_GATED), kw.get("dtype", B.SVDMLP_BF16)
-    d.max_M, d.d, d.ffn, d.r, d.r_down = kw.get("max_M", 64), kw.get("d", 256), kw.get("ffn", 512), kw.get("r", 64), kw.get("r_down", 128)
+    d.max_M, d.d, d.ffn, d.r, d.r_down = kw.get("max_M", 64), kw.get("d", 256), kw.get("ffn", 512), kw.get("r", 128), kw.get("r_down", 128)
     for n in ("Ug", "Vg", "Uu", "Vu", "Ud", "Vd"):
         setattr(d, n, kw.get(n, 0x1000))
     d.workspace, d.workspace_bytes = kw.get("workspace", 0x100000), kw.get("workspace_bytes", 1 << 40)
@@ -87,6 +87,7 @@ def test_workspace_bytes_formula(lib):
     (dict(workspace_bytes=1024), B.SVDMLP_WORKSPACE_TOO_SMALL),
     (dict(d=200), B.SVDMLP_UNSUPPORTED),                       # bf16 needs d % 128 == 0
     (dict(r=48), B.SVDMLP_UNSUPPORTED),                        # bf16 needs r % 64 == 0
+    (dict(r=64), B.SVDMLP_UNSUPPORTED),                        # ... and r >= 128
     (dict(r_down=192), B.SVDMLP_UNSUPPORTED),                  # r_down / 32 must be 2,4,8,16 or r_down % 512 == 0
     (dict(kind=B.SVDMLP_LINEAR), B.SVDMLP_UNSUPPORTED),        # LINEAR is fp32 only
     (dict(flags=B.FLAG_SKIP_ARCH_CHECK | B.FLAG_FORCE_TILED | B.FLAG_FORCE_STREAM), B.SVDMLP_INVALID_ARGUMENT),

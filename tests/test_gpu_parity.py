@@ -74,11 +74,11 @@ def test_f32_gated_ragged(M, d, ffn, r, rd):
 
 # ---------------------------------------------------------------------------------- bf16 tiled path
 @pytest.mark.parametrize("M,d,ffn,r,rd", [
-    (128, 128, 128, 64, 128),      # one tile of everything
-    (200, 256, 384, 64, 128),      # ragged M (two row tiles), several chunks
+    (128, 128, 128, 128, 128),     # one tile of everything
+    (200, 256, 384, 128, 128),     # ragged M (two row tiles), several chunks
     (333, 384, 1152, 192, 256),    # three row tiles, r not a power of two, NQ = 8
     (40, 512, 512, 128, 512),      # small M forced onto the tiled path, NQ = 16
-    (129, 1024, 1024, 64, 1024),   # down rank split over two workgroups
+    (129, 1024, 1024, 128, 1024),  # down rank split over two workgroups
 ])
 def test_bf16_tiled_small(M, d, ffn, r, rd):
     gi = synth.make_gated(M, d, ffn, r, rd, stream=21)
@@ -90,7 +90,7 @@ def test_bf16_tiled_small(M, d, ffn, r, rd):
 
 # ---------------------------------------------------------------------------------- bf16 streaming path
 @pytest.mark.parametrize("M", [1, 4, 16, 32, 7])
-@pytest.mark.parametrize("d,ffn,r,rd", [(256, 512, 64, 128), (512, 1408, 128, 256)])
+@pytest.mark.parametrize("d,ffn,r,rd", [(256, 512, 128, 128), (512, 1408, 192, 256)])
 def test_bf16_stream_small(M, d, ffn, r, rd):
     gi = synth.make_gated(M, d, ffn, r, rd, stream=31)
     Y, ref, path = run_gated(gi, max_M=32)
@@ -159,7 +159,7 @@ def test_workload_wide_sampled_rows():
 
 # ---------------------------------------------------------------------------------- edge cases
 def test_empty_and_invalid_calls():
-    gi = synth.make_gated(8, 128, 128, 64, 128, stream=41)
+    gi = synth.make_gated(8, 128, 128, 128, 128, stream=41)
     d = dev()
     f = {k: v.to(d) for k, v in gi.factors().items()}
     mlp = B.SvdMlp(max_M=8, **f)
@@ -183,7 +183,7 @@ def test_empty_and_invalid_calls():
 
 
 def test_zero_input_gives_zero_output():
-    gi = synth.make_gated(64, 128, 256, 64, 128, stream=42)
+    gi = synth.make_gated(64, 128, 256, 128, 128, stream=42)
     d = dev()
     f = {k: v.to(d) for k, v in gi.factors().items()}
     for flags, M in ((B.FLAG_FORCE_TILED, 64), (0, 16)):
