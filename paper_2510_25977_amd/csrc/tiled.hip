@@ -32,9 +32,30 @@ __device__ __forceinline__ const bf16x8* lds_frag(const char* lds, int slot, int
 }
 
 // ------------------------------------------------------------------------------------------------
+// 2 x 2 register tile step shared by k_s1 and k_s5: one contraction block (16) of a 64 x 64 wave tile.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void mfma_2x2(const u32x4 (&R)[4], f32x16 (&acc)[2][2]) {
+  acc[0][0] = mfma32(as_bf16x8(R[0]), as_bf16x8(R[2]), acc[0][0]);
+  acc[0][1] = mfma32(as_bf16x8(R[0]), as_bf16x8(R[3]), acc[0][1]);
+  acc[1][0] = mfma32(as_bf16x8(R[1]), as_bf16x8(R[2]), acc[1][0]);
+  acc[1][1] = mfma32(as_bf16x8(R[1]), as_bf16x8(R[3]), acc[1][1]);
+}
+
+// ------------------------------------------------------------------------------------------------
 // S1: T^T[p, m] = sum_k U^T[p, k] X^T[k, m]   (paper Alg. 3, first inner loop nest)
 // workgroup tile 128 (p) x 128 (m); wave (wp, wq) owns 64 x 64.
+// Unit stream: per 64-wide contraction step a unit of U^T frags (4 p tiles x 4 blocks) and a unit of X
+// (128 rows x 64 columns, copied as 16 rows x 64 B per wave-load with the 16 B pieces XOR-swizzled by bits
+// 2..3 of the row, so that the 16 lanes of a quarter wave hit 64 distinct banks when they read it back).
 // ------------------------------------------------------------------------------------------------
+template <int J>
+__device__ __forceinline__ void s1_read(u32x4 (&R)[4], unsigned aP, unsigned aX0e, unsigned aX0o, unsigned aX1e, unsigned aX1o) {
+  R[0] = lds_read<(0 * 4 + J) * FRAG_BYTES>(aP);
+  R[1] = lds_read<(1 * 4 + J) * FRAG_BYTES>(aP);
+  R[2] = lds_read<(J / 2) * FRAG_BYTES>((J & 1) ? aX0o : aX0e);
+  R[3] = lds_read<(J / 2) * FRAG_BYTES>((J & 1) ? aX1o : aX1e);
+}
+
 __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int M, int d, const char* __restrict__ wU,
                                             int r, char* __restrict__ T, int PT) {
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
@@ -45,9 +66,11 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
   const int mt = id / PT, pt = id % PT;
   const int KBd = d / 16, KBr = r / 16;
   const int nks = d / 64;
+  const unsigned lds_off = lds_offset_of(lds);
 
   // per-wave sources
-  const char* srcP = wU + ((size_t)(4 * pt + w) * KBd * 64 + lane) * 16;  // + ks * 4 KiB + i * 1 KiB
+  const char* srcP = wU + (size_t)(4 * pt + w) * KBd * FRAG_BYTES;  // + ks * 4 KiB + i * 1 KiB (+ lane * 16)
+  const unsigned lane16 = lane * 16;
   const uint16_t* srcX[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -57,17 +80,23 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
     const int piece = (lane % 4) ^ ((lane >> 4) & 3);
     srcX[i] = X + (size_t)row * d + 32 * kh + 8 * piece;  // + ks * 64
   }
-  auto issue = [&](int u) __attribute__((always_inline)) {
-    int ks = u >> 1;
-    ks = ks < nks ? ks : nks - 1;
-    char* dst = lds + (u % NU) * UNIT_BYTES + (4 * w) * FRAG_BYTES;
-    if ((u & 1) == 0) {
+  const unsigned m0base = lds_off + (4 * w) * FRAG_BYTES;
+  int pslot = 0, pks = 0;   // producer: ring slot and contraction step of the next unit pair
+  auto put_pair = [&]() __attribute__((always_inline)) {
+    const int ks = pks < nks ? pks : nks - 1;   // past the end: re-read the last step (never consumed)
+    const unsigned dP = m0base + pslot * UNIT_BYTES;
+    const unsigned dX = m0base + (pslot + 1 == NU ? 0 : pslot + 1) * UNIT_BYTES;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) dma16(srcP + (size_t)ks * 4096 + i * 1024, dst + i * FRAG_BYTES);
-    } else {
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcP + (size_t)ks * 4096 + i * 1024 + lane16),
+                                       (__attribute__((address_space(3))) void*)(uintptr_t)(dP + i * FRAG_BYTES), 16, 0, 0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) dma16(srcX[i] + ks * 64, dst + i * FRAG_BYTES);
-    }
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcX[i] + ks * 64),
+                                       (__attribute__((address_space(3))) void*)(uintptr_t)(dX + i * FRAG_BYTES), 16, 0, 0);
+    pslot += 2;
+    pslot = pslot >= NU ? pslot - NU : pslot;
+    ++pks;
   };
 
   f32x16 acc[2][2];
@@ -78,38 +107,48 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
-  // X frag addressing inside an X unit (see issue(): 16 rows x 64 B per wave-load, 16 B pieces XOR-swizzled
-  // with bits 2..3 of the row so the 16 lanes of a quarter-wave hit 64 distinct banks)
+  // X frag addressing inside an X unit: row group rg (16 rows) and contraction half kh sit at (rg * 2 + kh) KiB;
+  // within it row rho at rho * 64 B, piece p at slot p ^ bits 2..3 of rho.  Blocks j = 0, 1 are half kh = 0
+  // (pieces h and 2 + h), blocks 2, 3 half kh = 1.
   const int il = lane % 32, h = lane / 32, rho = il % 16;
-  int xoff[2][4];
+  unsigned xoff[2][2];
 #pragma unroll
   for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int rg = 2 * (2 * wq + b) + il / 16, kh = j / 2, piece = 2 * (j % 2) + h;
-      xoff[b][j] = (rg * 2 + kh) * FRAG_BYTES + rho * 64 + ((piece ^ ((rho >> 2) & 3)) * 16);
+    for (int o = 0; o < 2; ++o) {
+      const int rg = 2 * (2 * wq + b) + il / 16, piece = 2 * o + h;
+      xoff[b][o] = (rg * 2) * FRAG_BYTES + rho * 64 + ((piece ^ ((rho >> 2) & 3)) * 16);
     }
+  const unsigned pbase = lds_off + lane16 + (2 * wp) * 4 * FRAG_BYTES;
 
-#pragma unroll
-  for (int u = 0; u < PD; ++u) issue(u);
+  put_pair(); put_pair(); put_pair();   // PD = 6 units
+  int cslot = 0;
   for (int ks = 0; ks < nks; ++ks) {
     wait_vmcnt<4 * (PD - 2)>();
     lds_barrier();
-    issue(2 * ks + PD);
-    issue(2 * ks + PD + 1);
-    const int sP = (2 * ks) % NU, sX = (2 * ks + 1) % NU;
-    const char* xs = lds + sX * UNIT_BYTES;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      bf16x8 a0 = *lds_frag(lds, sP, (2 * wp + 0) * 4 + j, lane);
-      bf16x8 a1 = *lds_frag(lds, sP, (2 * wp + 1) * 4 + j, lane);
-      bf16x8 b0 = *reinterpret_cast<const bf16x8*>(xs + xoff[0][j]);
-      bf16x8 b1 = *reinterpret_cast<const bf16x8*>(xs + xoff[1][j]);
-      acc[0][0] = mfma32(a0, b0, acc[0][0]);
-      acc[0][1] = mfma32(a0, b1, acc[0][1]);
-      acc[1][0] = mfma32(a1, b0, acc[1][0]);
-      acc[1][1] = mfma32(a1, b1, acc[1][1]);
-    }
+    const unsigned aP = pbase + cslot * UNIT_BYTES;
+    const unsigned xs = lds_off + (cslot + 1 == NU ? 0 : cslot + 1) * UNIT_BYTES;
+    cslot += 2;
+    cslot = cslot >= NU ? cslot - NU : cslot;
+    const unsigned x0e = xs + xoff[0][0], x0o = xs + xoff[0][1], x1e = xs + xoff[1][0], x1o = xs + xoff[1][1];
+    u32x4 R0[4], R1[4], R2[4], R3[4];
+    s1_read<0>(R0, aP, x0e, x0o, x1e, x1o);
+    s1_read<1>(R1, aP, x0e, x0o, x1e, x1o);
+    lgkm_wait<4>(R0[0], R0[1], R0[2], R0[3]);
+    s1_read<2>(R2, aP, x0e, x0o, x1e, x1o);
+    mfma_2x2(R0, acc);
+    put_pair();
+    __builtin_amdgcn_sched_barrier(0);
+    lgkm_wait<4>(R1[0], R1[1], R1[2], R1[3]);
+    s1_read<3>(R3, aP, x0e, x0o, x1e, x1o);
+    mfma_2x2(R1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    lgkm_wait<4>(R2[0], R2[1], R2[2], R2[3]);
+    mfma_2x2(R2, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    lgkm_wait<0>(R3[0], R3[1], R3[2], R3[3]);
+    mfma_2x2(R3, acc);
+    __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();
   // epilogue: lane = activation row m; registers 8t..8t+7 are the chain-order frag of contraction block t
@@ -417,26 +456,47 @@ __global__ __launch_bounds__(256) void k_reduce(const float* __restrict__ Tdp, c
 
 // ------------------------------------------------------------------------------------------------
 // S5: Y[m, c] = sum_q Td[m, q] Vd[q, c]   (second phase of the down-projection XUV kernel, Alg. 2)
-// workgroup tile 128 (m) x 128 (c); output in the standard row-major layout.
+// workgroup tile 128 (m) x 128 (c); output in the standard row-major layout.  The contraction is only
+// r_down long, so a workgroup lives for a few steps: the ring is kept small (4 slots, 64 KiB) so that two
+// workgroups share a CU and one's pipeline fill overlaps the other's MFMAs.
 // ------------------------------------------------------------------------------------------------
+constexpr int NU5 = 4, PD5 = 2;
+template <int J>
+__device__ __forceinline__ void s5_read(u32x4 (&R)[4], unsigned aP, unsigned aQ) {
+  R[0] = lds_read<(0 * 4 + J) * FRAG_BYTES>(aP);
+  R[1] = lds_read<(1 * 4 + J) * FRAG_BYTES>(aP);
+  R[2] = lds_read<(0 * 4 + J) * FRAG_BYTES>(aQ);
+  R[3] = lds_read<(1 * 4 + J) * FRAG_BYTES>(aQ);
+}
+
 __global__ __launch_bounds__(256) void k_s5(const char* __restrict__ Td, const char* __restrict__ wVd, uint16_t* __restrict__ Y,
                                             int M, int d, int rd, int CT) {
-  __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds[NU5 * UNIT_BYTES];
   const int lane = threadIdx.x % 64;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);  // wave index, kept scalar
   const int wp = w / 2, wq = w % 2;
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int mt = id / CT, ct = id % CT;
   const int KBq = rd / 16, nks = rd / 64;
-  const char* srcP = Td + ((size_t)(4 * mt + w) * KBq * 64 + lane) * 16;
-  const char* srcQ = wVd + ((size_t)(4 * ct + w) * KBq * 64 + lane) * 16;
-  auto issue = [&](int u) __attribute__((always_inline)) {
-    int ks = u >> 1;
-    ks = ks < nks ? ks : nks - 1;
-    char* dst = lds + (u % NU) * UNIT_BYTES + (4 * w) * FRAG_BYTES;
-    const char* src = ((u & 1) == 0 ? srcP : srcQ) + (size_t)ks * 4096;
+  const unsigned lds_off = lds_offset_of(lds);
+  const unsigned lane16 = lane * 16;
+  const char* srcP = Td + (size_t)(4 * mt + w) * KBq * FRAG_BYTES;
+  const char* srcQ = wVd + (size_t)(4 * ct + w) * KBq * FRAG_BYTES;
+  const unsigned m0base = lds_off + (4 * w) * FRAG_BYTES;
+  int pslot = 0, pks = 0;
+  auto put_pair = [&]() __attribute__((always_inline)) {
+    const int ks = pks < nks ? pks : nks - 1;
+    const unsigned dP = m0base + pslot * UNIT_BYTES, dQ = dP + UNIT_BYTES;   // NU5 is even: a pair never wraps
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(src + i * 1024, dst + i * FRAG_BYTES);
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcP + (size_t)ks * 4096 + i * 1024 + lane16),
+                                       (__attribute__((address_space(3))) void*)(uintptr_t)(dP + i * FRAG_BYTES), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcQ + (size_t)ks * 4096 + i * 1024 + lane16),
+                                       (__attribute__((address_space(3))) void*)(uintptr_t)(dQ + i * FRAG_BYTES), 16, 0, 0);
+    pslot = (pslot + 2 == NU5) ? 0 : pslot + 2;
+    ++pks;
   };
   f32x16 acc[2][2];
 #pragma unroll
@@ -445,25 +505,33 @@ __global__ __launch_bounds__(256) void k_s5(const char* __restrict__ Td, const c
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
-#pragma unroll
-  for (int u = 0; u < PD; ++u) issue(u);
+  const unsigned pbase = lds_off + lane16 + (2 * wp) * 4 * FRAG_BYTES;
+  const unsigned qbase = lds_off + lane16 + (2 * wq) * 4 * FRAG_BYTES + UNIT_BYTES;
+  put_pair();   // PD5 = 2 units
+  int cslot = 0;
   for (int ks = 0; ks < nks; ++ks) {
-    wait_vmcnt<4 * (PD - 2)>();
+    wait_vmcnt<4 * (PD5 - 2)>();
     lds_barrier();
-    issue(2 * ks + PD);
-    issue(2 * ks + PD + 1);
-    const int sP = (2 * ks) % NU, sQ = (2 * ks + 1) % NU;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      bf16x8 a0 = *lds_frag(lds, sP, (2 * wp + 0) * 4 + j, lane);
-      bf16x8 a1 = *lds_frag(lds, sP, (2 * wp + 1) * 4 + j, lane);
-      bf16x8 b0 = *lds_frag(lds, sQ, (2 * wq + 0) * 4 + j, lane);
-      bf16x8 b1 = *lds_frag(lds, sQ, (2 * wq + 1) * 4 + j, lane);
-      acc[0][0] = mfma32(a0, b0, acc[0][0]);
-      acc[0][1] = mfma32(a0, b1, acc[0][1]);
-      acc[1][0] = mfma32(a1, b0, acc[1][0]);
-      acc[1][1] = mfma32(a1, b1, acc[1][1]);
-    }
+    const unsigned aP = pbase + cslot * UNIT_BYTES, aQ = qbase + cslot * UNIT_BYTES;
+    cslot = (cslot + 2 == NU5) ? 0 : cslot + 2;
+    u32x4 R0[4], R1[4], R2[4], R3[4];
+    s5_read<0>(R0, aP, aQ);
+    s5_read<1>(R1, aP, aQ);
+    lgkm_wait<4>(R0[0], R0[1], R0[2], R0[3]);
+    s5_read<2>(R2, aP, aQ);
+    mfma_2x2(R0, acc);
+    put_pair();
+    __builtin_amdgcn_sched_barrier(0);
+    lgkm_wait<4>(R1[0], R1[1], R1[2], R1[3]);
+    s5_read<3>(R3, aP, aQ);
+    mfma_2x2(R1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    lgkm_wait<4>(R2[0], R2[1], R2[2], R2[3]);
+    mfma_2x2(R2, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    lgkm_wait<0>(R3[0], R3[1], R3[2], R3[3]);
+    mfma_2x2(R3, acc);
+    __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();
   const int il = lane % 32, h = lane / 32;
