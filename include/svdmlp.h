@@ -60,7 +60,9 @@ enum {
 enum {
   SVDMLP_FLAG_FORCE_TILED = 1u << 0,    /* bf16: always take the MFMA-tiled (prefill) path */
   SVDMLP_FLAG_FORCE_STREAM = 1u << 1,   /* bf16: always take the weight-streaming (decode) path; needs M <= 32 */
-  SVDMLP_FLAG_SKIP_ARCH_CHECK = 1u << 2 /* do not require gfx950 (host-only unit tests of argument handling) */
+  SVDMLP_FLAG_SKIP_ARCH_CHECK = 1u << 2,/* do not require gfx950 (host-only unit tests of argument handling) */
+  SVDMLP_FLAG_STREAM_ONE_KERNEL = 1u << 3 /* weight-streaming path as one persistent kernel instead of four launches
+                                           (used when the extents fit its per-wave register budget) */
 };
 
 typedef struct {
@@ -110,7 +112,8 @@ const char *svdmlp_status_string(int status);
 int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
 
 /* Which path the last svdmlp_forward on this context took: 0 none yet, 1 fp32 debug,
- * 2 bf16 MFMA-tiled (prefill), 3 bf16 weight-streaming (decode). */
+ * 2 bf16 MFMA-tiled (prefill), 3 bf16 weight-streaming (decode) as four launches, 4 bf16 weight-streaming as one
+ * persistent kernel (SVDMLP_FLAG_STREAM_ONE_KERNEL). */
 int svdmlp_last_path(const svdmlp_ctx *ctx);
 
 /* Per-kernel timing for benchmarks.  svdmlp_profile_begin creates a pool of HIP events for up to

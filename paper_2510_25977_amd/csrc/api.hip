@@ -80,7 +80,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   p->off_Td = take((size_t)p->Mpad * rd * 2);
   p->off_H = take((size_t)32 * ffn * 2);            // streaming path: the ffn-wide activation of <= 32 rows
   p->off_part = take((size_t)8 << 20);              // streaming path: split-K partial tiles
-  p->off_cnt = take(16384);                          // streaming path: arrival counters (zero between calls)
+  p->off_cnt = take(32768 + 3 * 256 * 128);          // streaming paths: tickets, completion counters, per-workgroup flags
   p->total_bytes = off;
   return SVDMLP_OK;
 }
@@ -129,12 +129,14 @@ int svdmlp_create(const svdmlp_desc* desc, svdmlp_ctx** out) {
     if (reinterpret_cast<uintptr_t>(desc->workspace) & 255u) return SVDMLP_INVALID_ARGUMENT;
     if (desc->workspace_bytes < p.total_bytes) return SVDMLP_WORKSPACE_TOO_SMALL;
   }
+  int n_cus = 0;
   if (!(desc->flags & SVDMLP_FLAG_SKIP_ARCH_CHECK)) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return SVDMLP_NO_DEVICE; }
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return SVDMLP_NO_DEVICE; }
     if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return SVDMLP_NO_DEVICE;
+    n_cus = prop.multiProcessorCount;
   }
   Ctx* c = new (std::nothrow) Ctx;
   if (!c) return SVDMLP_INVALID_ARGUMENT;
@@ -143,6 +145,7 @@ int svdmlp_create(const svdmlp_desc* desc, svdmlp_ctx** out) {
   c->ws = static_cast<char*>(desc->workspace);
   c->last_hip_error = 0;
   c->last_path = 0;
+  c->n_cus = n_cus;
   if (desc->dtype == SVDMLP_BF16 && !(desc->flags & SVDMLP_FLAG_SKIP_ARCH_CHECK)) {
     // One-time re-tiling of the invariant factors into matrix-core fragments.
     int e = (int)hipDeviceSynchronize();
@@ -173,8 +176,10 @@ int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip
       if (M > 32) return SVDMLP_UNSUPPORTED;
       stream_path = true;
     }
-    c->last_path = stream_path ? 3 : 2;
-    e = stream_path ? bf16_stream_forward(c, X, M, Y, st) : bf16_tiled_forward(c, X, M, Y, st);
+    const bool one_kernel = stream_path && (c->plan.flags & SVDMLP_FLAG_STREAM_ONE_KERNEL) && bf16_decode_supported(c);
+    c->last_path = stream_path ? (one_kernel ? 4 : 3) : 2;
+    e = !stream_path ? bf16_tiled_forward(c, X, M, Y, st)
+                     : one_kernel ? bf16_decode_forward(c, X, M, Y, st) : bf16_stream_forward(c, X, M, Y, st);
   }
   if (e != 0) {
     c->last_hip_error = e;

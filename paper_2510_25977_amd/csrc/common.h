@@ -148,6 +148,8 @@ int f32_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st)
 int bf16_repack_all(const Ctx* c, hipStream_t st);
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
+int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
+bool bf16_decode_supported(const Ctx* c);
 
 // Optional per-kernel timing: HIP events recorded on the caller's stream around every kernel launch of
 // a forward (only while a profile is open; see svdmlp_profile_begin in svdmlp.h).
@@ -166,6 +168,8 @@ struct Ctx {
   char* ws;
   int last_hip_error;
   int last_path;
+  int n_cus = 0;                                 // compute units of the device the context was created on
+  mutable unsigned long long decode_gen = 0;     // forwards launched on the single-kernel decode path
   mutable Prof prof;
 };
 

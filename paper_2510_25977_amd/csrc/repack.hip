@@ -62,8 +62,9 @@ int bf16_repack_all(const Ctx* c, hipStream_t st) {
   if ((e = repack(de.Ud, p.ffn, p.rd, ws + p.off_wUd, ORDER_CHAIN, KB_MAJOR, 0, qt, st))) return e;
   // Vd^T: rows c in [0, d), contraction over rd, meets Td produced by an MFMA -> chain order
   if ((e = repack(de.Vd, p.rd, p.d, ws + p.off_wVd, ORDER_CHAIN, TILE_MAJOR, 0, (int)(p.d / 32), st))) return e;
-  // arrival counters of the streaming path start at zero and are left at zero by every forward
-  return (int)hipMemsetAsync(ws + p.off_cnt, 0, 16384, st);
+  // tickets of the streaming paths start at zero and are left at zero by every forward; the completion counters
+  // of the single-kernel decode path start at zero and only grow
+  return (int)hipMemsetAsync(ws + p.off_cnt, 0, 32768 + 3 * 256 * 128, st);
 }
 
 }  // namespace svdmlp

@@ -91,10 +91,12 @@ def test_bf16_tiled_small(M, d, ffn, r, rd):
 # ---------------------------------------------------------------------------------- bf16 streaming path
 @pytest.mark.parametrize("M", [1, 4, 16, 32, 7])
 @pytest.mark.parametrize("d,ffn,r,rd", [(256, 512, 128, 128), (512, 1408, 192, 256)])
-def test_bf16_stream_small(M, d, ffn, r, rd):
+@pytest.mark.parametrize("one_kernel", [False, True])
+def test_bf16_stream_small(M, d, ffn, r, rd, one_kernel):
+    """Weight-streaming path: as four launches (path 3, the default) and as one persistent kernel (path 4)."""
     gi = synth.make_gated(M, d, ffn, r, rd, stream=31)
-    Y, ref, path = run_gated(gi, max_M=32)
-    assert path == 3
+    Y, ref, path = run_gated(gi, max_M=32, flags=B.FLAG_STREAM_ONE_KERNEL if one_kernel else 0)
+    assert path == (4 if one_kernel else 3)
     assert relmax(Y, ref) <= BF16_TOL, (relmax(Y, ref), relfro(Y, ref))
     assert relfro(Y, ref) <= 1.5e-2
 
@@ -105,7 +107,8 @@ def test_bf16_stream_and_tiled_agree_and_are_deterministic():
     f = {k: v.to(d) for k, v in gi.factors().items()}
     X = gi.X.to(d)
     outs = {}
-    for name, flags in (("stream", B.FLAG_FORCE_STREAM), ("tiled", B.FLAG_FORCE_TILED)):
+    for name, flags in (("stream", B.FLAG_FORCE_STREAM), ("stream1", B.FLAG_FORCE_STREAM | B.FLAG_STREAM_ONE_KERNEL),
+                        ("tiled", B.FLAG_FORCE_TILED)):
         mlp = B.SvdMlp(max_M=16, flags=flags, **f)
         y1 = mlp(X).clone()
         y2 = mlp(X).clone()
@@ -116,6 +119,7 @@ def test_bf16_stream_and_tiled_agree_and_are_deterministic():
         outs[name] = y1.cpu().to(torch.float64).numpy()
         mlp.close()
     assert relmax(outs["stream"], outs["tiled"]) <= BF16_TOL
+    assert relmax(outs["stream1"], outs["tiled"]) <= BF16_TOL
 
 
 # ---------------------------------------------------------------------------------- full-size workloads
@@ -126,12 +130,13 @@ def test_workload_mlp_small():
     assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
 
 
+@pytest.mark.parametrize("one_kernel", [False, True])
 @pytest.mark.parametrize("M", [1, 4, 16])
-def test_workload_decode(M):
+def test_workload_decode(M, one_kernel):
     """d=4096 ffn=14336 r=512, M in {1,4,16}."""
     gi = synth.make_workload("decode", M=M)
-    Y, ref, path = run_gated(gi)
-    assert path == 3
+    Y, ref, path = run_gated(gi, flags=B.FLAG_STREAM_ONE_KERNEL if one_kernel else 0)
+    assert path == (4 if one_kernel else 3)
     assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
 
 
