@@ -71,7 +71,18 @@ def bench_forward(gi, dev, steps, warmup, profile=True):
     return ms, wall_ms, kernels, path
 
 
-def bench_decode_rotating(dev, M, steps, warmup, nsets=12):
+def copy_calibration(dev, reps=5):
+    """A plain device-to-device copy of known size (256 MiB read + 256 MiB written per launch)."""
+    n = 256 << 20
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    return dict(bytes_read=n, bytes_written=n, launches=reps, kernel="torch Tensor.copy_ (uint8, 256 MiB)")
+
+
+def bench_decode_rotating(dev, M, steps, warmup, nsets=12, flags=0):
     """Decode shape measured cold to the 256 MB memory-side cache: rotate through `nsets` independent
     factor sets (one context each, > 2x the cache in total) so every forward streams its weights from HBM."""
     gi = synth.make_workload("decode", M=M)
@@ -82,7 +93,7 @@ def bench_decode_rotating(dev, M, steps, warmup, nsets=12):
     f = {k: v.to(dev) for k, v in gi.factors().items()}
     for i in range(nsets):
         # the same values in every set; only the addresses (hence the cache lines) differ
-        ctxs.append(B.SvdMlp(max_M=16, keep_factors=False, **f))
+        ctxs.append(B.SvdMlp(max_M=16, keep_factors=False, flags=flags, **f))
     del f
     n = [0]
 
@@ -152,6 +163,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--one-kernel-decode", action="store_true", help="decode through the single persistent kernel")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (known size) so that a rocprofv3 --pmc run of this "
+                         "command can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the forward shards over rows with no communication; "
@@ -169,9 +184,10 @@ def main():
     flops = cm.gated_mlp_flops(M, d, ffn, r)
     nbytes = cm.gated_mlp_bytes(M, d, ffn, r)
 
+    dflags = B.FLAG_STREAM_ONE_KERNEL if args.one_kernel_decode else 0
     if args.workload == "decode":
-        dec = bench_decode_rotating(dev, M, args.steps, args.warmup)
-        ms, wall_ms, kernels, path = dec["ms_per_step"], dec["ms_per_step"], dec["warm_kernels_ms"], 3
+        dec = bench_decode_rotating(dev, M, args.steps, args.warmup, flags=dflags)
+        ms, wall_ms, kernels, path = dec["ms_per_step"], dec["ms_per_step"], dec["warm_kernels_ms"], (4 if dflags else 3)
     else:
         ms, wall_ms, kernels, path = bench_forward(gi, dev, args.steps, args.warmup)
         dec = None
@@ -184,7 +200,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: gated SVD-MLP d={d} ffn={ffn} r={r} M={M}", "M": M, "d": d, "ffn": ffn,
-                   "r": r, "path": {2: "mfma-tiled", 3: "weight-streaming"}.get(path, str(path))},
+                   "r": r, "path": {2: "mfma-tiled", 3: "weight-streaming, 4 launches", 4: "weight-streaming, 1 launch"}.get(path, str(path))},
         "flops_per_step": flops, "algorithmic_bytes_per_step": nbytes,
         "frac_of_bf16_mfma_peak": flops / ms / 1e9 / PEAK_BF16_TFLOPS,
         "wall_ms_per_step": wall_ms,
@@ -193,9 +209,13 @@ def main():
 
     # roofline of the dominant kernel (HIP-event average over the timed region)
     if args.workload == "decode":
-        k_ms = kernels.get("k_stream_d2", 0.0)
-        k_bytes = 2 * (2 * r * ffn) + 2 * (M * 2 * r + M * ffn)          # Vg, Vu once; T in, H out
-        out["roofline"] = {"bound": "hbm", "kernel": "k_stream_d2", "achieved": k_bytes / k_ms / 1e6 if k_ms else None,
+        kname = "k_decode" if "k_decode" in kernels else "k_stream_d2"
+        k_ms = kernels.get(kname, 0.0)
+        if kname == "k_decode":
+            k_bytes = nbytes                                              # the whole forward is one launch
+        else:
+            k_bytes = 2 * (2 * r * ffn) + 2 * (M * 2 * r + M * ffn)      # Vg, Vu once; T in, H out
+        out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": k_bytes / k_ms / 1e6 if k_ms else None,
                            "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": k_bytes / k_ms / 1e6 / PEAK_HBM_GBS if k_ms else None, "traffic": None,
                            "note": "per-kernel time from the warm single-set run"}
@@ -209,12 +229,14 @@ def main():
     if dec is not None:
         out["decode"] = dec
     elif not args.no_decode:
-        out["decode"] = bench_decode_rotating(dev, 16, max(args.steps, 48), args.warmup)
+        out["decode"] = bench_decode_rotating(dev, 16, max(args.steps, 48), args.warmup, flags=dflags)
     if not args.no_dense and args.workload != "decode":
         out["dense_baseline"] = bench_dense(dev, M, d, ffn, max(5, args.steps // 3), 3)
         out["dense_baseline"]["speedup_of_factored"] = out["dense_baseline"]["ms_per_step"] / ms
     out["paper_context"] = {"kernel_speedup_vs_nki": 1.35, "e2e_speedup": 1.21, "hardware": "AWS Trainium trn1",
                             "note": "paper figures for its own kernels; not the target"}
+    if args.copy_calibration:
+        out["copy_calibration"] = copy_calibration(dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(gi if args.workload != "decode" else synth.make_workload("decode", M=16))
     print(json.dumps(out))
