@@ -219,7 +219,8 @@ __device__ __forceinline__ void fused_mfma_b(const u32x4 (&U)[4], const bf16x8* 
 template <int E0, int N>
 __device__ __forceinline__ void silu_mul(const f32x16& g, const f32x16& p, f32x16& h) {
 #pragma unroll
-  for (int e = E0; e < E0 + N; ++e) h[e] = g[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[e])) * p[e];
+  for (int e = E0; e < E0 + N; ++e)
+    h[e] = g[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g[e] * -1.44269504088896f)) * p[e];  // exp(-g) = 2^(-g log2 e)
 }
 
 template <int NQ>
@@ -287,7 +288,7 @@ template <int NQ, int BN>
 __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const char* __restrict__ wVg,
                                                const char* __restrict__ wVu, const char* __restrict__ wUd,
                                                float* __restrict__ Tdp, int r, int nq_total, int MT128, int splits,
-                                               int QS, int chunks_total) {
+                                               int QS, int chunks_total, int mx, int sx) {
   static_assert(BN == 64, "a chunk is 64 ffn columns");
   constexpr int NT = 2;                     // ffn tiles per chunk
   constexpr int KBC = 4;                    // contraction blocks of the chunk in the down product
@@ -296,9 +297,21 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
   const int lane = threadIdx.x % 64;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);  // wave index, kept scalar
-  const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
-  const int mt = id / (splits * QS);
-  const int s = (id / QS) % splits, qs = id % QS;
+  // Workgroup -> (row tile, ffn range, q half).  With mx > 0 the 8 XCDs form a (MT128 / mx) x (splits / sx) grid:
+  // an XCD owns mx row tiles (their rank-r strips stay resident in its L2) and sx ffn ranges (each factor byte is
+  // then fetched by MT128 / mx XCDs instead of all 8).  Otherwise contiguous logical ids per XCD.
+  int mt, s, qs;
+  if (mx > 0) {
+    const int x = blockIdx.x % 8, i = blockIdx.x / 8, ngm = MT128 / mx;
+    mt = (x % ngm) * mx + i / (sx * QS);
+    s = (x / ngm) * sx + (i / QS) % sx;
+    qs = i % QS;
+  } else {
+    const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    mt = id / (splits * QS);
+    s = (id / QS) % splits;
+    qs = id % QS;
+  }
   const int NA = r / 64;
   const int c_begin = (int)((long long)chunks_total * s / splits);
   const int c_end = (int)((long long)chunks_total * (s + 1) / splits);
@@ -557,9 +570,21 @@ static int launch_fused(const Ctx* c, int MT128, int splits, int QS, hipStream_t
   const Plan& p = c->plan;
   char* ws = c->ws;
   const int chunks = (int)(p.ffn / BN);
+  // XCD grid: the most row tiles per XCD whose strips (128 x 2r bf16 each) fit in half of its 4 MiB L2
+  int mx = 0, sx = 0;
+  const long long strip = 128LL * 2 * p.r * 2;
+  for (int m = 8; m >= 1; m /= 2) {
+    if (MT128 % m || m * strip > (2LL << 20)) continue;
+    const int ngm = MT128 / m;
+    if (ngm > 8 || 8 % ngm) continue;
+    const int ngs = 8 / ngm;
+    if (splits % ngs) continue;
+    mx = m; sx = splits / ngs;
+    break;
+  }
   hipLaunchKernelGGL((k_fused<NQ, BN>), dim3(MT128 * splits * QS), dim3(256), 0, st, ws + p.off_T, ws + p.off_wVg,
                      ws + p.off_wVu, ws + p.off_wUd, reinterpret_cast<float*>(ws + p.off_Tdp), (int)p.r, (int)(p.rd / 32),
-                     MT128, splits, QS, chunks);
+                     MT128, splits, QS, chunks, mx, sx);
   return (int)hipGetLastError();
 }
 
