@@ -61,8 +61,10 @@ enum {
   SVDMLP_FLAG_FORCE_TILED = 1u << 0,    /* bf16: always take the MFMA-tiled (prefill) path */
   SVDMLP_FLAG_FORCE_STREAM = 1u << 1,   /* bf16: always take the weight-streaming (decode) path; needs M <= 32 */
   SVDMLP_FLAG_SKIP_ARCH_CHECK = 1u << 2,/* do not require gfx950 (host-only unit tests of argument handling) */
-  SVDMLP_FLAG_STREAM_ONE_KERNEL = 1u << 3 /* weight-streaming path as one persistent kernel instead of four launches
+  SVDMLP_FLAG_STREAM_ONE_KERNEL = 1u << 3,/* weight-streaming path as one persistent kernel instead of four launches
                                            (used when the extents fit its per-wave register budget) */
+  SVDMLP_FLAG_TILED_FUSED = 1u << 4     /* MFMA-tiled path: keep the gated activation in registers (one fused kernel)
+                                           instead of staging it through the workspace */
 };
 
 typedef struct {

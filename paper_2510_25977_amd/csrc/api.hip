@@ -59,7 +59,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   const int64_t nq = rd / 32;
   if (rd % 64 || !(pow2_upto16(nq) || rd % 512 == 0)) return SVDMLP_UNSUPPORTED;
 
-  p->Mpad = (de->max_M + 127) / 128 * 128;
+  p->Mpad = (de->max_M + 255) / 256 * 256;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   p->off_wU = take((size_t)2 * r * d * 2);
@@ -75,10 +75,17 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
     int64_t rws = (int64_t)tiled_splits(mt, nchunks) * mt * 128;
     if (rws > rows) rows = rws;
   }
+  if (rd % 128 == 0)
+    for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {
+      int64_t rws = (int64_t)gemm_splits(mt, rd / 128, ffn / 32) * mt * 256;
+      if (rws > rows) rows = rws;
+    }
   p->part_rows = rows;
   p->off_Tdp = take((size_t)rows * rd * 4);
   p->off_Td = take((size_t)p->Mpad * rd * 2);
   p->off_H = take((size_t)32 * ffn * 2);            // streaming path: the ffn-wide activation of <= 32 rows
+  // staged tiled path: the whole gated activation as frags
+  p->off_Hfull = take(rd % 128 == 0 ? (size_t)p->Mpad * ffn * 2 : 0);
   p->off_part = take((size_t)8 << 20);              // streaming path: split-K partial tiles
   p->off_cnt = take(32768 + 3 * 256 * 128);          // streaming paths: tickets, completion counters, per-workgroup flags
   p->total_bytes = off;

@@ -90,6 +90,14 @@ __device__ __forceinline__ u32x4 lds_read(unsigned addr) {
   return v;
 }
 template <int N>
+__device__ __forceinline__ void lgkm_wait(u32x4& a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void lgkm_wait(u32x4& a, u32x4& b, u32x4& c) {
+  asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(N));
+}
+template <int N>
 __device__ __forceinline__ void lgkm_wait(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
   asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
@@ -129,9 +137,9 @@ struct Plan {
   uint32_t flags;
   // bf16: byte offsets into the workspace (all 256-byte aligned)
   size_t off_wU, off_wVg, off_wVu, off_wUd, off_wVd;  // re-tiled factors
-  size_t off_T, off_Tdp, off_Td, off_H, off_part, off_cnt;
+  size_t off_T, off_Tdp, off_Td, off_H, off_Hfull, off_part, off_cnt;
   size_t total_bytes;
-  int64_t Mpad;       // max_M rounded up to 128
+  int64_t Mpad;       // max_M rounded up to 256
   int64_t part_rows;  // rows reserved for split-K partial sums of Td
   // f32: element offsets
   size_t f32_T, f32_H, f32_Td;
@@ -141,11 +149,15 @@ int make_plan(const svdmlp_desc* desc, Plan* plan);  // returns a status code
 
 // number of ffn splits the tiled path uses for a given number of 128-row tiles
 int tiled_splits(int64_t mtiles128, int64_t nchunks);
+// number of ffn ranges k_down1 uses for a given number of 256-row tiles, 128-wide rank tiles and steps
+int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps);
 
 // ---- launchers (each returns hipError_t as int; 0 = success) ---------------------------------
 struct Ctx;
 int f32_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_repack_all(const Ctx* c, hipStream_t st);
+int launch_gate_up(const Ctx* c, int MT256, hipStream_t st);
+int launch_down1(const Ctx* c, int MT256, int splits, hipStream_t st);
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);

@@ -432,13 +432,16 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
   }
   wait_vmcnt<0>();
 
-  // partial Td^T of this ffn range: [split][row tile][q tile][register][lane], fp32
+  // partial Td^T of this ffn range: [split][row tile][q tile][register group of 4][lane][4], fp32
   const int MT32 = 4 * MT128;
 #pragma unroll
   for (int q = 0; q < NQ; ++q) {
-    float* dst = Tdp + ((((size_t)s * MT32 + mtile) * nq_total + qs * NQ + q) * 16) * 64 + lane;
+    f32x4* dst = reinterpret_cast<f32x4*>(Tdp + (((size_t)s * MT32 + mtile) * nq_total + qs * NQ + q) * 1024) + lane;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) dst[e * 64] = acc[q][e];
+    for (int g = 0; g < 4; ++g) {
+      f32x4 v = {acc[q][4 * g], acc[q][4 * g + 1], acc[q][4 * g + 2], acc[q][4 * g + 3]};
+      dst[g * 64] = v;
+    }
   }
 }
 
@@ -453,11 +456,15 @@ __global__ __launch_bounds__(256) void k_reduce(const float* __restrict__ Tdp, c
   const int t = (int)((idx / 64) % 2);
   const long long tile = idx / 128;  // mtile * nq_total + qt
   float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  const size_t split_stride = (size_t)MT32 * nq_total * 16 * 64;
+  const size_t split_stride = (size_t)MT32 * nq_total * 1024;
   for (int sp = 0; sp < splits; ++sp) {
-    const float* src = Tdp + sp * split_stride + ((size_t)tile * 16 + 8 * t) * 64 + lane;
+    const f32x4* src = reinterpret_cast<const f32x4*>(Tdp + sp * split_stride + (size_t)tile * 1024) + 2 * t * 64 + lane;
+    const f32x4 a = src[0], b = src[64];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] += src[e * 64];
+    for (int e = 0; e < 4; ++e) {
+      v[e] += a[e];
+      v[4 + e] += b[e];
+    }
   }
   bf16x8 o;
 #pragma unroll
@@ -588,14 +595,47 @@ static int launch_fused(const Ctx* c, int MT128, int splits, int QS, hipStream_t
   return (int)hipGetLastError();
 }
 
+// Everything after k_s1 when the gated activation is staged through HBM (gemm.hip).
+static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st) {
+  const Plan& p = c->plan;
+  char* ws = c->ws;
+  const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
+  const int nq_total = (int)(p.rd / 32);
+  int e;
+  prof_mark(c, ps, 1, 0, st);
+  e = launch_gate_up(c, MT256, st);
+  prof_mark(c, ps, 1, 1, st);
+  if (e) return e;
+  const int splits = gemm_splits(MT256, p.rd / 128, p.ffn / 32);
+  prof_mark(c, ps, 2, 0, st);
+  e = launch_down1(c, MT256, splits, st);
+  prof_mark(c, ps, 2, 1, st);
+  if (e) return e;
+  const int MT32 = 8 * MT256;
+  const long long threads = (long long)MT32 * nq_total * 2 * 64;
+  prof_mark(c, ps, 3, 0, st);
+  hipLaunchKernelGGL(k_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                     reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_Td, splits, MT32, nq_total);
+  prof_mark(c, ps, 3, 1, st);
+  if ((e = (int)hipGetLastError())) return e;
+  const int CT = (int)(p.d / 128);
+  prof_mark(c, ps, 4, 0, st);
+  hipLaunchKernelGGL(k_s5, dim3(MT128 * CT), dim3(256), 0, st, ws + p.off_Td, ws + p.off_wVd, (uint16_t*)Y, (int)M, (int)p.d,
+                     (int)p.rd, CT);
+  prof_mark(c, ps, 4, 1, st);
+  return (int)hipGetLastError();
+}
+
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
   const int MT128 = (int)((M + 127) / 128);
   const int PT = (int)(2 * p.r / 128);
   int e;
-  static const char* const names[4] = {"k_s1", "k_fused", "k_reduce", "k_s5"};
-  const int ps = prof_open_forward(c, 4, names);
+  static const char* const names_fused[4] = {"k_s1", "k_fused", "k_reduce", "k_s5"};
+  static const char* const names_staged[5] = {"k_s1", "k_gate_up", "k_down1", "k_reduce", "k_s5"};
+  const bool staged = p.rd % 128 == 0 && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
+  const int ps = staged ? prof_open_forward(c, 5, names_staged) : prof_open_forward(c, 4, names_fused);
   prof_mark(c, ps, 0, 0, st);
   hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU, (int)p.r,
                      ws + p.off_T, PT);
@@ -603,6 +643,7 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   if ((e = (int)hipGetLastError())) return e;
 
   const int nq_total = (int)(p.rd / 32);
+  if (staged) return staged_tail(c, M, Y, ps, st);
   const int NQ = nq_total > 16 ? 16 : nq_total;
   const int QS = nq_total / NQ;
   const int splits = tiled_splits(MT128, p.ffn / 64);
