@@ -20,6 +20,8 @@ int tiled_splits(int64_t mtiles128, int64_t nchunks) {
   return (int)s;
 }
 
+bool staged_supported(int64_t rd, int64_t ffn) { return rd % 256 == 0 && ffn % 256 == 0; }
+
 static bool pow2_upto16(int64_t x) { return x == 2 || x == 4 || x == 8 || x == 16; }
 
 int make_plan(const svdmlp_desc* de, Plan* p) {
@@ -75,9 +77,9 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
     int64_t rws = (int64_t)tiled_splits(mt, nchunks) * mt * 128;
     if (rws > rows) rows = rws;
   }
-  if (rd % 128 == 0)
+  if (staged_supported(rd, ffn))
     for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {
-      int64_t rws = (int64_t)gemm_splits(mt, rd / 128, ffn / 32) * mt * 256;
+      int64_t rws = (int64_t)gemm_splits(mt, rd / 256, ffn / 32) * mt * 256;
       if (rws > rows) rows = rws;
     }
   p->part_rows = rows;
@@ -85,7 +87,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   p->off_Td = take((size_t)p->Mpad * rd * 2);
   p->off_H = take((size_t)32 * ffn * 2);            // streaming path: the ffn-wide activation of <= 32 rows
   // staged tiled path: the whole gated activation as frags
-  p->off_Hfull = take(rd % 128 == 0 ? (size_t)p->Mpad * ffn * 2 : 0);
+  p->off_Hfull = take(staged_supported(rd, ffn) ? (size_t)p->Mpad * ffn * 2 : 0);
   p->off_part = take((size_t)8 << 20);              // streaming path: split-K partial tiles
   p->off_cnt = take(32768 + 3 * 256 * 128);          // streaming paths: tickets, completion counters, per-workgroup flags
   p->total_bytes = off;

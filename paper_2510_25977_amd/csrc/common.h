@@ -149,7 +149,9 @@ int make_plan(const svdmlp_desc* desc, Plan* plan);  // returns a status code
 
 // number of ffn splits the tiled path uses for a given number of 128-row tiles
 int tiled_splits(int64_t mtiles128, int64_t nchunks);
-// number of ffn ranges k_down1 uses for a given number of 256-row tiles, 128-wide rank tiles and steps
+// extents the staged tiled path (gemm.hip) handles
+bool staged_supported(int64_t rd, int64_t ffn);
+// number of ffn ranges k_down1 uses for a given number of 256-row tiles, 256-wide rank tiles and unit pairs
 int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps);
 
 // ---- launchers (each returns hipError_t as int; 0 = success) ---------------------------------

@@ -606,7 +606,7 @@ static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st)
   e = launch_gate_up(c, MT256, st);
   prof_mark(c, ps, 1, 1, st);
   if (e) return e;
-  const int splits = gemm_splits(MT256, p.rd / 128, p.ffn / 32);
+  const int splits = gemm_splits(MT256, p.rd / 256, p.ffn / 32);
   prof_mark(c, ps, 2, 0, st);
   e = launch_down1(c, MT256, splits, st);
   prof_mark(c, ps, 2, 1, st);
@@ -634,7 +634,7 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   int e;
   static const char* const names_fused[4] = {"k_s1", "k_fused", "k_reduce", "k_s5"};
   static const char* const names_staged[5] = {"k_s1", "k_gate_up", "k_down1", "k_reduce", "k_s5"};
-  const bool staged = p.rd % 128 == 0 && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
+  const bool staged = staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
   const int ps = staged ? prof_open_forward(c, 5, names_staged) : prof_open_forward(c, 4, names_fused);
   prof_mark(c, ps, 0, 0, st);
   hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU, (int)p.r,
