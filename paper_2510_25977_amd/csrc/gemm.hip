@@ -5,6 +5,7 @@
 //                                                 first, squashed to SiLU(G) in bf16 pairs, then the up tile is
 //                                                 accumulated on top and multiplied in; H leaves as frags
 //   k_down1     Tdp  = H Ud over one ffn range     256 rows x 256 rank columns per workgroup, fp32 partials
+//   k_out       Y    = Td Vd                       256 rows x 256 columns per workgroup
 //
 // Why not keep H in registers: a workgroup that owns every rank column of its rows (so that H never has to be
 // stored) has room for only 128 rows, and then each byte brought into the CU feeds too few MFMAs.  A CU keeps a
@@ -19,15 +20,13 @@
 //
 // The two waves of a SIMD (w and w + 4) alternate between a memory phase and a compute phase, half a period
 // apart, so that the SIMD's matrix core always has exactly one wave feeding it while the other one fetches:
-//   memory phase of step s:  issue the copies of step s+2 (into the slot of step s-2), read the weight frags of
-//                            both units and the activation frags of the first unit of step s from LDS, do any
-//                            vector-ALU work that is due (SiLU, output conversion), wait for this wave's copies
-//                            of step s+1, barrier
-//   compute phase of step s: 16 MFMAs; the activation frags of the second unit are read into the registers the
-//                            first unit's MFMAs have released; barrier
+//   memory phase of step s:  issue the copies of step s+2 (into the slot of step s-2), read the twelve frags of
+//                            step s from LDS, do any vector-ALU work that is due (SiLU, output conversion), wait
+//                            for this wave's copies of step s+1, barrier
+//   compute phase of step s: 16 MFMAs and nothing else; barrier
 // Every barrier is a workgroup barrier; waves 4..7 pass one extra barrier at the start, which puts them one phase
-// behind waves 0..3 for the rest of the kernel.  Step s is read by waves 0..3 in phases 2s, 2s+1 and by waves
-// 4..7 in phases 2s+1, 2s+2; its copies were waited for before the barrier that opens phase 2s, and its slot is
+// behind waves 0..3 for the rest of the kernel.  Step s is read by waves 0..3 in phase 2s and by waves 4..7 in
+// phase 2s+1; its copies were waited for before the barrier that opens phase 2s, and its slot is
 // written again by copies issued in phase 2s+4 or later.
 #include "common.h"
 
@@ -71,10 +70,10 @@ struct GProd {
   }
 };
 
-// Operand registers of a wave: the four activation frags of one unit (refilled tile by tile with the second
-// unit's) and the two weight frags of each unit of the step.
+// Operand registers of a wave: four activation and two weight frags for each of the two units of a step.  All of
+// them are read in the memory phase, so the compute phase issues nothing but MFMAs.
 struct GRegs {
-  u32x4 A0, A1, A2, A3, Wa0, Wa1, Wb0, Wb1;
+  u32x4 A0, A1, A2, A3, Wa0, Wa1, B0, B1, B2, B3, Wb0, Wb1;
 };
 
 struct GCons {
@@ -83,9 +82,10 @@ struct GCons {
   int slot;           // slot of the step that is read next
   int done;           // steps consumed
 
-  // memory phase, LDS part: weight frags of both units, activation frags of the first
+  // memory phase, LDS part
   __device__ __forceinline__ void fetch() {
     const unsigned aA = rdA + slot * G_STEP, aW = rdW + slot * G_STEP;
+    slot = (slot + 1) & (G_SLOTS - 1);
     R.Wa0 = lds_read<0 * FRAG_BYTES>(aW);
     R.Wa1 = lds_read<1 * FRAG_BYTES>(aW);
     R.A0 = lds_read<0 * FRAG_BYTES>(aA);
@@ -94,47 +94,38 @@ struct GCons {
     R.A3 = lds_read<3 * FRAG_BYTES>(aA);
     R.Wb0 = lds_read<G_UNIT + 0 * FRAG_BYTES>(aW);
     R.Wb1 = lds_read<G_UNIT + 1 * FRAG_BYTES>(aW);
+    R.B0 = lds_read<G_UNIT + 0 * FRAG_BYTES>(aA);
+    R.B1 = lds_read<G_UNIT + 1 * FRAG_BYTES>(aA);
+    R.B2 = lds_read<G_UNIT + 2 * FRAG_BYTES>(aA);
+    R.B3 = lds_read<G_UNIT + 3 * FRAG_BYTES>(aA);
   }
   // compute phase.  acc[i][j]: weight tile i (rows of the transposed product), activation tile j (lanes).
   // FIRST: the accumulators start from zero with this step (the zero is the MFMA's C operand).
   template <bool FIRST>
   __device__ __forceinline__ void compute(f32x16 (&acc)[2][4]) {
-    const unsigned aA = rdA + slot * G_STEP + G_UNIT;
-    slot = (slot + 1) & (G_SLOTS - 1);
     ++done;
     f32x16 z;
 #pragma unroll
     for (int e = 0; e < 16; ++e) z[e] = 0.f;
-    lgkm_wait<0>(R.Wa0, R.Wa1, R.Wb0, R.Wb1);
-    lgkm_wait<0>(R.A0, R.A1, R.A2, R.A3);
+    lgkm_wait<6>(R.A0, R.A1, R.A2, R.A3, R.Wa0, R.Wa1);
     acc[0][0] = mfma32(as_bf16x8(R.Wa0), as_bf16x8(R.A0), FIRST ? z : acc[0][0]);
     acc[1][0] = mfma32(as_bf16x8(R.Wa1), as_bf16x8(R.A0), FIRST ? z : acc[1][0]);
-    __builtin_amdgcn_sched_barrier(0);
-    R.A0 = lds_read<0 * FRAG_BYTES>(aA);
     acc[0][1] = mfma32(as_bf16x8(R.Wa0), as_bf16x8(R.A1), FIRST ? z : acc[0][1]);
     acc[1][1] = mfma32(as_bf16x8(R.Wa1), as_bf16x8(R.A1), FIRST ? z : acc[1][1]);
-    __builtin_amdgcn_sched_barrier(0);
-    R.A1 = lds_read<1 * FRAG_BYTES>(aA);
     acc[0][2] = mfma32(as_bf16x8(R.Wa0), as_bf16x8(R.A2), FIRST ? z : acc[0][2]);
     acc[1][2] = mfma32(as_bf16x8(R.Wa1), as_bf16x8(R.A2), FIRST ? z : acc[1][2]);
-    __builtin_amdgcn_sched_barrier(0);
-    R.A2 = lds_read<2 * FRAG_BYTES>(aA);
     acc[0][3] = mfma32(as_bf16x8(R.Wa0), as_bf16x8(R.A3), FIRST ? z : acc[0][3]);
     acc[1][3] = mfma32(as_bf16x8(R.Wa1), as_bf16x8(R.A3), FIRST ? z : acc[1][3]);
     __builtin_amdgcn_sched_barrier(0);
-    R.A3 = lds_read<3 * FRAG_BYTES>(aA);
-    lgkm_wait<3>(R.A0);
-    acc[0][0] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.A0), acc[0][0]);
-    acc[1][0] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.A0), acc[1][0]);
-    lgkm_wait<2>(R.A1);
-    acc[0][1] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.A1), acc[0][1]);
-    acc[1][1] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.A1), acc[1][1]);
-    lgkm_wait<1>(R.A2);
-    acc[0][2] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.A2), acc[0][2]);
-    acc[1][2] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.A2), acc[1][2]);
-    lgkm_wait<0>(R.A3);
-    acc[0][3] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.A3), acc[0][3]);
-    acc[1][3] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.A3), acc[1][3]);
+    lgkm_wait<0>(R.B0, R.B1, R.B2, R.B3, R.Wb0, R.Wb1);
+    acc[0][0] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.B0), acc[0][0]);
+    acc[1][0] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.B0), acc[1][0]);
+    acc[0][1] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.B1), acc[0][1]);
+    acc[1][1] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.B1), acc[1][1]);
+    acc[0][2] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.B2), acc[0][2]);
+    acc[1][2] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.B2), acc[1][2]);
+    acc[0][3] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.B3), acc[0][3]);
+    acc[1][3] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.B3), acc[1][3]);
     __builtin_amdgcn_sched_barrier(0);
   }
 };
@@ -406,6 +397,88 @@ __global__ __launch_bounds__(G_THREADS) void k_down1(const char* __restrict__ H,
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Y = Td Vd   (second phase of the down-projection XUV kernel, Alg. 2), 256 rows x 256 columns per workgroup.
+// Td: [32-row tile][rd / 16] chain-order frags; wVd: [column tile][rd / 16] frags; Y row-major [M, d] bf16.
+// The accumulators hold the tile transposed (lane = row, registers = columns); each wave turns its 128 x 64 part
+// around through a private piece of LDS (rows padded to 144 bytes so that a half wave's writes fall into
+// different banks) and stores whole 128-byte row segments.
+// ------------------------------------------------------------------------------------------------
+constexpr int OUT_ROW = 144;                      // bytes per staged row: 64 bf16 + 16 bytes of padding
+constexpr int OUT_WAVE = 128 * OUT_ROW;           // 18 KiB per wave
+constexpr int OUT_LDS = 8 * OUT_WAVE > G_LDS ? 8 * OUT_WAVE : G_LDS;
+
+__global__ __launch_bounds__(G_THREADS) void k_out(const char* __restrict__ Td, const char* __restrict__ wVd,
+                                                   uint16_t* __restrict__ Y, int M, int d, int KBq, int MT, int CT) {
+  __shared__ __attribute__((aligned(1024))) char lds[OUT_LDS];
+  const int lane = threadIdx.x % 64;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+  const int wm = w / 4, wn = w % 4;
+  const int L = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int ct = L % CT, mt = L / CT;
+  const int total_steps = KBq / 2;
+  const unsigned lds_off = lds_offset_of(lds);
+
+  GProd prod;
+  prod.a_kb = FRAG_BYTES;
+  prod.w_kb = FRAG_BYTES;
+  prod.pa = Td + (long long)(8 * mt + w) * KBq * FRAG_BYTES;
+  prod.pw = wVd + (long long)(8 * ct + w) * KBq * FRAG_BYTES;
+  prod.lane16 = lane * 16;
+  prod.dst = lds_off + w * FRAG_BYTES;
+  prod.dstw = lds_off + (8 + w) * FRAG_BYTES;
+  prod.slot = 0;
+  prod.issued = 0;
+  GCons cons;
+  cons.rdA = lds_off + lane * 16 + 4 * wm * FRAG_BYTES;
+  cons.rdW = lds_off + lane * 16 + (8 + 2 * wn) * FRAG_BYTES;
+  cons.slot = 0;
+  cons.done = 0;
+
+  if (prod.issued < total_steps) prod.step();
+  if (prod.issued < total_steps) prod.step();
+  if (prod.issued >= 2) wait_vmcnt<4>();
+  else wait_vmcnt<0>();
+  if (w >= 4) lds_barrier();
+  lds_barrier();
+
+  f32x16 acc[2][4];
+  for (int i = 0; i < total_steps; ++i) {
+    if (prod.issued < total_steps) prod.step();
+    cons.fetch();
+    g_certify(prod, cons);
+    if (i == 0) cons.compute<true>(acc);
+    else cons.compute<false>(acc);
+    lds_barrier();
+  }
+  if (w < 4) lds_barrier();
+  // every wave has read its last operands and no copy is in flight: LDS is free
+
+  char* stage = lds + w * OUT_WAVE;
+  const int il = lane % 32, h = lane / 32;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {  // registers 4g..4g+3: columns 32 i + 8 g + 4 h + (0..3) of row 32 j + il
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (__bf16)acc[i][j][4 * g + e];
+        *reinterpret_cast<bf16x4*>(stage + (32 * j + il) * OUT_ROW + (32 * i + 8 * g + 4 * h) * 2) = v;
+      }
+  // rows come back eight per instruction, 16 bytes per lane
+  const int rsub = lane / 8, piece = lane % 8;
+  const long long m0 = 256LL * mt + 128 * wm;
+  const int c0 = 256 * ct + 64 * wn;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int row = 8 * k + rsub;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * OUT_ROW + piece * 16);
+    if (m0 + row < M) *reinterpret_cast<u32x4*>(Y + (m0 + row) * d + c0 + piece * 8) = v;
+  }
+}
+
 int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps) {
   // one workgroup per CU on 256 CUs; every split keeps at least four steps
   int64_t s = (256 + mt256 * qt - 1) / (mt256 * qt);
@@ -443,6 +516,15 @@ int launch_down1(const Ctx* c, int MT256, int splits, hipStream_t st) {
   const int QT = (int)(p.rd / 256);
   hipLaunchKernelGGL(k_down1, dim3(MT256 * QT * splits), dim3(G_THREADS), 0, st, ws + p.off_Hfull, ws + p.off_wUd,
                      reinterpret_cast<float*>(ws + p.off_Tdp), (int)(p.ffn / 16), (int)(p.rd / 32), MT256, QT, splits);
+  return (int)hipGetLastError();
+}
+
+int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st) {
+  const Plan& p = c->plan;
+  char* ws = c->ws;
+  const int CT = (int)(p.d / 256);
+  hipLaunchKernelGGL(k_out, dim3(MT256 * CT), dim3(G_THREADS), 0, st, ws + p.off_Td, ws + p.off_wVd, (uint16_t*)Y, (int)M,
+                     (int)p.d, (int)(p.rd / 16), MT256, CT);
   return (int)hipGetLastError();
 }
 

@@ -618,12 +618,17 @@ static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st)
                      reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_Td, splits, MT32, nq_total);
   prof_mark(c, ps, 3, 1, st);
   if ((e = (int)hipGetLastError())) return e;
-  const int CT = (int)(p.d / 128);
   prof_mark(c, ps, 4, 0, st);
-  hipLaunchKernelGGL(k_s5, dim3(MT128 * CT), dim3(256), 0, st, ws + p.off_Td, ws + p.off_wVd, (uint16_t*)Y, (int)M, (int)p.d,
-                     (int)p.rd, CT);
+  if (p.d % 256 == 0) {
+    e = launch_out(c, M, Y, MT256, st);
+  } else {
+    const int CT = (int)(p.d / 128);
+    hipLaunchKernelGGL(k_s5, dim3(MT128 * CT), dim3(256), 0, st, ws + p.off_Td, ws + p.off_wVd, (uint16_t*)Y, (int)M,
+                       (int)p.d, (int)p.rd, CT);
+    e = (int)hipGetLastError();
+  }
   prof_mark(c, ps, 4, 1, st);
-  return (int)hipGetLastError();
+  return e;
 }
 
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
@@ -633,7 +638,7 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   const int PT = (int)(2 * p.r / 128);
   int e;
   static const char* const names_fused[4] = {"k_s1", "k_fused", "k_reduce", "k_s5"};
-  static const char* const names_staged[5] = {"k_s1", "k_gate_up", "k_down1", "k_reduce", "k_s5"};
+  static const char* const names_staged[5] = {"k_s1", "k_gate_up", "k_down1", "k_reduce", "k_out"};
   const bool staged = staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
   const int ps = staged ? prof_open_forward(c, 5, names_staged) : prof_open_forward(c, 4, names_fused);
   prof_mark(c, ps, 0, 0, st);
