@@ -114,8 +114,10 @@ const char *svdmlp_status_string(int status);
 int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
 
 /* Which path the last svdmlp_forward on this context took: 0 none yet, 1 fp32 debug,
- * 2 bf16 MFMA-tiled (prefill), 3 bf16 weight-streaming (decode) as four launches, 4 bf16 weight-streaming as one
- * persistent kernel (SVDMLP_FLAG_STREAM_ONE_KERNEL). */
+ * 2 bf16 MFMA-tiled (prefill) with the gated activation kept in registers (SVDMLP_FLAG_TILED_FUSED, or extents the
+ * staged variant does not take: it needs ffn and r_down to be multiples of 256), 3 bf16 weight-streaming (decode) as
+ * four launches, 4 bf16 weight-streaming as one persistent kernel (SVDMLP_FLAG_STREAM_ONE_KERNEL), 5 bf16
+ * MFMA-tiled with the gated activation staged through the workspace (the default for large M). */
 int svdmlp_last_path(const svdmlp_ctx *ctx);
 
 /* Per-kernel timing for benchmarks.  svdmlp_profile_begin creates a pool of HIP events for up to

@@ -82,10 +82,32 @@ def test_f32_gated_ragged(M, d, ffn, r, rd):
 ])
 def test_bf16_tiled_small(M, d, ffn, r, rd):
     gi = synth.make_gated(M, d, ffn, r, rd, stream=21)
-    Y, ref, path = run_gated(gi, flags=B.FLAG_FORCE_TILED)
+    Y, ref, path = run_gated(gi, flags=B.FLAG_FORCE_TILED | B.FLAG_TILED_FUSED)
     assert path == 2
     assert relmax(Y, ref) <= BF16_TOL, (relmax(Y, ref), relfro(Y, ref))
     assert relfro(Y, ref) <= 1.5e-2
+
+
+@pytest.mark.parametrize("M,d,ffn,r,rd", [
+    (40, 512, 512, 128, 512),      # one row tile, mostly padding; two column tiles everywhere
+    (300, 512, 1024, 192, 256),    # ragged M over two 256-row tiles, r not a power of two
+    (520, 768, 512, 256, 512),     # odd number of row tiles, three output column tiles
+    (300, 384, 512, 128, 256),     # d not a multiple of 256: the 128-column output kernel finishes the job
+    (129, 1024, 1024, 128, 1024),  # four rank tiles
+    (2304, 256, 7680, 128, 256),   # more tiles (9 x 30) than compute units: workgroups of k_gate_up take several
+])
+def test_bf16_staged_small(M, d, ffn, r, rd):
+    """Tiled path with the gated activation staged through the workspace (path 5); the fused variant must agree."""
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=22)
+    big = M > 1000
+    rows = list(range(0, M, 97)) + [M - 1] if big else None
+    Y, ref, path = run_gated(gi, flags=B.FLAG_FORCE_TILED, rows=rows)
+    assert path == 5
+    assert relmax(Y, ref) <= BF16_TOL, (relmax(Y, ref), relfro(Y, ref))
+    assert relfro(Y, ref) <= 1.5e-2
+    Yf, _, pathf = run_gated(gi, flags=B.FLAG_FORCE_TILED | B.FLAG_TILED_FUSED, rows=rows)
+    assert pathf == 2
+    assert relmax(Y, Yf) <= BF16_TOL
 
 
 # ---------------------------------------------------------------------------------- bf16 streaming path
@@ -150,6 +172,14 @@ def test_workload_prefill_sampled_rows(r):
     gi = synth.make_workload("prefill", r=r)
     rows = SAMPLE_ROWS + [4095, 3000]
     Y, ref, path = run_gated(gi, rows=rows)
+    assert path == 5
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+
+
+def test_workload_prefill_fused_variant_sampled_rows():
+    """The same workload with the gated activation kept in registers (one fused kernel, path 2)."""
+    gi = synth.make_workload("prefill", r=512)
+    Y, ref, path = run_gated(gi, rows=SAMPLE_ROWS + [4095], flags=B.FLAG_TILED_FUSED)
     assert path == 2
     assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
 
@@ -158,7 +188,7 @@ def test_workload_wide_sampled_rows():
     """d=5120 ffn=27648 r=1024 M=2048, power-law U columns, 1 % of X entries x20."""
     gi = synth.make_workload("wide")
     Y, ref, path = run_gated(gi, rows=SAMPLE_ROWS)
-    assert path == 2
+    assert path == 5
     assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
 
 
