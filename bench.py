@@ -52,23 +52,24 @@ def make_ctx(gi, dev, max_M, flags=0):
     return B.SvdMlp(max_M=max_M, flags=flags, keep_factors=False, **f)
 
 
-def bench_forward(gi, dev, steps, warmup, profile=True):
-    """Time `steps` forwards of one context; per-kernel averages come from HIP events the library records
-    on the launch stream inside the same timed region."""
+def bench_forward(gi, dev, steps, warmup, profile=True, flags=0):
+    """Time `steps` forwards of one context, twice: first bare (this is the reported throughput), then again with
+    the library recording a HIP event before and after every kernel on the launch stream, which gives the
+    per-kernel averages (the event packets between the kernels cost a few microseconds per launch, so the second
+    pass is slower; both step times are reported)."""
     dims = gi.dims
-    mlp = make_ctx(gi, dev, dims["M"])
+    mlp = make_ctx(gi, dev, dims["M"], flags=flags)
     X = gi.X.to(dev)
     Y = torch.empty_like(X)
-    for _ in range(warmup):
-        mlp(X, Y)
-    torch.cuda.synchronize()
+    ms, wall_ms = time_steps(lambda: mlp(X, Y), steps, warmup)
+    kernels, ms_ev = {}, None
     if profile:
         B.svdmlp_profile_begin(mlp.ctx, steps)
-    ms, wall_ms = time_steps(lambda: mlp(X, Y), steps, 0)
-    kernels, nf = (B.svdmlp_profile_end(mlp.ctx) if profile else ({}, 0))
+        ms_ev, _ = time_steps(lambda: mlp(X, Y), steps, 0)
+        kernels, nf = B.svdmlp_profile_end(mlp.ctx)
     path = mlp.last_path
     mlp.close()
-    return ms, wall_ms, kernels, path
+    return ms, wall_ms, kernels, path, ms_ev
 
 
 def copy_calibration(dev, reps=5):
@@ -164,6 +165,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--one-kernel-decode", action="store_true", help="decode through the single persistent kernel")
+    ap.add_argument("--fused", action="store_true",
+                    help="tiled path with the gated activation kept in registers (one fused kernel) instead of staged")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (known size) so that a rocprofv3 --pmc run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE")
@@ -189,7 +192,8 @@ def main():
         dec = bench_decode_rotating(dev, M, args.steps, args.warmup, flags=dflags)
         ms, wall_ms, kernels, path = dec["ms_per_step"], dec["ms_per_step"], dec["warm_kernels_ms"], (4 if dflags else 3)
     else:
-        ms, wall_ms, kernels, path = bench_forward(gi, dev, args.steps, args.warmup)
+        ms, wall_ms, kernels, path, ms_ev = bench_forward(gi, dev, args.steps, args.warmup,
+                                                          flags=B.FLAG_TILED_FUSED if args.fused else 0)
         dec = None
 
     out = {
@@ -200,12 +204,15 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: gated SVD-MLP d={d} ffn={ffn} r={r} M={M}", "M": M, "d": d, "ffn": ffn,
-                   "r": r, "path": {2: "mfma-tiled", 3: "weight-streaming, 4 launches", 4: "weight-streaming, 1 launch"}.get(path, str(path))},
+                   "r": r, "path": {2: "mfma-tiled, fused", 3: "weight-streaming, 4 launches", 4: "weight-streaming, 1 launch",
+                            5: "mfma-tiled, staged"}.get(path, str(path))},
         "flops_per_step": flops, "algorithmic_bytes_per_step": nbytes,
         "frac_of_bf16_mfma_peak": flops / ms / 1e9 / PEAK_BF16_TFLOPS,
         "wall_ms_per_step": wall_ms,
         "kernels_ms": kernels,
     }
+    if args.workload != "decode":
+        out["ms_per_step_with_kernel_events"] = ms_ev
 
     # roofline of the dominant kernel (HIP-event average over the timed region)
     if args.workload == "decode":
@@ -220,11 +227,20 @@ def main():
                            "frac": k_bytes / k_ms / 1e6 / PEAK_HBM_GBS if k_ms else None, "traffic": None,
                            "note": "per-kernel time from the warm single-set run"}
     else:
-        k_ms = kernels.get("k_fused", 0.0)
-        k_flops = 6 * M * ffn * r                                         # gate + up second stage, down first stage
-        out["roofline"] = {"bound": "mfma", "kernel": "k_fused", "achieved": k_flops / k_ms / 1e9 if k_ms else None,
+        rd = dims.get("r_down", r)
+        kflops = {"k_s1": 2 * M * d * 2 * r,                # X [Ug|Uu]
+                  "k_fused": 4 * M * ffn * r + 2 * M * ffn * rd,   # gate + up second stage, down first stage
+                  "k_gate_up": 4 * M * ffn * r,             # gate + up second stage
+                  "k_down1": 2 * M * ffn * rd,              # down first stage
+                  "k_s5": 2 * M * rd * d, "k_out": 2 * M * rd * d}
+        cand = {k: v for k, v in kernels.items() if k in kflops}
+        kname = max(cand, key=cand.get) if cand else "k_gate_up"   # the dominant kernel: the longest one
+        k_ms = kernels.get(kname, 0.0)
+        k_flops = kflops[kname]
+        out["roofline"] = {"bound": "mfma", "kernel": kname, "achieved": k_flops / k_ms / 1e9 if k_ms else None,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": k_flops / k_ms / 1e9 / PEAK_BF16_TFLOPS if k_ms else None, "traffic": None}
+                           "frac": k_flops / k_ms / 1e9 / PEAK_BF16_TFLOPS if k_ms else None, "traffic": None,
+                           "per_kernel_TFLOPs": {k: kflops[k] / v / 1e9 for k, v in cand.items() if v}}
 
     if dec is not None:
         out["decode"] = dec

@@ -79,6 +79,7 @@ struct GRegs {
 struct GCons {
   GRegs R;
   unsigned rdA, rdW;  // per-lane LDS read addresses in slot 0
+  unsigned rdAh;      // ... of the activation frags when the tile has 128 rows (k_gate_up's half tiles)
   int slot;           // slot of the step that is read next
   int done;           // steps consumed
 
@@ -128,6 +129,38 @@ struct GCons {
     acc[1][3] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.B3), acc[1][3]);
     __builtin_amdgcn_sched_barrier(0);
   }
+  // The same two phases for a tile of 128 rows: two activation frags per unit, accumulators acc[i][0..1].
+  __device__ __forceinline__ void fetch_half() {
+    const unsigned aA = rdAh + slot * G_STEP, aW = rdW + slot * G_STEP;
+    slot = (slot + 1) & (G_SLOTS - 1);
+    R.Wa0 = lds_read<0 * FRAG_BYTES>(aW);
+    R.Wa1 = lds_read<1 * FRAG_BYTES>(aW);
+    R.A0 = lds_read<0 * FRAG_BYTES>(aA);
+    R.A1 = lds_read<1 * FRAG_BYTES>(aA);
+    R.Wb0 = lds_read<G_UNIT + 0 * FRAG_BYTES>(aW);
+    R.Wb1 = lds_read<G_UNIT + 1 * FRAG_BYTES>(aW);
+    R.B0 = lds_read<G_UNIT + 0 * FRAG_BYTES>(aA);
+    R.B1 = lds_read<G_UNIT + 1 * FRAG_BYTES>(aA);
+  }
+  template <bool FIRST>
+  __device__ __forceinline__ void compute_half(f32x16 (&acc)[2][4]) {
+    ++done;
+    f32x16 z;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) z[e] = 0.f;
+    lgkm_wait<4>(R.A0, R.A1, R.Wa0, R.Wa1);
+    acc[0][0] = mfma32(as_bf16x8(R.Wa0), as_bf16x8(R.A0), FIRST ? z : acc[0][0]);
+    acc[1][0] = mfma32(as_bf16x8(R.Wa1), as_bf16x8(R.A0), FIRST ? z : acc[1][0]);
+    acc[0][1] = mfma32(as_bf16x8(R.Wa0), as_bf16x8(R.A1), FIRST ? z : acc[0][1]);
+    acc[1][1] = mfma32(as_bf16x8(R.Wa1), as_bf16x8(R.A1), FIRST ? z : acc[1][1]);
+    __builtin_amdgcn_sched_barrier(0);
+    lgkm_wait<0>(R.B0, R.B1, R.Wb0, R.Wb1);
+    acc[0][0] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.B0), acc[0][0]);
+    acc[1][0] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.B0), acc[1][0]);
+    acc[0][1] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.B1), acc[0][1]);
+    acc[1][1] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.B1), acc[1][1]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
 };
 
 // End of a memory phase: this wave's copies of the next step have landed (those of the step after it, if it has
@@ -154,6 +187,13 @@ __device__ __forceinline__ void g_tile_of(int id, int MT, int NT, int mx, int ng
   }
 }
 
+// 16 bytes per lane to a wave-uniform base plus a 32-bit per-lane offset (no 64-bit vector address arithmetic).
+// The data registers of a store wider than 8 bytes must not be rewritten by the vector ALU in the next two issue
+// slots; the compiler cannot see into the asm, so the wait states are part of it.
+__device__ __forceinline__ void store16_sv(char* sbase, unsigned voff, const u32x4& v) {
+  asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(voff), "v"(v), "s"(sbase) : "memory");
+}
+
 __device__ __forceinline__ unsigned silu_pair(float g0, float g1) {
   const float s0 = g0 * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g0 * -1.44269504088896f));
   const float s1 = g1 * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g1 * -1.44269504088896f));
@@ -174,21 +214,51 @@ __device__ __forceinline__ unsigned mul_pair(unsigned sp, float p0, float p1) {
 // H = SiLU(Tg Vg) .* (Tu Vu)   (paper Alg. 3, second loop nest and gating epilogue)
 // T: per 32-row tile the gate strip's KB frags then the up strip's (as written by k_s1).
 // wVg, wVu: [ffn tile][KB] frags.  H: [32-row tile][ffn / 16] chain-order frags.
-// Persistent: workgroup b works on tiles b, b + gridDim.x, ...; the copy stream runs on into the next tile and a
+// Persistent: a workgroup works through its tiles (GuSched); the copy stream runs on into the next tile and a
 // finished tile's stores are not waited for.
 // ------------------------------------------------------------------------------------------------
+// Tiles of one workgroup of k_gate_up.  ntiles = G q + rem tiles go to G workgroups.  If at most half of the
+// workgroups would get a tile in the last round, the rem leftover tiles are cut into upper and lower halves
+// (128 rows each) and given to 2 rem workgroups of a second launch (HALF): the last round then costs about half a
+// tile's time instead of a whole one.  Full launch: workgroup b takes tiles b, b + G, ... below `ntiles`.
+// Half launch: workgroup b takes one half of one of the tiles first .. first + rem - 1.
+template <bool HALF>
+struct GuSched {
+  int b, G, ntiles, first, rem;
+  __device__ __forceinline__ void init(int b_, int G_, int ntiles_, int first_, int rem_) {
+    b = b_; G = G_; ntiles = ntiles_; first = first_; rem = rem_;
+  }
+  __device__ __forceinline__ int count() const { return HALF ? 1 : (b < ntiles ? (ntiles - 1 - b) / G + 1 : 0); }
+  // k-th tile of this workgroup: id, and hh = -1 for a full tile, 0 / 1 for the upper / lower half
+  __device__ __forceinline__ void tile(int k, int& id, int& hh) const {
+    if (!HALF) {
+      id = b + k * G;
+      hh = -1;
+    } else if (rem % 8 == 0) {  // both halves of a tile on one XCD, the one its id maps to
+      id = first + 8 * (b / 16) + b % 8;
+      hh = (b / 8) % 2;
+    } else {
+      id = first + b / 2;
+      hh = b % 2;
+    }
+  }
+};
+
 struct GuTile {
   const char* pa_g;  // this wave's copy sources: gate strip / up strip of its row tile, gate / up frags of its column tile
   const char* pa_u;
   const char* pw_g;
   const char* pw_u;
 };
-__device__ __forceinline__ GuTile gu_tile(int id, int w, const char* T, const char* wVg, const char* wVu, long long strip, int MT,
-                                          int NT, int mx, int ngm) {
+// hh < 0: full tile, wave w copies activation frag w.  Half tile: the four activation frags are copied twice
+// (waves w and w + 4 copy the same one), which keeps every wave at two copies per unit.
+__device__ __forceinline__ GuTile gu_tile(int id, int hh, int w, const char* T, const char* wVg, const char* wVu, long long strip,
+                                          int MT, int NT, int mx, int ngm) {
   int mt, nt;
   g_tile_of(id, MT, NT, mx, ngm, mt, nt);
+  const int af = hh < 0 ? w : 4 * hh + w % 4;
   GuTile t;
-  t.pa_g = T + (long long)(8 * mt + w) * 2 * strip;
+  t.pa_g = T + (long long)(8 * mt + af) * 2 * strip;
   t.pa_u = t.pa_g + strip;
   t.pw_g = wVg + (long long)(8 * nt + w) * strip;
   t.pw_u = wVu + (long long)(8 * nt + w) * strip;
@@ -196,15 +266,24 @@ __device__ __forceinline__ GuTile gu_tile(int id, int w, const char* T, const ch
 }
 
 // producer of k_gate_up: walks gate units, up units, then the next tile of this workgroup
+template <bool HALF>
 struct GuProd {
   GProd prod;
   GuTile pt;
+  GuSched<HALF> sched;
   const char* T;
   const char* wVg;
   const char* wVu;
   long long strip;
-  int w, MT, NT, mx, ngm, KB, half, ntiles, total_steps, stride;
-  int p_tile, p_step;
+  int w, MT, NT, mx, ngm, KB, half, total_steps;
+  int p_k, p_step;
+  __device__ __forceinline__ void load_tile() {
+    int id, hh;
+    sched.tile(p_k, id, hh);
+    pt = gu_tile(id, hh, w, T, wVg, wVu, strip, MT, NT, mx, ngm);
+    prod.pa = pt.pa_g;
+    prod.pw = pt.pw_g;
+  }
   __device__ __forceinline__ void produce() {
     if (prod.issued < total_steps) {
       prod.step();
@@ -214,34 +293,29 @@ struct GuProd {
         prod.pw = pt.pw_u;
       } else if (p_step == KB) {
         p_step = 0;
-        p_tile += stride;
-        if (p_tile < ntiles) {
-          pt = gu_tile(p_tile, w, T, wVg, wVu, strip, MT, NT, mx, ngm);
-          prod.pa = pt.pa_g;
-          prod.pw = pt.pw_g;
-        }
+        ++p_k;
+        if (p_k < sched.count()) load_tile();
       }
     }
   }
 };
 
+template <bool HALF>
 __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ T, const char* __restrict__ wVg,
                                                        const char* __restrict__ wVu, char* __restrict__ H, int KB, int KBf,
-                                                       int MT, int NT, int mx, int ngm) {
+                                                       int MT, int NT, int mx, int ngm, int ntiles, int first, int rem) {
   __shared__ __attribute__((aligned(1024))) char lds[G_LDS];
   const int lane = threadIdx.x % 64;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const int wm = w / 4, wn = w % 4;
   const unsigned lds_off = lds_offset_of(lds);
   const long long strip = (long long)KB * FRAG_BYTES;
-  const int ntiles = MT * NT;
-  const int my_tiles = ((int)blockIdx.x < ntiles) ? (ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
-  const int half = KB / 2;               // steps per phase
-  const int total_steps = my_tiles * KB;  // two phases per tile
 
   // producer: position in the stream
-  GuProd gp;
+  GuProd<HALF> gp;
   GProd& prod = gp.prod;
+  gp.sched.init(blockIdx.x, gridDim.x, ntiles, first, rem);
+  const int my_tiles = gp.sched.count();
   prod.a_kb = FRAG_BYTES;
   prod.w_kb = FRAG_BYTES;
   prod.lane16 = lane * 16;
@@ -252,15 +326,16 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
   gp.T = T; gp.wVg = wVg; gp.wVu = wVu;
   gp.strip = strip;
   gp.w = w; gp.MT = MT; gp.NT = NT; gp.mx = mx; gp.ngm = ngm;
-  gp.KB = KB; gp.half = half; gp.ntiles = ntiles; gp.total_steps = total_steps; gp.stride = gridDim.x;
-  gp.p_tile = blockIdx.x;
+  const int half = KB / 2;
+  gp.KB = KB; gp.half = half;            // steps per tile (two phases), steps per phase
+  gp.total_steps = my_tiles * KB;
+  gp.p_k = 0;
   gp.p_step = 0;
-  gp.pt = gu_tile(gp.p_tile, w, T, wVg, wVu, strip, MT, NT, mx, ngm);
-  prod.pa = gp.pt.pa_g;
-  prod.pw = gp.pt.pw_g;
+  if (my_tiles > 0) gp.load_tile();
 
   GCons cons;
   cons.rdA = lds_off + lane * 16 + 4 * wm * FRAG_BYTES;
+  cons.rdAh = lds_off + lane * 16 + 2 * wm * FRAG_BYTES;
   cons.rdW = lds_off + lane * 16 + (8 + 2 * wn) * FRAG_BYTES;
   cons.slot = 0;
   cons.done = 0;
@@ -274,29 +349,38 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
 
   f32x16 acc[2][4];
   u32x4 S[16];  // SiLU(G) as bf16 pairs, frag by frag, while the up tile is accumulated
-  int c_tile = blockIdx.x;
-  for (int t = 0; t < my_tiles; ++t, c_tile += gridDim.x) {
-    int mt, nt;
-    g_tile_of(c_tile, MT, NT, mx, ngm, mt, nt);
-    char* hbase = H + (((long long)(8 * mt + 4 * wm)) * KBf + 2 * (8 * nt + 2 * wn)) * FRAG_BYTES;
+  for (int k = 0; k < my_tiles; ++k) {
+    int id, hh, mt, nt;
+    gp.sched.tile(k, id, hh);
+    g_tile_of(id, MT, NT, mx, ngm, mt, nt);
+    // One tile: gate phase, SiLU, up phase, H out.  HALF: 128 rows; wave (wm, wn) then owns rows 64 wm.. of the half.
+    char* hbase = H + (((long long)(8 * mt + (HALF ? 4 * hh + 2 * wm : 4 * wm))) * KBf + 2 * (8 * nt + 2 * wn)) * FRAG_BYTES;
+    constexpr int NB = HALF ? 2 : 4;
     // ---- gate phase ----
     for (int i = 0; i < half; ++i) {
       gp.produce();
-      cons.fetch();
-      g_certify(prod, cons);
-      if (i == 0) cons.compute<true>(acc);
-      else cons.compute<false>(acc);
+      if (HALF) cons.fetch_half();
+      else cons.fetch();
+      g_certify(gp.prod, cons);
+      if (HALF) {
+        if (i == 0) cons.compute_half<true>(acc);
+        else cons.compute_half<false>(acc);
+      } else {
+        if (i == 0) cons.compute<true>(acc);
+        else cons.compute<false>(acc);
+      }
       lds_barrier();
     }
     // ---- up phase ----
     for (int i = 0; i < half; ++i) {
       gp.produce();
-      cons.fetch();
+      if (HALF) cons.fetch_half();
+      else cons.fetch();
       if (i == 0) {  // SiLU(G), rounded to bf16 pairs; runs under the other wave's compute phase
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
-          for (int b = 0; b < 4; ++b)
+          for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int t2 = 0; t2 < 2; ++t2) {
               u32x4 v;
@@ -306,9 +390,14 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
               S[(a * 4 + b) * 2 + t2] = v;
             }
       }
-      g_certify(prod, cons);
-      if (i == 0) cons.compute<true>(acc);
-      else cons.compute<false>(acc);
+      g_certify(gp.prod, cons);
+      if (HALF) {
+        if (i == 0) cons.compute_half<true>(acc);
+        else cons.compute_half<false>(acc);
+      } else {
+        if (i == 0) cons.compute<true>(acc);
+        else cons.compute<false>(acc);
+      }
       lds_barrier();
     }
     // H = SiLU(G) .* P rounded to bf16: registers 8t..8t+7 of tile (a, b) are the frag of ffn contraction block
@@ -316,13 +405,13 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
           u32x4 v = S[(a * 4 + b) * 2 + t2];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = mul_pair(v[e], acc[a][b][8 * t2 + 2 * e], acc[a][b][8 * t2 + 2 * e + 1]);
-          *reinterpret_cast<u32x4*>(hbase + ((long long)b * KBf + 2 * a + t2) * FRAG_BYTES + prod.lane16) = v;
+          store16_sv(hbase + ((long long)b * KBf + 2 * a + t2) * FRAG_BYTES, gp.prod.lane16, v);
         }
   }
   if (w < 4) lds_barrier();  // matches the extra barrier of waves 4..7
@@ -504,9 +593,17 @@ int launch_gate_up(const Ctx* c, int MT256, hipStream_t st) {
     break;
   }
   const int ncu = c->n_cus > 0 ? c->n_cus : 256;
-  const int grid = MT256 * NT < ncu ? MT256 * NT : ncu;  // persistent: one workgroup per CU
-  hipLaunchKernelGGL(k_gate_up, dim3(grid), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
-                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, mx, ngm);
+  const int ntiles = MT256 * NT;
+  const int G = ntiles < ncu ? ntiles : ncu;  // persistent: one workgroup per CU
+  const int q = ntiles / G, rem = ntiles % G;
+  const bool halves = rem > 0 && 2 * rem <= G && q > 0;  // see GuSched
+  const int nfull = halves ? q * G : ntiles;
+  hipLaunchKernelGGL(k_gate_up<false>, dim3(G), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
+                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, mx, ngm, nfull, 0, 0);
+  int e = (int)hipGetLastError();
+  if (e || !halves) return e;
+  hipLaunchKernelGGL(k_gate_up<true>, dim3(2 * rem), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
+                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, mx, ngm, ntiles, nfull, rem);
   return (int)hipGetLastError();
 }
 
