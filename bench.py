@@ -32,6 +32,15 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
+# HBM-side bytes per forward of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
+# scaled by a plain copy of known size (profiles/prefill_r512_pmc_traffic_mfma.txt); key = (kernel, M, d, ffn, r)
+MEASURED_TRAFFIC = {
+    ("k_gate_up", 4096, 4096, 14336, 512): {"read_MB": 184.9, "written_MB": 117.4, "algorithmic_read_MB": 37.7,
+                                            "algorithmic_written_MB": 117.4,
+                                            "source": "profiles/prefill_r512_pmc_traffic_mfma.txt"},
+}
+
+
 def time_steps(fn, steps, warmup):
     for _ in range(warmup):
         fn()
@@ -239,7 +248,8 @@ def main():
         k_flops = kflops[kname]
         out["roofline"] = {"bound": "mfma", "kernel": kname, "achieved": k_flops / k_ms / 1e9 if k_ms else None,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": k_flops / k_ms / 1e9 / PEAK_BF16_TFLOPS if k_ms else None, "traffic": None,
+                           "frac": k_flops / k_ms / 1e9 / PEAK_BF16_TFLOPS if k_ms else None,
+                           "traffic": MEASURED_TRAFFIC.get((kname, M, d, ffn, r)),
                            "per_kernel_TFLOPs": {k: kflops[k] / v / 1e9 for k, v in cand.items() if v}}
 
     if dec is not None:
