@@ -81,6 +81,29 @@ def bench_forward(gi, dev, steps, warmup, profile=True, flags=0):
     return ms, wall_ms, kernels, path, ms_ev
 
 
+def bench_xuv(dev, M, steps, warmup, dense=True):
+    """Stand-alone factored layer O = (X U) V at the shape of the paper's kernel evaluation (Sec. 5.2:
+    X[M,8192] U[8192,4096] V[4096,16384]); FLOPs 2 M r (d + n).  Beside it the dense X W product (third party)."""
+    d, r, n = 8192, 4096, 16384
+    li = synth.make_linear_gaussian(M, d, n, r)
+    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dev), Vg=li.V.to(dev), kind=B.SVDMLP_LINEAR, keep_factors=False)
+    X = li.X.to(dev)
+    O = torch.empty((M, n), dtype=torch.bfloat16, device=dev)
+    ms, wall_ms = time_steps(lambda: mlp(X, O), steps, warmup)
+    B.svdmlp_profile_begin(mlp.ctx, steps)
+    ms_ev, _ = time_steps(lambda: mlp(X, O), steps, 0)
+    kernels, _ = B.svdmlp_profile_end(mlp.ctx)
+    path = mlp.last_path
+    mlp.close()
+    out = dict(M=M, d=d, r=r, n=n, ms=ms, wall_ms=wall_ms, ms_ev=ms_ev, kernels=kernels, path=path, flops=2 * M * r * (d + n))
+    if dense:
+        W = torch.randn((d, n), dtype=torch.bfloat16, device=dev) * (d ** -0.5)
+        dms, _ = time_steps(lambda: torch.matmul(X, W, out=O), max(5, steps // 3), 3)
+        out["dense"] = dict(ms_per_step=dms, TFLOPs=2 * M * d * n / dms / 1e9, flops=2 * M * d * n,
+                            provider="torch.matmul (third-party GEMM)")
+    return out
+
+
 def copy_calibration(dev, reps=5):
     """A plain device-to-device copy of known size (256 MiB read + 256 MiB written per launch)."""
     n = 256 << 20
@@ -167,7 +190,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="prefill", choices=["prefill", "wide", "mlp_small", "decode"])
+    ap.add_argument("--workload", default="prefill", choices=["prefill", "wide", "mlp_small", "decode", "xuv"])
     ap.add_argument("--r", type=int, default=None)
     ap.add_argument("--M", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -189,6 +212,27 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     B.lib()  # fail loudly if the HIP library is missing
+
+    if args.workload == "xuv":
+        x = bench_xuv(dev, args.M or 4096, args.steps, args.warmup, dense=not args.no_dense)
+        k = x["kernels"]
+        kfl = {"k_s1": 2 * x["M"] * x["d"] * x["r"], "k_out": 2 * x["M"] * x["r"] * x["n"]}
+        kname = max(k, key=k.get)
+        out = {"metric": METRIC, "value": x["flops"] / x["ms"] / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+               "warmup": args.warmup, "ms_per_step": x["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+               "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": f"xuv: factored layer (X U) V, X[{x['M']},{x['d']}] U[{x['d']},{x['r']}] V[{x['r']},{x['n']}]",
+                          "path": "k_s1 + k_out"},
+               "flops_per_step": x["flops"], "frac_of_bf16_mfma_peak": x["flops"] / x["ms"] / 1e9 / PEAK_BF16_TFLOPS,
+               "wall_ms_per_step": x["wall_ms"], "ms_per_step_with_kernel_events": x["ms_ev"], "kernels_ms": k,
+               "roofline": {"bound": "mfma", "kernel": kname, "achieved": kfl[kname] / k[kname] / 1e9, "peak": PEAK_BF16_TFLOPS,
+                            "unit": "TFLOP/s", "frac": kfl[kname] / k[kname] / 1e9 / PEAK_BF16_TFLOPS, "traffic": None,
+                            "per_kernel_TFLOPs": {n_: kfl[n_] / v / 1e9 for n_, v in k.items() if v}}}
+        if "dense" in x:
+            out["dense_baseline"] = x["dense"]
+            out["dense_baseline"]["speedup_of_factored"] = x["dense"]["ms_per_step"] / x["ms"]
+        print(json.dumps(out))
+        return
 
     gi = synth.make_workload(args.workload, M=args.M, r=args.r)
     dims = gi.dims

@@ -43,7 +43,7 @@ typedef struct svdmlp_ctx svdmlp_ctx; /* opaque; host memory only */
  *   F32 : debug path, fp32 storage and fp32 arithmetic everywhere, no matrix cores. */
 enum { SVDMLP_BF16 = 0, SVDMLP_F32 = 1 };
 
-/* GATED: Alg. 2.  LINEAR: Sec. 4.2.1 (fp32 debug path only). */
+/* GATED: Alg. 2.  LINEAR: the single factored layer O = (X U) V of Sec. 4.2.1 (bf16: d, ffn, r multiples of 128). */
 enum { SVDMLP_GATED = 0, SVDMLP_LINEAR = 1 };
 
 /* Status codes (0 = success, negative = failure). */
@@ -117,7 +117,8 @@ int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
  * 2 bf16 MFMA-tiled (prefill) with the gated activation kept in registers (SVDMLP_FLAG_TILED_FUSED, or extents the
  * staged variant does not take: it needs ffn and r_down to be multiples of 256), 3 bf16 weight-streaming (decode) as
  * four launches, 4 bf16 weight-streaming as one persistent kernel (SVDMLP_FLAG_STREAM_ONE_KERNEL), 5 bf16
- * MFMA-tiled with the gated activation staged through the workspace (the default for large M). */
+ * MFMA-tiled with the gated activation staged through the workspace (the default for large M), 6 bf16 single
+ * factored layer (SVDMLP_LINEAR). */
 int svdmlp_last_path(const svdmlp_ctx *ctx);
 
 /* Per-kernel timing for benchmarks.  svdmlp_profile_begin creates a pool of HIP events for up to

@@ -55,7 +55,19 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   }
 
   // ---- bf16 ----
-  if (!gated) return SVDMLP_UNSUPPORTED;  // the single factored linear layer is offered on the fp32 path only
+  if (!gated) {
+    // single factored layer O = (X U) V: the first and the last kernel of the tiled path back to back
+    const int64_t d = de->d, n = de->ffn, r = de->r;
+    if (d % 128 || n % 128 || r % 128) return SVDMLP_UNSUPPORTED;
+    p->Mpad = (de->max_M + 255) / 256 * 256;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    p->off_wU = take((size_t)r * d * 2);
+    p->off_wVd = take((size_t)n * r * 2);
+    p->off_T = take((size_t)p->Mpad * r * 2);
+    p->total_bytes = off;
+    return SVDMLP_OK;
+  }
   const int64_t d = de->d, ffn = de->ffn, r = de->r, rd = p->rd;
   if (d % 128 || ffn % 128 || r % 64 || r < 128) return SVDMLP_UNSUPPORTED;
   const int64_t nq = rd / 32;
@@ -178,6 +190,9 @@ int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip
   if (c->plan.dtype == SVDMLP_F32) {
     c->last_path = 1;
     e = f32_forward(c, X, M, Y, st);
+  } else if (c->plan.kind == SVDMLP_LINEAR) {
+    c->last_path = 6;
+    e = bf16_linear_forward(c, X, M, Y, st);
   } else {
     bool stream_path = M <= 32;
     if (c->plan.flags & SVDMLP_FLAG_FORCE_TILED) stream_path = false;

@@ -616,13 +616,19 @@ int launch_down1(const Ctx* c, int MT256, int splits, hipStream_t st) {
   return (int)hipGetLastError();
 }
 
+// act: [32-row tile][k / 16] chain-order frags; w: [32-column tile][k / 16] frags; Y row-major [M, n], n % 256 == 0
+int launch_out_generic(const Ctx* c, const char* act, const char* w, int64_t M, void* Y, int MT256, int64_t n, int64_t k,
+                       hipStream_t st) {
+  (void)c;
+  const int CT = (int)(n / 256);
+  hipLaunchKernelGGL(k_out, dim3(MT256 * CT), dim3(G_THREADS), 0, st, act, w, (uint16_t*)Y, (int)M, (int)n, (int)(k / 16),
+                     MT256, CT);
+  return (int)hipGetLastError();
+}
+
 int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st) {
   const Plan& p = c->plan;
-  char* ws = c->ws;
-  const int CT = (int)(p.d / 256);
-  hipLaunchKernelGGL(k_out, dim3(MT256 * CT), dim3(G_THREADS), 0, st, ws + p.off_Td, ws + p.off_wVd, (uint16_t*)Y, (int)M,
-                     (int)p.d, (int)(p.rd / 16), MT256, CT);
-  return (int)hipGetLastError();
+  return launch_out_generic(c, c->ws + p.off_Td, c->ws + p.off_wVd, M, Y, MT256, p.d, p.rd, st);
 }
 
 }  // namespace svdmlp

@@ -48,6 +48,12 @@ int bf16_repack_all(const Ctx* c, hipStream_t st) {
   const svdmlp_desc& de = c->desc;
   char* ws = c->ws;
   int e;
+  if (p.kind == SVDMLP_LINEAR) {
+    // U^T: rows p in [0, r), contraction over d, meets row-major X -> natural order; V^T: rows n in [0, ffn),
+    // contraction over r, meets T produced by an MFMA -> chain order
+    if ((e = repack(de.Ug, p.d, p.r, ws + p.off_wU, ORDER_NATURAL, TILE_MAJOR, 0, (int)(p.r / 32), st))) return e;
+    return repack(de.Vg, p.r, p.ffn, ws + p.off_wVd, ORDER_CHAIN, TILE_MAJOR, 0, (int)(p.ffn / 32), st);
+  }
   // [Ug | Uu]^T: rows p in [0, 2r), contraction over d, meets X read from row-major memory -> natural order
   const int pt = (int)(2 * p.r / 32);
   if ((e = repack(de.Ug, p.d, p.r, ws + p.off_wU, ORDER_NATURAL, TILE_MAJOR, 0, pt, st))) return e;

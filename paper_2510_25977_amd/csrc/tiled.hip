@@ -631,6 +631,34 @@ static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st)
   return e;
 }
 
+// Single factored layer O = (X U) V  (paper Sec. 4.2.1, the XUV product): k_s1 with the rank split in two equal
+// "strips" lays T out as [32-row tile][r / 16] chain-order frags, which is what the output kernels read.
+int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
+  const Plan& p = c->plan;
+  char* ws = c->ws;
+  const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
+  const int PT = (int)(p.r / 128);
+  static const char* const names[2] = {"k_s1", "k_out"};
+  const int ps = prof_open_forward(c, 2, names);
+  int e;
+  prof_mark(c, ps, 0, 0, st);
+  hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
+                     (int)(p.r / 2), ws + p.off_T, PT);
+  prof_mark(c, ps, 0, 1, st);
+  if ((e = (int)hipGetLastError())) return e;
+  prof_mark(c, ps, 1, 0, st);
+  if (p.ffn % 256 == 0) {
+    e = launch_out_generic(c, ws + p.off_T, ws + p.off_wVd, M, Y, MT256, p.ffn, p.r, st);
+  } else {
+    const int CT = (int)(p.ffn / 128);
+    hipLaunchKernelGGL(k_s5, dim3(MT128 * CT), dim3(256), 0, st, ws + p.off_T, ws + p.off_wVd, (uint16_t*)Y, (int)M,
+                       (int)p.ffn, (int)p.r, CT);
+    e = (int)hipGetLastError();
+  }
+  prof_mark(c, ps, 1, 1, st);
+  return e;
+}
+
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;

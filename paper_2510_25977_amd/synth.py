@@ -110,8 +110,8 @@ class LinearInputs:
     X: torch.Tensor      # [M, d]
     U: torch.Tensor      # [d, r]
     V: torch.Tensor      # [r, n]
-    W: np.ndarray        # [d, n] float64, the full-rank matrix before truncation / rounding
-    s: np.ndarray        # singular values of W (float64, descending)
+    W: Optional[np.ndarray] = None   # [d, n] float64, the full-rank matrix before truncation / rounding
+    s: Optional[np.ndarray] = None   # singular values of W (float64, descending)
 
 
 def make_linear_powerlaw(M: int = 32, d: int = 256, n: int = 1024, r: int = 16, *, stream: int = 1,
@@ -132,6 +132,14 @@ def make_linear_powerlaw(M: int = 32, d: int = 256, n: int = 1024, r: int = 16, 
     V = Q2[:, :r].T
     X = _normal(stream, "X", (M, d), 1.0)
     return LinearInputs(X=_store(X, dtype), U=_store(U, dtype), V=_store(V, dtype), W=W, s=s)
+
+
+def make_linear_gaussian(M: int, d: int, n: int, r: int, *, stream: int = 6, dtype: torch.dtype = torch.bfloat16) -> LinearInputs:
+    """Stand-alone factored layer O = (X U) V with Gaussian factors: U ~ N(0, 1/d), V ~ N(0, 1/r), X ~ N(0, 1)
+    (so T = X U and O are O(1) per entry).  The shape of the paper's kernel evaluation (Sec. 5.2) is
+    d = 8192, r = 4096, n = 16384."""
+    return LinearInputs(X=_store(_normal(stream, "X", (M, d), 1.0), dtype), U=_store(_normal(stream, "Ug", (d, r), 1.0 / d), dtype),
+                        V=_store(_normal(stream, "Vg", (r, n), 1.0 / r), dtype))
 
 
 # ----------------------------------------------------------------------------------------------

@@ -71,6 +71,9 @@ def test_workspace_bytes_formula(lib):
     assert B.svdmlp_workspace_bytes(d32) >= 4 * 10 * (48 + 200 + 40)
     dl = desc(dtype=B.SVDMLP_F32, kind=B.SVDMLP_LINEAR, max_M=32, d=256, ffn=1024, r=16, r_down=0)
     assert 0 < B.svdmlp_workspace_bytes(dl) <= 4 * 32 * 16 + 256
+    # bf16 LINEAR: re-tiled U and V + the rank-r strip of 256-row-padded M
+    db = desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=1024, r=256, r_down=0)
+    assert B.svdmlp_workspace_bytes(db) == 2 * (256 * 512 + 1024 * 256 + 512 * 256)
 
 
 @pytest.mark.parametrize("kw,status", [
@@ -89,7 +92,7 @@ def test_workspace_bytes_formula(lib):
     (dict(r=48), B.SVDMLP_UNSUPPORTED),                        # bf16 needs r % 64 == 0
     (dict(r=64), B.SVDMLP_UNSUPPORTED),                        # ... and r >= 128
     (dict(r_down=192), B.SVDMLP_UNSUPPORTED),                  # r_down / 32 must be 2,4,8,16 or r_down % 512 == 0
-    (dict(kind=B.SVDMLP_LINEAR), B.SVDMLP_UNSUPPORTED),        # LINEAR is fp32 only
+    (dict(kind=B.SVDMLP_LINEAR, r=64), B.SVDMLP_UNSUPPORTED),  # bf16 LINEAR needs r % 128 == 0
     (dict(flags=B.FLAG_SKIP_ARCH_CHECK | B.FLAG_FORCE_TILED | B.FLAG_FORCE_STREAM), B.SVDMLP_INVALID_ARGUMENT),
 ])
 def test_create_rejects_bad_descriptions(lib, kw, status):

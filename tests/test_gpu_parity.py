@@ -110,6 +110,42 @@ def test_bf16_staged_small(M, d, ffn, r, rd):
     assert relmax(Y, Yf) <= BF16_TOL
 
 
+# ---------------------------------------------------------------------------------- bf16 single factored layer
+@pytest.mark.parametrize("M,d,n,r", [
+    (70, 256, 512, 128),       # one row tile, mostly padding
+    (300, 384, 640, 256),      # n not a multiple of 256: 128-column output kernel
+    (513, 1024, 768, 384),     # three 256-row tiles, r not a power of two
+])
+def test_bf16_linear_small(M, d, n, r):
+    """O = (X U) V in bf16 (path 6) against the oracle's plain chain."""
+    li = synth.make_linear_gaussian(M, d, n, r, stream=41)
+    dv = dev()
+    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
+    O = mlp(li.X.to(dv))
+    torch.cuda.synchronize()
+    assert mlp.last_path == 6 and tuple(O.shape) == (M, n)
+    Oh = O.cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Oh, ref) <= BF16_TOL, (relmax(Oh, ref), relfro(Oh, ref))
+    assert relfro(Oh, ref) <= 1.5e-2
+
+
+def test_bf16_linear_paper_kernel_shape_sampled_rows():
+    """The paper's kernel-evaluation shape X[M,8192] U[8192,4096] V[4096,16384] (Sec. 5.2) at M = 1024; the
+    oracle evaluates a sample of rows."""
+    li = synth.make_linear_gaussian(1024, 8192, 16384, 4096, stream=42)
+    dv = dev()
+    mlp = B.SvdMlp(max_M=1024, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR, keep_factors=False)
+    O = mlp(li.X.to(dv))
+    torch.cuda.synchronize()
+    rows = [0, 31, 32, 255, 256, 700, 1023]
+    Oh = O[rows].cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.linear(synth.to_f64(li.X)[rows], synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
+
+
 # ---------------------------------------------------------------------------------- bf16 streaming path
 @pytest.mark.parametrize("M", [1, 4, 16, 32, 7])
 @pytest.mark.parametrize("d,ffn,r,rd", [(256, 512, 128, 128), (512, 1408, 192, 256)])
