@@ -216,13 +216,13 @@ def main():
     if args.workload == "xuv":
         x = bench_xuv(dev, args.M or 4096, args.steps, args.warmup, dense=not args.no_dense)
         k = x["kernels"]
-        kfl = {"k_s1": 2 * x["M"] * x["d"] * x["r"], "k_out": 2 * x["M"] * x["r"] * x["n"]}
+        kfl = {"k_s1": 2 * x["M"] * x["d"] * x["r"], "k_in": 2 * x["M"] * x["d"] * x["r"], "k_out": 2 * x["M"] * x["r"] * x["n"]}
         kname = max(k, key=k.get)
         out = {"metric": METRIC, "value": x["flops"] / x["ms"] / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
                "warmup": args.warmup, "ms_per_step": x["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
                "dtype": "bf16", "data": "synthetic",
                "config": {"workload": f"xuv: factored layer (X U) V, X[{x['M']},{x['d']}] U[{x['d']},{x['r']}] V[{x['r']},{x['n']}]",
-                          "path": "k_s1 + k_out"},
+                          "path": " + ".join(k)},
                "flops_per_step": x["flops"], "frac_of_bf16_mfma_peak": x["flops"] / x["ms"] / 1e9 / PEAK_BF16_TFLOPS,
                "wall_ms_per_step": x["wall_ms"], "ms_per_step_with_kernel_events": x["ms_ev"], "kernels_ms": k,
                "roofline": {"bound": "mfma", "kernel": kname, "achieved": kfl[kname] / k[kname] / 1e9, "peak": PEAK_BF16_TFLOPS,
@@ -281,7 +281,7 @@ def main():
                            "note": "per-kernel time from the warm single-set run"}
     else:
         rd = dims.get("r_down", r)
-        kflops = {"k_s1": 2 * M * d * 2 * r,                # X [Ug|Uu]
+        kflops = {"k_s1": 2 * M * d * 2 * r, "k_in": 2 * M * d * 2 * r,   # X [Ug|Uu]
                   "k_fused": 4 * M * ffn * r + 2 * M * ffn * rd,   # gate + up second stage, down first stage
                   "k_gate_up": 4 * M * ffn * r,             # gate + up second stage
                   "k_down1": 2 * M * ffn * rd,              # down first stage

@@ -80,6 +80,7 @@ struct GCons {
   GRegs R;
   unsigned rdA, rdW;  // per-lane LDS read addresses in slot 0
   unsigned rdAh;      // ... of the activation frags when the tile has 128 rows (k_gate_up's half tiles)
+  unsigned rdX0, rdX1;  // ... of this lane's 16-byte pieces of row-major activation rows (k_in), first / second unit
   int slot;           // slot of the step that is read next
   int done;           // steps consumed
 
@@ -128,6 +129,27 @@ struct GCons {
     acc[0][3] = mfma32(as_bf16x8(R.Wb0), as_bf16x8(R.B3), acc[0][3]);
     acc[1][3] = mfma32(as_bf16x8(R.Wb1), as_bf16x8(R.B3), acc[1][3]);
     __builtin_amdgcn_sched_barrier(0);
+  }
+  // Memory phase when the activation comes straight from row-major memory (k_in): a step's activation part is
+  // 256 rows x 64 bytes, sixteen rows per KiB, the 16-byte pieces of a row XOR-swizzled by bits 2..3 of the row
+  // (so that a quarter wave's reads fall into distinct banks); rows 0..127 sit where the first unit's activation
+  // frags would, rows 128..255 in the second unit's place.  Piece 2 u + h of a row is natural-order half h of
+  // contraction block u.
+  __device__ __forceinline__ void fetch_x() {
+    const unsigned a0 = rdX0 + slot * G_STEP, a1 = rdX1 + slot * G_STEP, aW = rdW + slot * G_STEP;
+    slot = (slot + 1) & (G_SLOTS - 1);
+    R.Wa0 = lds_read<0 * FRAG_BYTES>(aW);
+    R.Wa1 = lds_read<1 * FRAG_BYTES>(aW);
+    R.A0 = lds_read<0 * FRAG_BYTES>(a0);
+    R.A1 = lds_read<2 * FRAG_BYTES>(a0);
+    R.A2 = lds_read<4 * FRAG_BYTES>(a0);
+    R.A3 = lds_read<6 * FRAG_BYTES>(a0);
+    R.Wb0 = lds_read<G_UNIT + 0 * FRAG_BYTES>(aW);
+    R.Wb1 = lds_read<G_UNIT + 1 * FRAG_BYTES>(aW);
+    R.B0 = lds_read<0 * FRAG_BYTES>(a1);
+    R.B1 = lds_read<2 * FRAG_BYTES>(a1);
+    R.B2 = lds_read<4 * FRAG_BYTES>(a1);
+    R.B3 = lds_read<6 * FRAG_BYTES>(a1);
   }
   // The same two phases for a tile of 128 rows: two activation frags per unit, accumulators acc[i][0..1].
   __device__ __forceinline__ void fetch_half() {
@@ -487,6 +509,97 @@ __global__ __launch_bounds__(G_THREADS) void k_down1(const char* __restrict__ H,
 }
 
 // ------------------------------------------------------------------------------------------------
+// T = X [Ug | Uu]   (paper Alg. 3, first loop nest; for kind LINEAR: T = X U), 256 rows x 256 rank columns per
+// workgroup, contraction over d.  X row-major [M, d] bf16; wU: [rank tile][d / 16] natural-order frags.
+// T: per 32-row tile two strips of r_strip / 16 chain-order frags each (rank columns below / from r_strip).
+// Used when there are enough 256 x 256 tiles to fill the chip; k_s1 (128 x 128 tiles) otherwise.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(G_THREADS) void k_in(const uint16_t* __restrict__ X, int M, int d, const char* __restrict__ wU,
+                                                  int r_strip, char* __restrict__ T, int MT, int PT) {
+  __shared__ __attribute__((aligned(1024))) char lds[G_LDS];
+  const int lane = threadIdx.x % 64;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+  const int wm = w / 4, wn = w % 4;
+  const int L = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int pt = L % PT, mt = L / PT;
+  const int KBd = d / 16, KBr = r_strip / 16;
+  const int total_steps = d / 32;
+  const unsigned lds_off = lds_offset_of(lds);
+
+  // producer: rows 16 w + lane / 4 of each half of the tile, one 16-byte piece per lane (rows beyond M re-read row
+  // M - 1; they only feed output rows that nobody uses)
+  const int rl = lane / 4, piece = (lane % 4) ^ ((lane >> 4) & 3);
+  int rowA = 256 * mt + 16 * w + rl, rowB = rowA + 128;
+  rowA = rowA < M ? rowA : M - 1;
+  rowB = rowB < M ? rowB : M - 1;
+  const unsigned voffA = (unsigned)rowA * (unsigned)d * 2u + piece * 16, voffB = (unsigned)rowB * (unsigned)d * 2u + piece * 16;
+  const char* bx = reinterpret_cast<const char*>(X);
+  const char* pw = wU + (long long)(8 * pt + w) * KBd * FRAG_BYTES;
+  const unsigned lane16 = lane * 16;
+  const unsigned dst = lds_off + w * FRAG_BYTES, dstw = lds_off + (8 + w) * FRAG_BYTES;
+  int pslot = 0, issued = 0;
+  auto produce = [&]() __attribute__((always_inline)) {
+    if (issued < total_steps) {
+      const unsigned b = dst + pslot * G_STEP, bw = dstw + pslot * G_STEP;
+      dma16_sv(bx, voffA, b);
+      dma16_sv(pw, lane16, bw);
+      dma16_sv(bx, voffB, b + G_UNIT);
+      dma16_sv(pw + FRAG_BYTES, lane16, bw + G_UNIT);
+      bx += 64;
+      pw += 2 * FRAG_BYTES;
+      pslot = (pslot + 1) & (G_SLOTS - 1);
+      ++issued;
+    }
+  };
+
+  GCons cons;
+  const int il = lane % 32, h = lane / 32, sw = (il >> 2) & 3;
+  const unsigned c0 = (il / 16) * FRAG_BYTES + (il % 16) * 64;
+  cons.rdX0 = lds_off + wm * G_UNIT + c0 + ((0 + h) ^ sw) * 16;
+  cons.rdX1 = lds_off + wm * G_UNIT + c0 + ((2 + h) ^ sw) * 16;
+  cons.rdW = lds_off + lane * 16 + (8 + 2 * wn) * FRAG_BYTES;
+  cons.slot = 0;
+  cons.done = 0;
+
+  produce();
+  produce();
+  if (issued >= 2) wait_vmcnt<4>();
+  else wait_vmcnt<0>();
+  if (w >= 4) lds_barrier();
+  lds_barrier();
+
+  f32x16 acc[2][4];
+  for (int i = 0; i < total_steps; ++i) {
+    produce();
+    cons.fetch_x();
+    if (issued >= cons.done + 3) wait_vmcnt<4>();
+    else wait_vmcnt<0>();
+    lds_barrier();
+    if (i == 0) cons.compute<true>(acc);
+    else cons.compute<false>(acc);
+    lds_barrier();
+  }
+  if (w < 4) lds_barrier();
+
+  // registers 8t..8t+7 of tile (i, j) are the chain-order frag of rank contraction block 2 (rank tile) + t, row tile j
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int p0 = 32 * (8 * pt + 2 * wn + i);
+    const int which = p0 >= r_strip ? 1 : 0;
+    const int kb0 = (p0 - which * r_strip) / 16;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const long long mtile = 8 * mt + 4 * wm + j;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const u32x4 v = __builtin_bit_cast(u32x4, pack_chain(acc[i][j], t));
+        store16_sv(T + ((mtile * 2 + which) * KBr + kb0 + t) * FRAG_BYTES, lane16, v);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Y = Td Vd   (second phase of the down-projection XUV kernel, Alg. 2), 256 rows x 256 columns per workgroup.
 // Td: [32-row tile][rd / 16] chain-order frags; wVd: [column tile][rd / 16] frags; Y row-major [M, d] bf16.
 // The accumulators hold the tile transposed (lane = row, registers = columns); each wave turns its 128 x 64 part
@@ -629,6 +742,22 @@ int launch_out_generic(const Ctx* c, const char* act, const char* w, int64_t M, 
 int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st) {
   const Plan& p = c->plan;
   return launch_out_generic(c, c->ws + p.off_Td, c->ws + p.off_wVd, M, Y, MT256, p.d, p.rd, st);
+}
+
+// ncols = rank columns of the product (2 r gated, r linear); r_strip = columns per strip of T
+bool in_supported(int64_t M, int64_t d, int64_t ncols) {
+  // 256 x 256 tiles must keep at least 70 % of the 256 CUs busy over their rounds (k_s1 with its 128 x 128 tiles
+  // reaches about 0.63 of this kernel's rate and fills the chip at any size); 32-bit byte offsets into X
+  if (ncols % 256 || d % 64 || M * d * 2 >= (int64_t(1) << 32)) return false;
+  const int64_t tiles = ((M + 255) / 256) * (ncols / 256), rounds = (tiles + 255) / 256;
+  return tiles * 10 >= rounds * 256 * 7;
+}
+int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_strip, hipStream_t st) {
+  const Plan& p = c->plan;
+  const int MT = (int)((M + 255) / 256), PT = (int)(ncols / 256);
+  hipLaunchKernelGGL(k_in, dim3(MT * PT), dim3(G_THREADS), 0, st, (const uint16_t*)X, (int)M, (int)p.d, c->ws + p.off_wU,
+                     (int)r_strip, c->ws + p.off_T, MT, PT);
+  return (int)hipGetLastError();
 }
 
 }  // namespace svdmlp

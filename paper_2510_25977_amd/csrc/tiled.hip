@@ -638,14 +638,20 @@ int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   char* ws = c->ws;
   const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
   const int PT = (int)(p.r / 128);
-  static const char* const names[2] = {"k_s1", "k_out"};
-  const int ps = prof_open_forward(c, 2, names);
+  static const char* const names_s1[2] = {"k_s1", "k_out"};
+  static const char* const names_in[2] = {"k_in", "k_out"};
+  const int ps = prof_open_forward(c, 2, in_supported(M, p.d, p.r) ? names_in : names_s1);
   int e;
   prof_mark(c, ps, 0, 0, st);
-  hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
-                     (int)(p.r / 2), ws + p.off_T, PT);
+  if (in_supported(M, p.d, p.r)) {
+    e = launch_in(c, X, M, p.r, p.r / 2, st);
+  } else {
+    hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
+                       (int)(p.r / 2), ws + p.off_T, PT);
+    e = (int)hipGetLastError();
+  }
   prof_mark(c, ps, 0, 1, st);
-  if ((e = (int)hipGetLastError())) return e;
+  if (e) return e;
   prof_mark(c, ps, 1, 0, st);
   if (p.ffn % 256 == 0) {
     e = launch_out_generic(c, ws + p.off_T, ws + p.off_wVd, M, Y, MT256, p.ffn, p.r, st);
@@ -665,15 +671,22 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   const int MT128 = (int)((M + 127) / 128);
   const int PT = (int)(2 * p.r / 128);
   int e;
-  static const char* const names_fused[4] = {"k_s1", "k_fused", "k_reduce", "k_s5"};
-  static const char* const names_staged[5] = {"k_s1", "k_gate_up", "k_down1", "k_reduce", "k_out"};
+  const bool big = in_supported(M, p.d, 2 * p.r);
+  static const char* const names_fused[2][4] = {{"k_s1", "k_fused", "k_reduce", "k_s5"}, {"k_in", "k_fused", "k_reduce", "k_s5"}};
+  static const char* const names_staged[2][5] = {{"k_s1", "k_gate_up", "k_down1", "k_reduce", "k_out"},
+                                                 {"k_in", "k_gate_up", "k_down1", "k_reduce", "k_out"}};
   const bool staged = staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
-  const int ps = staged ? prof_open_forward(c, 5, names_staged) : prof_open_forward(c, 4, names_fused);
+  const int ps = staged ? prof_open_forward(c, 5, names_staged[big]) : prof_open_forward(c, 4, names_fused[big]);
   prof_mark(c, ps, 0, 0, st);
-  hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU, (int)p.r,
-                     ws + p.off_T, PT);
+  if (in_supported(M, p.d, 2 * p.r)) {
+    e = launch_in(c, X, M, 2 * p.r, p.r, st);
+  } else {
+    hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
+                       (int)p.r, ws + p.off_T, PT);
+    e = (int)hipGetLastError();
+  }
   prof_mark(c, ps, 0, 1, st);
-  if ((e = (int)hipGetLastError())) return e;
+  if (e) return e;
 
   const int nq_total = (int)(p.rd / 32);
   if (staged) return staged_tail(c, M, Y, ps, st);

@@ -131,6 +131,35 @@ def test_bf16_linear_small(M, d, n, r):
     assert relfro(Oh, ref) <= 1.5e-2
 
 
+def test_bf16_linear_many_tiles_uses_256_tile_first_stage():
+    """Enough 256 x 256 tiles of T for the eight-wave first-stage kernel (k_in instead of k_s1); ragged M."""
+    M, d, n, r = 3000, 4096, 4096, 4096
+    li = synth.make_linear_gaussian(M, d, n, r, stream=43)
+    dv = dev()
+    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
+    B.svdmlp_profile_begin(mlp.ctx, 1)
+    O = mlp(li.X.to(dv))
+    torch.cuda.synchronize()
+    kernels, _ = B.svdmlp_profile_end(mlp.ctx)
+    assert "k_in" in kernels, kernels
+    rows = list(range(0, M, 61)) + [M - 1]
+    Oh = O[rows].cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.linear(synth.to_f64(li.X)[rows], synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
+
+
+def test_bf16_gated_many_tiles_uses_256_tile_first_stage():
+    M, d, ffn, r, rd = 6000, 1024, 1024, 1024, 256
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=44)
+    rows = list(range(0, M, 113)) + [M - 1]
+    Y, ref, path = run_gated(gi, rows=rows)
+    assert path == 5
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+    Yf, _, _ = run_gated(gi, rows=rows, flags=B.FLAG_TILED_FUSED)
+    assert relmax(Yf, ref) <= BF16_TOL
+
+
 def test_bf16_linear_paper_kernel_shape_sampled_rows():
     """The paper's kernel-evaluation shape X[M,8192] U[8192,4096] V[4096,16384] (Sec. 5.2) at M = 1024; the
     oracle evaluates a sample of rows."""
