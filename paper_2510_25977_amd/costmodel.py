@@ -65,3 +65,19 @@ def gated_mlp_bytes(M: int, d: int, ffn: int, r: int, r_down: int | None = None,
 def dense_mlp_flops(M: int, d: int, ffn: int) -> int:
     """FLOPs of the uncompressed gated MLP (three dense matmuls)."""
     return 6 * M * d * ffn
+
+
+def sqrt_sigma_factors(W, r: int):
+    """Rank-r factors of a dense weight W[k, n] with the singular values split evenly between the two sides
+    (paper Sec. 3.1, Eq. 6-8): W ~ U V with U = U_r sqrt(S_r) [k, r] and V = sqrt(S_r) V_r^T [r, n].
+    Plain truncated SVD of a given matrix (float64 numpy): no whitening, no fine-tuning.  Returns (U, V, s) with s
+    all singular values of W, so that the truncation error is known in closed form:
+    ||W - U V||_F = sqrt(sum(s[r:]**2))."""
+    import numpy as np
+    W = np.asarray(W, dtype=np.float64)
+    if W.ndim != 2 or not (1 <= r <= min(W.shape)):
+        raise ValueError("W must be a matrix and 1 <= r <= min(W.shape)")
+    u, s, vt = np.linalg.svd(W, full_matrices=False)
+    root = np.sqrt(s[:r])
+    return u[:, :r] * root[None, :], root[:, None] * vt[:r, :], s
+

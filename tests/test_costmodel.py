@@ -49,3 +49,24 @@ def test_gated_mlp_totals():
     assert cm.gated_mlp_bytes(M, d, ffn, r) == 2 * (3 * r * (d + ffn) + 2 * M * d)
     assert cm.dense_mlp_flops(M, d, ffn) == 6 * M * d * ffn
     assert cm.gated_mlp_flops(16, d, ffn, r, r_down=256) == 2 * 2 * 16 * r * (d + ffn) + 2 * 16 * 256 * (d + ffn)
+
+
+def test_sqrt_sigma_factors_truncation_error_and_balance():
+    """Factoriser of Eq. 6-8 on a synthetic matrix: Eckart-Young residual, equal column / row norms of the two
+    factors (each carries sqrt(s_i)), and the oracle's factored product equals X W_r."""
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(7)
+    W = rng.standard_normal((48, 80)) @ np.diag(np.arange(1, 81, dtype=np.float64) ** -0.8)
+    r = 16
+    U, V, s = cm.sqrt_sigma_factors(W, r)
+    assert U.shape == (48, r) and V.shape == (r, 80)
+    assert np.isclose(np.linalg.norm(W - U @ V), np.sqrt(np.sum(s[r:] ** 2)), rtol=1e-10)
+    assert np.allclose(np.linalg.norm(U, axis=0), np.sqrt(s[:r]), rtol=1e-10)
+    assert np.allclose(np.linalg.norm(V, axis=1), np.sqrt(s[:r]), rtol=1e-10)
+    X = rng.standard_normal((5, 48))
+    assert np.allclose(oracle.linear(X, U, V), X @ (U @ V), rtol=1e-10, atol=1e-12)
+    r_rule = cm.block_aligned_rank(48, 80, 0.5, block_size=8)
+    U2, V2, _ = cm.sqrt_sigma_factors(W, r_rule)
+    assert cm.compression_ratio(48, 80, r_rule) <= 0.55 and U2.shape[1] == r_rule
+
