@@ -282,6 +282,34 @@ def test_empty_and_invalid_calls():
     mlp.close()
 
 
+def test_one_context_many_M_staged_path_row_boundaries():
+    """One context, forwards at every size around the path switch (32 / 33) and around the 128- and 256-row tile
+    edges, largest first so that the smaller calls run over stale rows of the workspace; rows beyond M of the
+    output must stay untouched and each call must be bitwise repeatable."""
+    d_, ffn, r, rd, maxM = 512, 768, 128, 256, 520
+    gi = synth.make_gated(maxM, d_, ffn, r, rd, stream=45)
+    dv = dev()
+    f = {k: v.to(dv) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=maxM, **f)
+    Xd = gi.X.to(dv)
+    a = {k: synth.to_f64(v) for k, v in gi.factors().items()}
+    ref = oracle.gated(synth.to_f64(gi.X), **a)
+    scale = np.max(np.abs(ref))
+    for M in (520, 513, 512, 511, 257, 256, 255, 129, 128, 127, 33, 32, 31, 1):
+        Y = torch.full((maxM, d_), 7.0, dtype=torch.bfloat16, device=dv)
+        B.svdmlp_forward(mlp.ctx, Xd.data_ptr(), M, Y.data_ptr())
+        torch.cuda.synchronize()
+        assert mlp.last_path == (5 if M > 32 else 3), (M, mlp.last_path)
+        assert torch.all(Y[M:] == 7.0), M
+        Yh = Y[:M].cpu().to(torch.float64).numpy()
+        assert np.max(np.abs(Yh - ref[:M])) / scale <= BF16_TOL, M
+        Y2 = torch.empty_like(Y)
+        B.svdmlp_forward(mlp.ctx, Xd.data_ptr(), M, Y2.data_ptr())
+        torch.cuda.synchronize()
+        assert torch.equal(Y[:M], Y2[:M]), M
+    mlp.close()
+
+
 def test_zero_input_gives_zero_output():
     gi = synth.make_gated(64, 128, 256, 128, 128, stream=42)
     d = dev()
