@@ -65,6 +65,13 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
     p->off_wU = take((size_t)r * d * 2);
     p->off_wVd = take((size_t)n * r * 2);
     p->off_T = take((size_t)p->Mpad * r * 2);
+    // fp32 tiles of T per range of d when the first stage cuts its contraction (few tiles)
+    int64_t prow = 0;
+    for (int64_t mt = 1; mt <= p->Mpad / 128; ++mt) {
+      const int64_t s1 = s1_splits(mt, r / 128, d);
+      if (s1 > 1 && s1 * mt * 128 > prow) prow = s1 * mt * 128;
+    }
+    p->off_Tdp = take((size_t)prow * r * 4);
     p->total_bytes = off;
     return SVDMLP_OK;
   }
@@ -95,7 +102,13 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
       if (rws > rows) rows = rws;
     }
   p->part_rows = rows;
-  p->off_Tdp = take((size_t)rows * rd * 4);
+  // the same buffer first holds the fp32 tiles of T per range of d when k_s1 cuts its contraction (few tiles)
+  size_t part_bytes = (size_t)rows * rd * 4;
+  for (int64_t mt = 1; mt <= p->Mpad / 128; ++mt) {
+    const int64_t s1 = s1_splits(mt, 2 * r / 128, d);
+    if (s1 > 1 && (size_t)(s1 * mt * 128) * 2 * r * 4 > part_bytes) part_bytes = (size_t)(s1 * mt * 128) * 2 * r * 4;
+  }
+  p->off_Tdp = take(part_bytes);
   p->off_Td = take((size_t)p->Mpad * rd * 2);
   p->off_H = take((size_t)32 * ffn * 2);            // streaming path: the ffn-wide activation of <= 32 rows
   // staged tiled path: the whole gated activation as frags

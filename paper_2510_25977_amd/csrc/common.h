@@ -149,6 +149,8 @@ int make_plan(const svdmlp_desc* desc, Plan* plan);  // returns a status code
 
 // number of ffn splits the tiled path uses for a given number of 128-row tiles
 int tiled_splits(int64_t mtiles128, int64_t nchunks);
+// number of ranges of d the first stage (k_s1) uses for mt128 x pt tiles of 128 x 128
+int s1_splits(int64_t mt128, int64_t pt, int64_t d);
 // extents the staged tiled path (gemm.hip) handles
 bool staged_supported(int64_t rd, int64_t ffn);
 // number of ffn ranges k_down1 uses for a given number of 256-row tiles, 256-wide rank tiles and unit pairs

@@ -56,16 +56,19 @@ __device__ __forceinline__ void s1_read(u32x4 (&R)[4], unsigned aP, unsigned aX0
   R[3] = lds_read<(J / 2) * FRAG_BYTES>((J & 1) ? aX1o : aX1e);
 }
 
+// S > 1: the contraction over d is cut into S ranges (when the tiles alone would leave most CUs idle); every
+// workgroup then writes its fp32 tile to Tpart in k_reduce's layout and k_reduce adds the ranges and writes T.
 __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int M, int d, const char* __restrict__ wU,
-                                            int r, char* __restrict__ T, int PT) {
+                                            int r, char* __restrict__ T, int PT, int S, float* __restrict__ Tpart, int MT128) {
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
   const int lane = threadIdx.x % 64;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);  // wave index, kept scalar
   const int wp = w / 2, wq = w % 2;
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
-  const int mt = id / PT, pt = id % PT;
+  const int sp = id % S, mt = (id / S) / PT, pt = (id / S) % PT;
   const int KBd = d / 16, KBr = r / 16;
-  const int nks = d / 64;
+  const int nks_all = d / 64;
+  const int ks0 = nks_all * sp / S, nks = nks_all * (sp + 1) / S;   // this workgroup's contraction steps [ks0, nks)
   const unsigned lds_off = lds_offset_of(lds);
 
   // per-wave sources
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
     srcX[i] = X + (size_t)row * d + 32 * kh + 8 * piece;  // + ks * 64
   }
   const unsigned m0base = lds_off + (4 * w) * FRAG_BYTES;
-  int pslot = 0, pks = 0;   // producer: ring slot and contraction step of the next unit pair
+  int pslot = 0, pks = ks0;   // producer: ring slot and contraction step of the next unit pair
   auto put_pair = [&]() __attribute__((always_inline)) {
     const int ks = pks < nks ? pks : nks - 1;   // past the end: re-read the last step (never consumed)
     const unsigned dP = m0base + pslot * UNIT_BYTES;
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
 
   put_pair(); put_pair(); put_pair();   // PD = 6 units
   int cslot = 0;
-  for (int ks = 0; ks < nks; ++ks) {
+  for (int ks = ks0; ks < nks; ++ks) {
     wait_vmcnt<4 * (PD - 2)>();
     lds_barrier();
     const unsigned aP = pbase + cslot * UNIT_BYTES;
@@ -151,6 +154,23 @@ __global__ __launch_bounds__(256) void k_s1(const uint16_t* __restrict__ X, int 
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();
+  if (S > 1) {
+    // fp32 tile of this contraction range: [range][32-row tile][rank tile][4 register groups][lane][4]
+    const int nq = 2 * r / 32;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const size_t tile = (size_t)(4 * mt + 2 * wq + b) * nq + 4 * pt + 2 * wp + a;
+        f32x4* dst = reinterpret_cast<f32x4*>(Tpart + ((size_t)sp * 4 * MT128 * nq + tile) * 1024) + lane;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+          dst[g * 64] = v;
+        }
+      }
+    return;
+  }
   // epilogue: lane = activation row m; registers 8t..8t+7 are the chain-order frag of contraction block t
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
@@ -595,6 +615,35 @@ static int launch_fused(const Ctx* c, int MT128, int splits, int QS, hipStream_t
   return (int)hipGetLastError();
 }
 
+// Ranges of d for k_s1: fill the chip when the 128 x 128 tiles alone do not, keeping at least 8 steps per range.
+int s1_splits(int64_t mt128, int64_t pt, int64_t d) {
+  const int64_t wgs = mt128 * pt;
+  if (wgs >= 160) return 1;
+  int64_t s = 256 / wgs;
+  if (s > d / 512) s = d / 512;
+  if (s > 8) s = 8;
+  return s < 1 ? 1 : (int)s;
+}
+
+// First stage T = X [Ug|Uu] (ncols = 2 r_strip rank columns in two strips): k_in when its 256 x 256 tiles fill the
+// chip, else k_s1, with its contraction cut into ranges (+ k_reduce) when there are few tiles.
+static int first_stage(const Ctx* c, const void* X, int64_t M, int64_t r_strip, hipStream_t st) {
+  const Plan& p = c->plan;
+  char* ws = c->ws;
+  if (in_supported(M, p.d, 2 * r_strip)) return launch_in(c, X, M, 2 * r_strip, r_strip, st);
+  const int MT128 = (int)((M + 127) / 128), PT = (int)(2 * r_strip / 128);
+  const int S = s1_splits(MT128, PT, p.d);
+  hipLaunchKernelGGL(k_s1, dim3(MT128 * PT * S), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
+                     (int)r_strip, ws + p.off_T, PT, S, reinterpret_cast<float*>(ws + p.off_Tdp), MT128);
+  int e = (int)hipGetLastError();
+  if (e || S == 1) return e;
+  const int MT32 = 4 * MT128, nq = (int)(2 * r_strip / 32);
+  const long long threads = (long long)MT32 * nq * 2 * 64;
+  hipLaunchKernelGGL(k_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                     reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_T, S, MT32, nq);
+  return (int)hipGetLastError();
+}
+
 // Everything after k_s1 when the gated activation is staged through HBM (gemm.hip).
 static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st) {
   const Plan& p = c->plan;
@@ -643,13 +692,7 @@ int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   const int ps = prof_open_forward(c, 2, in_supported(M, p.d, p.r) ? names_in : names_s1);
   int e;
   prof_mark(c, ps, 0, 0, st);
-  if (in_supported(M, p.d, p.r)) {
-    e = launch_in(c, X, M, p.r, p.r / 2, st);
-  } else {
-    hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
-                       (int)(p.r / 2), ws + p.off_T, PT);
-    e = (int)hipGetLastError();
-  }
+  e = first_stage(c, X, M, p.r / 2, st);
   prof_mark(c, ps, 0, 1, st);
   if (e) return e;
   prof_mark(c, ps, 1, 0, st);
@@ -678,13 +721,7 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   const bool staged = staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
   const int ps = staged ? prof_open_forward(c, 5, names_staged[big]) : prof_open_forward(c, 4, names_fused[big]);
   prof_mark(c, ps, 0, 0, st);
-  if (in_supported(M, p.d, 2 * p.r)) {
-    e = launch_in(c, X, M, 2 * p.r, p.r, st);
-  } else {
-    hipLaunchKernelGGL(k_s1, dim3(MT128 * PT), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
-                       (int)p.r, ws + p.off_T, PT);
-    e = (int)hipGetLastError();
-  }
+  e = first_stage(c, X, M, p.r, st);
   prof_mark(c, ps, 0, 1, st);
   if (e) return e;
 
