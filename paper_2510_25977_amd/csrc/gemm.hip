@@ -235,7 +235,8 @@ __device__ __forceinline__ unsigned mul_pair(unsigned sp, float p0, float p1) {
 // ------------------------------------------------------------------------------------------------
 // H = SiLU(Tg Vg) .* (Tu Vu)   (paper Alg. 3, second loop nest and gating epilogue)
 // T: per 32-row tile the gate strip's KB frags then the up strip's (as written by k_s1).
-// wVg, wVu: [ffn tile][KB] frags.  H: [32-row tile][ffn / 16] chain-order frags.
+// wVg, wVu: [ffn tile][KB] frags.  H: [256-row tile][ffn / 16][8 row tiles of 32] chain-order frags (the eight
+// activation frags of a unit of k_down1 are contiguous).
 // Persistent: a workgroup works through its tiles (GuSched); the copy stream runs on into the next tile and a
 // finished tile's stores are not waited for.
 // ------------------------------------------------------------------------------------------------
@@ -376,7 +377,7 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
     gp.sched.tile(k, id, hh);
     g_tile_of(id, MT, NT, mx, ngm, mt, nt);
     // One tile: gate phase, SiLU, up phase, H out.  HALF: 128 rows; wave (wm, wn) then owns rows 64 wm.. of the half.
-    char* hbase = H + (((long long)(8 * mt + (HALF ? 4 * hh + 2 * wm : 4 * wm))) * KBf + 2 * (8 * nt + 2 * wn)) * FRAG_BYTES;
+    char* hbase = H + ((((long long)mt * KBf + 2 * (8 * nt + 2 * wn)) * 8) + (HALF ? 4 * hh + 2 * wm : 4 * wm)) * FRAG_BYTES;
     constexpr int NB = HALF ? 2 : 4;
     // ---- gate phase ----
     for (int i = 0; i < half; ++i) {
@@ -433,7 +434,7 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
           u32x4 v = S[(a * 4 + b) * 2 + t2];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = mul_pair(v[e], acc[a][b][8 * t2 + 2 * e], acc[a][b][8 * t2 + 2 * e + 1]);
-          store16_sv(hbase + ((long long)b * KBf + 2 * a + t2) * FRAG_BYTES, gp.prod.lane16, v);
+          store16_sv(hbase + ((long long)(2 * a + t2) * 8 + b) * FRAG_BYTES, gp.prod.lane16, v);
         }
   }
   if (w < 4) lds_barrier();  // matches the extra barrier of waves 4..7
@@ -459,9 +460,9 @@ __global__ __launch_bounds__(G_THREADS) void k_down1(const char* __restrict__ H,
   const unsigned lds_off = lds_offset_of(lds);
 
   GProd prod;
-  prod.a_kb = FRAG_BYTES;
+  prod.a_kb = 8 * FRAG_BYTES;
   prod.w_kb = (long long)nq_total * FRAG_BYTES;
-  prod.pa = H + ((long long)(8 * mt + w) * KBf + 2 * s0) * FRAG_BYTES;
+  prod.pa = H + (((long long)mt * KBf + 2 * s0) * 8 + w) * FRAG_BYTES;
   prod.pw = wUd + ((long long)(2 * s0) * nq_total + 8 * qt + w) * FRAG_BYTES;
   prod.lane16 = lane * 16;
   prod.dst = lds_off + w * FRAG_BYTES;
