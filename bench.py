@@ -268,17 +268,22 @@ def main():
         out["ms_per_step_with_kernel_events"] = ms_ev
 
     # roofline of the dominant kernel (HIP-event average over the timed region)
-    if args.workload == "decode":
-        kname = "k_decode" if "k_decode" in kernels else "k_stream_d2"
+    if path in (3, 4):   # weight-streaming path: HBM-bound
+        rd = dims.get("r_down", r)
+        kbytes = {"k_decode": nbytes,                                           # the whole forward is one launch
+                  "k_stream_d1": 2 * (2 * d * r) + 2 * (M * d + M * 2 * r),     # Ug, Uu once; X in, T out
+                  "k_stream_d2": 2 * (2 * r * ffn) + 2 * (M * 2 * r + M * ffn), # Vg, Vu once; T in, H out
+                  "k_stream_d4": 2 * (ffn * rd) + 2 * (M * ffn + M * rd),       # Ud once; H in, Td out
+                  "k_stream_d5": 2 * (rd * d) + 2 * (M * rd + M * d)}           # Vd once; Td in, Y out
+        cand = {k_: v for k_, v in kernels.items() if k_ in kbytes}
+        kname = "k_stream_d2" if args.workload == "decode" and "k_stream_d2" in cand else max(cand, key=cand.get)
         k_ms = kernels.get(kname, 0.0)
-        if kname == "k_decode":
-            k_bytes = nbytes                                              # the whole forward is one launch
-        else:
-            k_bytes = 2 * (2 * r * ffn) + 2 * (M * 2 * r + M * ffn)      # Vg, Vu once; T in, H out
+        k_bytes = kbytes[kname]
         out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": k_bytes / k_ms / 1e6 if k_ms else None,
                            "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": k_bytes / k_ms / 1e6 / PEAK_HBM_GBS if k_ms else None, "traffic": None,
-                           "note": "per-kernel time from the warm single-set run"}
+                           "whole_forward_GBps": nbytes / ms / 1e6,
+                           "note": "per-kernel time from HIP events" + (" of the warm single-set run" if args.workload == "decode" else "")}
     else:
         rd = dims.get("r_down", r)
         kflops = {"k_s1": 2 * M * d * 2 * r, "k_in": 2 * M * d * 2 * r,   # X [Ug|Uu]

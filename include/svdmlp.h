@@ -59,10 +59,10 @@ enum {
 /* Bits of svdmlp_desc.flags (testing and benchmarking aids; 0 = automatic choice). */
 enum {
   SVDMLP_FLAG_FORCE_TILED = 1u << 0,    /* bf16: always take the MFMA-tiled (prefill) path */
-  SVDMLP_FLAG_FORCE_STREAM = 1u << 1,   /* bf16: always take the weight-streaming (decode) path; needs M <= 32 */
+  SVDMLP_FLAG_FORCE_STREAM = 1u << 1,   /* bf16: always take the weight-streaming (decode) path; needs M <= 128 */
   SVDMLP_FLAG_SKIP_ARCH_CHECK = 1u << 2,/* do not require gfx950 (host-only unit tests of argument handling) */
   SVDMLP_FLAG_STREAM_ONE_KERNEL = 1u << 3,/* weight-streaming path as one persistent kernel instead of four launches
-                                           (used when the extents fit its per-wave register budget) */
+                                           (used when M <= 32 and the extents fit its per-wave register budget) */
   SVDMLP_FLAG_TILED_FUSED = 1u << 4     /* MFMA-tiled path: keep the gated activation in registers (one fused kernel)
                                            instead of staging it through the workspace */
 };
@@ -115,9 +115,9 @@ int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
 
 /* Which path the last svdmlp_forward on this context took: 0 none yet, 1 fp32 debug,
  * 2 bf16 MFMA-tiled (prefill) with the gated activation kept in registers (SVDMLP_FLAG_TILED_FUSED, or extents the
- * staged variant does not take: it needs ffn and r_down to be multiples of 256), 3 bf16 weight-streaming (decode) as
+ * staged variant does not take: it needs ffn and r_down to be multiples of 256), 3 bf16 weight-streaming (decode; the default for M <= 128) as
  * four launches, 4 bf16 weight-streaming as one persistent kernel (SVDMLP_FLAG_STREAM_ONE_KERNEL), 5 bf16
- * MFMA-tiled with the gated activation staged through the workspace (the default for large M), 6 bf16 single
+ * MFMA-tiled with the gated activation staged through the workspace (the default for M > 128), 6 bf16 single
  * factored layer (SVDMLP_LINEAR). */
 int svdmlp_last_path(const svdmlp_ctx *ctx);
 

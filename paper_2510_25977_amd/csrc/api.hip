@@ -110,7 +110,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   }
   p->off_Tdp = take(part_bytes);
   p->off_Td = take((size_t)p->Mpad * rd * 2);
-  p->off_H = take((size_t)32 * ffn * 2);            // streaming path: the ffn-wide activation of <= 32 rows
+  p->off_H = take((size_t)STREAM_MAX_M * ffn * 2);  // streaming path: the ffn-wide activation of its rows
   // staged tiled path: the whole gated activation as frags
   p->off_Hfull = take(staged_supported(rd, ffn) ? (size_t)p->Mpad * ffn * 2 : 0);
   p->off_part = take((size_t)8 << 20);              // streaming path: split-K partial tiles
@@ -207,13 +207,13 @@ int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip
     c->last_path = 6;
     e = bf16_linear_forward(c, X, M, Y, st);
   } else {
-    bool stream_path = M <= 32;
+    bool stream_path = M <= STREAM_MAX_M;
     if (c->plan.flags & SVDMLP_FLAG_FORCE_TILED) stream_path = false;
     if (c->plan.flags & SVDMLP_FLAG_FORCE_STREAM) {
-      if (M > 32) return SVDMLP_UNSUPPORTED;
+      if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
       stream_path = true;
     }
-    const bool one_kernel = stream_path && (c->plan.flags & SVDMLP_FLAG_STREAM_ONE_KERNEL) && bf16_decode_supported(c);
+    const bool one_kernel = stream_path && M <= 32 && (c->plan.flags & SVDMLP_FLAG_STREAM_ONE_KERNEL) && bf16_decode_supported(c);
     const bool staged = staged_supported(c->plan.rd, c->plan.ffn) && !(c->plan.flags & SVDMLP_FLAG_TILED_FUSED);
     c->last_path = stream_path ? (one_kernel ? 4 : 3) : (staged ? 5 : 2);
     e = !stream_path ? bf16_tiled_forward(c, X, M, Y, st)

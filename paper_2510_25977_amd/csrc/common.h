@@ -169,6 +169,7 @@ int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_s
 int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int launch_out_generic(const Ctx* c, const char* act, const char* w, int64_t M, void* Y, int MT256, int64_t n, int64_t k,
                        hipStream_t st);
+constexpr int STREAM_MAX_M = 128;   // rows the weight-streaming path takes (four 32-row tiles)
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 bool bf16_decode_supported(const Ctx* c);

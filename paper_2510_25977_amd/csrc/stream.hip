@@ -1,4 +1,4 @@
-// bf16 weight-streaming (decode) path: M <= 32 rows, weight-bandwidth bound.
+// bf16 weight-streaming (decode) path: M <= 128 rows, weight-bandwidth bound.
 //
 // Each of the four products of the factored MLP (paper Alg. 2) is one launch of k_stream:
 //   D1  T^T  = [Ug|Uu]^T X^T          split-K over d
@@ -6,9 +6,9 @@
 //   D4  Td^T = Ud^T H^T               split-K over ffn
 //   D5  Y^T  = Vd^T Td^T
 // Every weight frag (common.h) is read exactly once, straight from HBM into registers with one
-// coalesced 16-byte-per-lane load, and multiplied against the (tiny, L2-resident) activation frag on
-// the matrix cores with the activation rows padded to one 32-row tile.  The contraction range of a
-// workgroup is split over its 8 waves; their partial tiles are summed through LDS, and, when the
+// coalesced 16-byte-per-lane load, and multiplied on the matrix cores against the (tiny, L2-resident)
+// activation frags of the RT = 1, 2 or 4 tiles of 32 rows that the batch is padded to.  The contraction range
+// of a workgroup is split over its 8 waves; their partial tiles are summed through LDS, and, when the
 // contraction is also split over workgroups, through a partial buffer in which the last workgroup to
 // arrive (an atomic ticket, no spinning) adds the partials in a fixed order, so results are
 // bit-reproducible.  Products are computed transposed (lane = activation row), so each output tile is
@@ -23,20 +23,31 @@ constexpr int SW = 8;  // waves per workgroup
 struct StreamArgs {
   const char* W0;       // weight frags (D2: gate)
   const char* W1;       // D2: up frags
-  const void* act;      // D1: X row-major bf16; otherwise activation frags [kb] (D2: Tg at 0, Tu at KB frags)
+  const void* act;      // D1: X row-major bf16; otherwise activation frags [row tile][kb] (D2: Tg at 0, Tu at KB frags)
   void* out;            // D1: T frags; D2: H frags; D4: Td frags; D5: Y row-major
-  float* part;          // split-K partial tiles [tile][split][16][64]
+  float* part;          // split-K partial tiles [tile][split][accumulator][row tile][16][64]
   int* cnt;             // arrival counters [tile]
   int M, KB, tiles, S;  // contraction blocks, output tiles, workgroup-level splits
   int ldx;              // D1: row length of X (= d); D5: row length of Y (= d)
   int r;                // D1: rank (separates gate tiles from up tiles)
   int kb_major;         // weight frag order (1 for Ud)
+  int act_rt, out_rt;   // frags between consecutive 32-row tiles of the activation / of the output
 };
 
-template <int PH>
+template <int PH, int RT>
 __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
   constexpr int NACC = (PH == PH_D2) ? 2 : 1;
-  __shared__ float red[NACC][SW][16][64];
+  // D2 with four row tiles: the gate product, then the up product (half the accumulator registers, so that two
+  // workgroups still share a CU); otherwise both at once, which keeps more weight loads in flight
+  constexpr bool SEQ = PH == PH_D2 && RT == 4;
+  constexpr int NPASS = SEQ ? 2 : 1;
+  constexpr int NA = NACC / NPASS;            // accumulators (per row tile) live at a time
+  constexpr int NT = NACC * RT;               // accumulator tiles of a wave in all: tile n RT + rt
+  constexpr int NTP = NA * RT;                // ... per pass
+  // ... staged in LDS per round (32 KiB each).  D2 has more workgroups than CUs: 64 KiB lets two of them share a CU
+  constexpr int NB = (PH == PH_D2) ? 2 : (NTP < 4 ? NTP : 4);
+  constexpr int ROUNDS = NTP / NB;
+  __shared__ float red[NB][SW][16][64];
   __shared__ int s_last;
   const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
   const int tile = blockIdx.x / a.S, sp = blockIdx.x % a.S;
@@ -48,52 +59,78 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
   if (k1 > kend) k1 = kend;
 
   const int il = lane % 32, h = lane / 32;
-  f32x16 acc[NACC];
-#pragma unroll
-  for (int n = 0; n < NACC; ++n)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
-
   const size_t wstride = a.kb_major ? (size_t)a.tiles * FRAG_BYTES : (size_t)FRAG_BYTES;
   const char* wp0 = a.W0 + (a.kb_major ? (size_t)tile : (size_t)tile * a.KB) * FRAG_BYTES + lane * 16;
   const char* wp1 = (PH == PH_D2) ? a.W1 + (size_t)tile * a.KB * FRAG_BYTES + lane * 16 : nullptr;
-  const uint16_t* xrow = nullptr;
-  if (PH == PH_D1) xrow = static_cast<const uint16_t*>(a.act) + (size_t)(il < a.M ? il : a.M - 1) * a.ldx + 8 * h;
-  const char* af = static_cast<const char*>(a.act) + lane * 16;
-
-#pragma unroll 4
-  for (int kb = k0; kb < k1; ++kb) {
-    bf16x8 wv = *reinterpret_cast<const bf16x8*>(wp0 + (size_t)kb * wstride);
-    bf16x8 av;
-    if (PH == PH_D1) av = *reinterpret_cast<const bf16x8*>(xrow + 16 * kb);
-    else av = *reinterpret_cast<const bf16x8*>(af + (size_t)kb * FRAG_BYTES);
-    acc[0] = mfma32(wv, av, acc[0]);
-    if (PH == PH_D2) {
-      bf16x8 wu = *reinterpret_cast<const bf16x8*>(wp1 + (size_t)kb * FRAG_BYTES);
-      bf16x8 au = *reinterpret_cast<const bf16x8*>(af + (size_t)(a.KB + kb) * FRAG_BYTES);
-      acc[NACC - 1] = mfma32(wu, au, acc[NACC - 1]);
-    }
+  const uint16_t* xrow[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int row = 32 * rt + il;
+    xrow[rt] = (PH == PH_D1) ? static_cast<const uint16_t*>(a.act) + (size_t)(row < a.M ? row : a.M - 1) * a.ldx + 8 * h : nullptr;
   }
-
-  // ---- sum the 8 waves' partial tiles through LDS (fixed order) ----
-#pragma unroll
-  for (int n = 0; n < NACC; ++n)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) red[n][w][e][lane] = acc[n][e];
-  __syncthreads();
-  // thread (t, lane), t = 0,1: registers 8t..8t+7 of the tile = one chain-order frag
-  const int t = threadIdx.x / 64;  // only t < 2 take part from here on
+  const char* af = static_cast<const char*>(a.act) + lane * 16;
+  // wave t < 2 RT finishes registers 8 (t % 2) .. + 7 (= one chain-order frag) of row tile t / 2
+  const int t = threadIdx.x / 64;
+  const int rtf = t / 2, hf = t % 2;
   float v[NACC][8];
-  if (t < 2) {
+
 #pragma unroll
-    for (int n = 0; n < NACC; ++n)
+  for (int pass = 0; pass < NPASS; ++pass) {
+    f32x16 acc[NA][RT];
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        float x = 0.f;
+    for (int n = 0; n < NA; ++n)
 #pragma unroll
-        for (int ww = 0; ww < SW; ++ww) x += red[n][ww][8 * t + s][lane];
-        v[n][s] = x;
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[n][rt][e] = 0.f;
+    const char* wa = (SEQ && pass == 1) ? wp1 : wp0;
+    const int aoff = SEQ ? pass * a.KB : 0;
+#pragma unroll 4
+    for (int kb = k0; kb < k1; ++kb) {
+      const bf16x8 wv = *reinterpret_cast<const bf16x8*>(wa + (size_t)kb * wstride);
+      bf16x8 wu;
+      if (PH == PH_D2 && !SEQ) wu = *reinterpret_cast<const bf16x8*>(wp1 + (size_t)kb * FRAG_BYTES);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        bf16x8 av;
+        if (PH == PH_D1) av = *reinterpret_cast<const bf16x8*>(xrow[rt] + 16 * kb);
+        else av = *reinterpret_cast<const bf16x8*>(af + ((size_t)rt * a.act_rt + aoff + kb) * FRAG_BYTES);
+        acc[0][rt] = mfma32(wv, av, acc[0][rt]);
+        if (PH == PH_D2 && !SEQ) {
+          const bf16x8 au = *reinterpret_cast<const bf16x8*>(af + ((size_t)rt * a.act_rt + a.KB + kb) * FRAG_BYTES);
+          acc[NA - 1][rt] = mfma32(wu, au, acc[NA - 1][rt]);
+        }
       }
+    }
+
+    // ---- sum the 8 waves' partial tiles through LDS (fixed order) ----
+#pragma unroll
+    for (int q = 0; q < ROUNDS; ++q) {
+      if (pass > 0 || q > 0) __syncthreads();   // the previous round has been read
+#pragma unroll
+      for (int jj = 0; jj < NB; ++jj) {
+        const int j = q * NB + jj;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[jj][w][e][lane] = acc[j / RT][j % RT][e];
+      }
+      __syncthreads();
+      if (t < 2 * RT) {
+#pragma unroll
+        for (int n = 0; n < NA; ++n) {
+          const int j = n * RT + rtf;
+          if (j / NB == q) {
+            const int jj = j % NB;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+              float x = 0.f;
+#pragma unroll
+              for (int ww = 0; ww < SW; ++ww) x += red[jj][ww][8 * hf + s][lane];
+              v[pass * NA + n][s] = x;
+            }
+          }
+        }
+      }
+    }
   }
   if (a.S > 1) {
     // Partials cross workgroups (possibly on different XCDs, whose L2s are not coherent with each other) as
@@ -101,13 +138,14 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
     // so no cache write-back / invalidate (which a device-scope fence would cost every workgroup) is needed.
     // Ordering: each thread waits for its own stores to be acknowledged, the workgroup barrier collects
     // them, then one thread takes the ticket.
-    float* mine = a.part + (((size_t)tile * a.S + sp) * NACC) * 1024;
-    if (t < 2) {
+    float* mine = a.part + ((size_t)tile * a.S + sp) * NT * 1024;
+    const int eo = (8 * hf) * 64 + lane;
+    if (t < 2 * RT) {
 #pragma unroll
       for (int n = 0; n < NACC; ++n)
 #pragma unroll
         for (int s = 0; s < 8; ++s)
-          __hip_atomic_store(&mine[n * 1024 + (8 * t + s) * 64 + lane], v[n][s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(&mine[(n * RT + rtf) * 1024 + eo + s * 64], v[n][s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     asm volatile("" ::: "memory");
     wait_vmcnt<0>();
@@ -116,7 +154,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
       s_last = (__hip_atomic_fetch_add(&a.cnt[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.S - 1);
     __syncthreads();
     if (!s_last) return;
-    if (t < 2) {
+    if (t < 2 * RT) {
 #pragma unroll
       for (int n = 0; n < NACC; ++n) {
 #pragma unroll
@@ -127,7 +165,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
 #pragma unroll
           for (int qq = 0; qq < 4; ++qq) {
             const int q = q0 + qq < a.S ? q0 + qq : a.S - 1;
-            const float* src = a.part + (((size_t)tile * a.S + q) * NACC + n) * 1024 + (8 * t) * 64 + lane;
+            const float* src = a.part + (((size_t)tile * a.S + q) * NT + n * RT + rtf) * 1024 + eo;
 #pragma unroll
             for (int s = 0; s < 8; ++s) tmp[qq][s] = __hip_atomic_load(src + s * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
@@ -142,13 +180,14 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
     }
     if (threadIdx.x == 0) __hip_atomic_store(&a.cnt[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next forward
   }
-  if (t >= 2) return;
+  if (t >= 2 * RT) return;
 
   // ---- epilogue ----
   if (PH == PH_D5) {
-    // lane = row m; slots s <-> columns 32 tile + 16 t + 8 (s / 4) + 4 h + s % 4
-    if (il < a.M) {
-      uint16_t* y = static_cast<uint16_t*>(a.out) + (size_t)il * a.ldx + 32 * tile + 16 * t + 4 * h;
+    // lane = row m; slots s <-> columns 32 tile + 16 hf + 8 (s / 4) + 4 h + s % 4
+    const int row = 32 * rtf + il;
+    if (row < a.M) {
+      uint16_t* y = static_cast<uint16_t*>(a.out) + (size_t)row * a.ldx + 32 * tile + 16 * hf + 4 * h;
 #pragma unroll
       for (int g = 0; g < 2; ++g) {
         bf16x4 o;
@@ -164,19 +203,19 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       const float g = v[0][s];
-      o[s] = (__bf16)(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * v[1][s]);
+      o[s] = (__bf16)(g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * v[NACC - 1][s]);
     }
   } else {
 #pragma unroll
     for (int s = 0; s < 8; ++s) o[s] = (__bf16)v[0][s];
   }
-  size_t frag;
+  size_t frag = (size_t)rtf * a.out_rt;
   if (PH == PH_D1) {
     const int p0 = 32 * tile;
     const int which = p0 >= a.r ? 1 : 0;
-    frag = (size_t)which * (a.r / 16) + (p0 - which * a.r) / 16 + t;
+    frag += (size_t)which * (a.r / 16) + (p0 - which * a.r) / 16 + hf;
   } else {
-    frag = (size_t)2 * tile + t;
+    frag += (size_t)2 * tile + hf;
   }
   *reinterpret_cast<bf16x8*>(static_cast<char*>(a.out) + (frag * 64 + lane) * 16) = o;
 }
@@ -189,49 +228,60 @@ static int pick_splits(int tiles, int KB) {
   return s < 1 ? 1 : s;
 }
 
+template <int PH>
+static void launch_stream(int rt, const StreamArgs& a, hipStream_t st) {
+  const dim3 grid(a.tiles * a.S), block(SW * 64);
+  if (rt == 1) hipLaunchKernelGGL((k_stream<PH, 1>), grid, block, 0, st, a);
+  else if (rt == 2) hipLaunchKernelGGL((k_stream<PH, 2>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((k_stream<PH, 4>), grid, block, 0, st, a);
+}
+
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
   int* cnt = reinterpret_cast<int*>(ws + p.off_cnt);
   float* part = reinterpret_cast<float*>(ws + p.off_part);
   const size_t part_floats = ((size_t)8 << 20) / 4;
+  if (M > STREAM_MAX_M) return (int)hipErrorInvalidValue;
+  const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;   // 32-row tiles the batch is padded to
   int e;
   static const char* const names[4] = {"k_stream_d1", "k_stream_d2", "k_stream_d4", "k_stream_d5"};
   const int ps = prof_open_forward(c, 4, names);
+  const int fT = (int)(2 * p.r / 16), fH = (int)(p.ffn / 16), fTd = (int)(p.rd / 16);   // frags per 32-row tile
 
   StreamArgs a;
   // D1
   a = StreamArgs{ws + p.off_wU, nullptr, X, ws + p.off_T, part, cnt, (int)M, (int)(p.d / 16), (int)(2 * p.r / 32), 1,
-                 (int)p.d, (int)p.r, 0};
+                 (int)p.d, (int)p.r, 0, 0, fT};
   a.S = pick_splits(a.tiles, a.KB);
-  while (a.S > 1 && (size_t)a.tiles * a.S * 1024 > part_floats) --a.S;
+  while (a.S > 1 && (size_t)a.tiles * a.S * rt * 1024 > part_floats) --a.S;
   if (a.tiles > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 0, 0, st);
-  hipLaunchKernelGGL(k_stream<PH_D1>, dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+  launch_stream<PH_D1>(rt, a, st);
   prof_mark(c, ps, 0, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D2 (never split over workgroups: its contraction is only r long)
   a = StreamArgs{ws + p.off_wVg, ws + p.off_wVu, ws + p.off_T, ws + p.off_H, part, cnt, (int)M, (int)(p.r / 16),
-                 (int)(p.ffn / 32), 1, 0, (int)p.r, 0};
+                 (int)(p.ffn / 32), 1, 0, (int)p.r, 0, fT, fH};
   prof_mark(c, ps, 1, 0, st);
-  hipLaunchKernelGGL(k_stream<PH_D2>, dim3(a.tiles), dim3(SW * 64), 0, st, a);
+  launch_stream<PH_D2>(rt, a, st);
   prof_mark(c, ps, 1, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D4
   a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048, (int)M, (int)(p.ffn / 16),
-                 (int)(p.rd / 32), 1, 0, (int)p.r, 1};
+                 (int)(p.rd / 32), 1, 0, (int)p.r, 1, fH, fTd};
   a.S = pick_splits(a.tiles, a.KB);
-  while (a.S > 1 && (size_t)a.tiles * a.S * 1024 > part_floats) --a.S;
+  while (a.S > 1 && (size_t)a.tiles * a.S * rt * 1024 > part_floats) --a.S;
   if (a.tiles > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 2, 0, st);
-  hipLaunchKernelGGL(k_stream<PH_D4>, dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+  launch_stream<PH_D4>(rt, a, st);
   prof_mark(c, ps, 2, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D5
   a = StreamArgs{ws + p.off_wVd, nullptr, ws + p.off_Td, Y, part, cnt, (int)M, (int)(p.rd / 16), (int)(p.d / 32), 1,
-                 (int)p.d, (int)p.r, 0};
+                 (int)p.d, (int)p.r, 0, fTd, 0};
   prof_mark(c, ps, 3, 0, st);
-  hipLaunchKernelGGL(k_stream<PH_D5>, dim3(a.tiles), dim3(SW * 64), 0, st, a);
+  launch_stream<PH_D5>(rt, a, st);
   prof_mark(c, ps, 3, 1, st);
   return (int)hipGetLastError();
 }

@@ -188,6 +188,42 @@ def test_bf16_stream_small(M, d, ffn, r, rd, one_kernel):
     assert relfro(Y, ref) <= 1.5e-2
 
 
+@pytest.mark.parametrize("M", [33, 48, 64, 65, 100, 128])
+@pytest.mark.parametrize("d,ffn,r,rd", [(256, 512, 128, 128), (512, 1408, 192, 256)])
+def test_bf16_stream_several_row_tiles(M, d, ffn, r, rd):
+    """Weight-streaming path with the batch padded to two or four 32-row tiles (every weight frag still read once)."""
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=33)
+    Y, ref, path = run_gated(gi, max_M=128, flags=B.FLAG_FORCE_STREAM)
+    assert path == 3
+    assert relmax(Y, ref) <= BF16_TOL, (relmax(Y, ref), relfro(Y, ref))
+    assert relfro(Y, ref) <= 1.5e-2
+
+
+def test_bf16_stream_one_context_many_M():
+    """One context, batches on both sides of every row-tile count; rows must not depend on M or on what an
+    earlier, larger batch left in the workspace; the tiled path must agree."""
+    gi = synth.make_gated(128, 512, 1408, 192, 256, stream=34)
+    d = dev()
+    f = {k: v.to(d) for k, v in gi.factors().items()}
+    X = gi.X.to(d)
+    mlp = B.SvdMlp(max_M=128, flags=B.FLAG_FORCE_STREAM, **f)
+    full = mlp(X).clone()
+    for M in (128, 97, 96, 65, 64, 33, 32, 31, 1, 128):
+        y = mlp(X[:M]).clone()
+        torch.cuda.synchronize()
+        assert mlp.last_path == 3
+        assert torch.equal(y, full[:M]), M
+    mlp.close()
+    tiled = B.SvdMlp(max_M=128, flags=B.FLAG_FORCE_TILED, **f)
+    yt = tiled(X)
+    torch.cuda.synchronize()
+    tiled.close()
+    a = {k: synth.to_f64(v) for k, v in gi.factors().items()}
+    ref = oracle.gated(synth.to_f64(gi.X), **a)
+    assert relmax(full.cpu().to(torch.float64).numpy(), ref) <= BF16_TOL
+    assert relmax(full.cpu().to(torch.float64).numpy(), yt.cpu().to(torch.float64).numpy()) <= BF16_TOL
+
+
 def test_bf16_stream_and_tiled_agree_and_are_deterministic():
     gi = synth.make_gated(16, 512, 1408, 128, 256, stream=32)
     d = dev()
@@ -210,10 +246,21 @@ def test_bf16_stream_and_tiled_agree_and_are_deterministic():
 
 
 # ---------------------------------------------------------------------------------- full-size workloads
-def test_workload_mlp_small():
-    """d=2048 ffn=8192 r=256 M=128."""
+@pytest.mark.parametrize("flags,want", [(0, 3), (B.FLAG_FORCE_TILED, 5)])
+def test_workload_mlp_small(flags, want):
+    """d=2048 ffn=8192 r=256 M=128: the weight-streaming path by default (four row tiles), the tiled one on request."""
     gi = synth.make_workload("mlp_small")
+    Y, ref, path = run_gated(gi, flags=flags)
+    assert path == want
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+
+
+@pytest.mark.parametrize("M", [64, 128])
+def test_workload_decode_shape_larger_batches(M):
+    """d=4096 ffn=14336 r=512 at batch sizes that take two and four row tiles of the streaming path."""
+    gi = synth.make_workload("decode", M=M)
     Y, ref, path = run_gated(gi)
+    assert path == 3
     assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
 
 
@@ -283,8 +330,8 @@ def test_empty_and_invalid_calls():
 
 
 def test_one_context_many_M_staged_path_row_boundaries():
-    """One context, forwards at every size around the path switch (32 / 33) and around the 128- and 256-row tile
-    edges, largest first so that the smaller calls run over stale rows of the workspace; rows beyond M of the
+    """One context, forwards at every size around the path switch (128 / 129), around the row-tile counts of the
+    streaming path and around the 256-row tile edges, largest first so that the smaller calls run over stale rows of the workspace; rows beyond M of the
     output must stay untouched and each call must be bitwise repeatable."""
     d_, ffn, r, rd, maxM = 512, 768, 128, 256, 520
     gi = synth.make_gated(maxM, d_, ffn, r, rd, stream=45)
@@ -295,11 +342,11 @@ def test_one_context_many_M_staged_path_row_boundaries():
     a = {k: synth.to_f64(v) for k, v in gi.factors().items()}
     ref = oracle.gated(synth.to_f64(gi.X), **a)
     scale = np.max(np.abs(ref))
-    for M in (520, 513, 512, 511, 257, 256, 255, 129, 128, 127, 33, 32, 31, 1):
+    for M in (520, 513, 512, 511, 257, 256, 255, 130, 129, 128, 127, 65, 64, 33, 32, 31, 1):
         Y = torch.full((maxM, d_), 7.0, dtype=torch.bfloat16, device=dv)
         B.svdmlp_forward(mlp.ctx, Xd.data_ptr(), M, Y.data_ptr())
         torch.cuda.synchronize()
-        assert mlp.last_path == (5 if M > 32 else 3), (M, mlp.last_path)
+        assert mlp.last_path == (5 if M > 128 else 3), (M, mlp.last_path)
         assert torch.all(Y[M:] == 7.0), M
         Yh = Y[:M].cpu().to(torch.float64).numpy()
         assert np.max(np.abs(Yh - ref[:M])) / scale <= BF16_TOL, M
