@@ -114,7 +114,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   // staged tiled path: the whole gated activation as frags
   p->off_Hfull = take(staged_supported(rd, ffn) ? (size_t)p->Mpad * ffn * 2 : 0);
   p->off_part = take((size_t)8 << 20);              // streaming path: split-K partial tiles
-  p->off_cnt = take(32768 + 3 * 256 * 128);          // streaming paths: tickets, completion counters, per-workgroup flags
+  p->off_cnt = take(CNT_BYTES);                     // streaming paths: tickets, completion counters, per-workgroup flags
   p->total_bytes = off;
   return SVDMLP_OK;
 }

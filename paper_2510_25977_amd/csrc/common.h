@@ -169,6 +169,12 @@ int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_s
 int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int launch_out_generic(const Ctx* c, const char* act, const char* w, int64_t M, void* Y, int MT256, int64_t n, int64_t k,
                        hipStream_t st);
+// Counter area of the streaming paths: [0, 32 KiB) tickets, completion counters and the error word of the one-kernel
+// variant, then its 3 x 256 flag lines, then the tickets of the four-launch variant, one 128-byte line each (tickets
+// that share a line are served one after the other): 2048 for D1, 2048 for D4.
+constexpr size_t CNT_ONE_KERNEL_BYTES = 32768 + 3 * 256 * 128;
+constexpr int TICKET_STRIDE = 32;   // ints
+constexpr size_t CNT_BYTES = CNT_ONE_KERNEL_BYTES + 2 * 2048 * TICKET_STRIDE * 4;
 constexpr int STREAM_MAX_M = 128;   // rows the weight-streaming path takes (four 32-row tiles)
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);

@@ -70,7 +70,7 @@ int bf16_repack_all(const Ctx* c, hipStream_t st) {
   if ((e = repack(de.Vd, p.rd, p.d, ws + p.off_wVd, ORDER_CHAIN, TILE_MAJOR, 0, (int)(p.d / 32), st))) return e;
   // tickets of the streaming paths start at zero and are left at zero by every forward; the completion counters
   // of the single-kernel decode path start at zero and only grow
-  return (int)hipMemsetAsync(ws + p.off_cnt, 0, 32768 + 3 * 256 * 128, st);
+  return (int)hipMemsetAsync(ws + p.off_cnt, 0, CNT_BYTES, st);
 }
 
 }  // namespace svdmlp

@@ -26,7 +26,7 @@ struct StreamArgs {
   const void* act;      // D1: X row-major bf16; otherwise activation frags [row tile][kb] (D2: Tg at 0, Tu at KB frags)
   void* out;            // D1: T frags; D2: H frags; D4: Td frags; D5: Y row-major
   float* part;          // split-K partial tiles [tile][split][accumulator][row tile][16][64]
-  int* cnt;             // arrival counters [tile]
+  int* cnt;             // arrival counters [tile], TICKET_STRIDE ints apart
   int M, KB, tiles, S;  // contraction blocks, output tiles, workgroup-level splits
   int ldx;              // D1: row length of X (= d); D5: row length of Y (= d)
   int r;                // D1: rank (separates gate tiles from up tiles)
@@ -47,7 +47,8 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
   // ... staged in LDS per round (32 KiB each).  D2 has more workgroups than CUs: 64 KiB lets two of them share a CU
   constexpr int NB = (PH == PH_D2) ? 2 : (NTP < 4 ? NTP : 4);
   constexpr int ROUNDS = NTP / NB;
-  __shared__ float red[NB][SW][16][64];
+  // staging of accumulator tiles: [tile][wave][registers 4 p .. 4 p + 3][lane], 16 bytes per lane
+  __shared__ f32x4 red[NB][SW][4][64];
   __shared__ int s_last;
   const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
   const int tile = blockIdx.x / a.S, sp = blockIdx.x % a.S;
@@ -111,7 +112,10 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
       for (int jj = 0; jj < NB; ++jj) {
         const int j = q * NB + jj;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) red[jj][w][e][lane] = acc[j / RT][j % RT][e];
+        for (int pl = 0; pl < 4; ++pl) {
+          const f32x16& c = acc[j / RT][j % RT];
+          red[jj][w][pl][lane] = f32x4{c[4 * pl], c[4 * pl + 1], c[4 * pl + 2], c[4 * pl + 3]};
+        }
       }
       __syncthreads();
       if (t < 2 * RT) {
@@ -121,11 +125,12 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
           if (j / NB == q) {
             const int jj = j % NB;
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-              float x = 0.f;
+            for (int s = 0; s < 8; ++s) v[pass * NA + n][s] = 0.f;
 #pragma unroll
-              for (int ww = 0; ww < SW; ++ww) x += red[jj][ww][8 * hf + s][lane];
-              v[pass * NA + n][s] = x;
+            for (int ww = 0; ww < SW; ++ww) {
+              const f32x4 x0 = red[jj][ww][2 * hf][lane], x1 = red[jj][ww][2 * hf + 1][lane];
+#pragma unroll
+              for (int s = 0; s < 4; ++s) { v[pass * NA + n][s] += x0[s]; v[pass * NA + n][4 + s] += x1[s]; }
             }
           }
         }
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
     wait_vmcnt<0>();
     __syncthreads();
     if (threadIdx.x == 0)
-      s_last = (__hip_atomic_fetch_add(&a.cnt[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.S - 1);
+      s_last = (__hip_atomic_fetch_add(&a.cnt[tile * TICKET_STRIDE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.S - 1);
     __syncthreads();
     if (!s_last) return;
     if (t < 2 * RT) {
@@ -178,7 +183,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
         }
       }
     }
-    if (threadIdx.x == 0) __hip_atomic_store(&a.cnt[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next forward
+    if (threadIdx.x == 0) __hip_atomic_store(&a.cnt[tile * TICKET_STRIDE], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next forward
   }
   if (t >= 2 * RT) return;
 
@@ -239,7 +244,7 @@ static void launch_stream(int rt, const StreamArgs& a, hipStream_t st) {
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
-  int* cnt = reinterpret_cast<int*>(ws + p.off_cnt);
+  int* cnt = reinterpret_cast<int*>(ws + p.off_cnt + CNT_ONE_KERNEL_BYTES);
   float* part = reinterpret_cast<float*>(ws + p.off_part);
   const size_t part_floats = ((size_t)8 << 20) / 4;
   if (M > STREAM_MAX_M) return (int)hipErrorInvalidValue;
@@ -268,7 +273,7 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   prof_mark(c, ps, 1, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D4
-  a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048, (int)M, (int)(p.ffn / 16),
+  a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048 * TICKET_STRIDE, (int)M, (int)(p.ffn / 16),
                  (int)(p.rd / 32), 1, 0, (int)p.r, 1, fH, fTd};
   a.S = pick_splits(a.tiles, a.KB);
   while (a.S > 1 && (size_t)a.tiles * a.S * rt * 1024 > part_floats) --a.S;
