@@ -81,12 +81,14 @@ def bench_forward(gi, dev, steps, warmup, profile=True, flags=0):
     return ms, wall_ms, kernels, path, ms_ev
 
 
-def bench_xuv(dev, M, steps, warmup, dense=True):
-    """Stand-alone factored layer O = (X U) V at the shape of the paper's kernel evaluation (Sec. 5.2:
-    X[M,8192] U[8192,4096] V[4096,16384]); FLOPs 2 M r (d + n).  Beside it the dense X W product (third party)."""
-    d, r, n = 8192, 4096, 16384
+def bench_xuv(dev, M, steps, warmup, dense=True, shape=(8192, 4096, 16384)):
+    """Stand-alone factored layer O = (X U) V at the shapes of the paper's kernel evaluation (Sec. 5.2:
+    X[M,8192] U[8192,4096] V[4096,16384], M = 1K .. 32K; Sec. 5.3: X[4096,7168] U[7168,4096] V[4096,18432]);
+    FLOPs 2 M r (d + n).  Beside it (third party, torch.matmul): the dense product X W that the factors replace,
+    and the factored layer as two separate GEMMs with T = X U written out by one and read back by the other."""
+    d, r, n = shape
     li = synth.make_linear_gaussian(M, d, n, r)
-    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dev), Vg=li.V.to(dev), kind=B.SVDMLP_LINEAR, keep_factors=False)
+    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dev), Vg=li.V.to(dev), kind=B.SVDMLP_LINEAR, keep_factors=True)
     X = li.X.to(dev)
     O = torch.empty((M, n), dtype=torch.bfloat16, device=dev)
     ms, wall_ms = time_steps(lambda: mlp(X, O), steps, warmup)
@@ -94,13 +96,24 @@ def bench_xuv(dev, M, steps, warmup, dense=True):
     ms_ev, _ = time_steps(lambda: mlp(X, O), steps, 0)
     kernels, _ = B.svdmlp_profile_end(mlp.ctx)
     path = mlp.last_path
-    mlp.close()
+    U, V = mlp.tensors[0], mlp.tensors[1]
     out = dict(M=M, d=d, r=r, n=n, ms=ms, wall_ms=wall_ms, ms_ev=ms_ev, kernels=kernels, path=path, flops=2 * M * r * (d + n))
     if dense:
+        T = torch.empty((M, r), dtype=torch.bfloat16, device=dev)
+
+        def two_gemms():
+            torch.matmul(X, U, out=T)
+            torch.matmul(T, V, out=O)
+
+        ums, _ = time_steps(two_gemms, max(5, steps // 3), 3)
+        out["unfused"] = dict(ms_per_step=ums, TFLOPs=2 * M * r * (d + n) / ums / 1e9,
+                              provider="two torch.matmul calls, T through HBM (third-party GEMM)")
         W = torch.randn((d, n), dtype=torch.bfloat16, device=dev) * (d ** -0.5)
         dms, _ = time_steps(lambda: torch.matmul(X, W, out=O), max(5, steps // 3), 3)
         out["dense"] = dict(ms_per_step=dms, TFLOPs=2 * M * d * n / dms / 1e9, flops=2 * M * d * n,
                             provider="torch.matmul (third-party GEMM)")
+        del W, T
+    mlp.close()
     return out
 
 
@@ -193,6 +206,8 @@ def main():
     ap.add_argument("--workload", default="prefill", choices=["prefill", "wide", "mlp_small", "decode", "xuv"])
     ap.add_argument("--r", type=int, default=None)
     ap.add_argument("--M", type=int, default=None)
+    ap.add_argument("--shape", default=None, help="xuv workload: d,r,n (default 8192,4096,16384)")
+    ap.add_argument("--sweep", action="store_true", help="xuv workload: M = 1K .. 32K, one table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
@@ -214,10 +229,35 @@ def main():
     B.lib()  # fail loudly if the HIP library is missing
 
     if args.workload == "xuv":
-        x = bench_xuv(dev, args.M or 4096, args.steps, args.warmup, dense=not args.no_dense)
+        shape = tuple(int(v) for v in args.shape.split(",")) if args.shape else (8192, 4096, 16384)
+        if args.sweep:
+            rows = []
+            for Ms in (1024, 2048, 4096, 8192, 16384, 32768):
+                x = bench_xuv(dev, Ms, max(5, args.steps // 3), 3, dense=not args.no_dense, shape=shape)
+                row = {"M": Ms, "ms": x["ms"], "TFLOPs": x["flops"] / x["ms"] / 1e9, "kernels_ms": x["kernels"]}
+                if "dense" in x:
+                    row.update(dense_ms=x["dense"]["ms_per_step"], unfused_ms=x["unfused"]["ms_per_step"],
+                               speedup_vs_dense=x["dense"]["ms_per_step"] / x["ms"],
+                               speedup_vs_unfused=x["unfused"]["ms_per_step"] / x["ms"])
+                rows.append(row)
+                torch.cuda.empty_cache()
+            avg = lambda key: sum(r_[key] for r_ in rows) / len(rows)
+            out = {"metric": METRIC, "value": avg("TFLOPs"), "unit": "TFLOP/s", "n_gpus": 1, "steps": max(5, args.steps // 3),
+                   "warmup": 3, "ms_per_step": avg("ms"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                   "dtype": "bf16", "data": "synthetic",
+                   "config": {"workload": f"xuv sweep: (X U) V, X[M,{shape[0]}] U[{shape[0]},{shape[1]}] V[{shape[1]},{shape[2]}], "
+                                          "M = 1K .. 32K; value = mean over M"},
+                   "sweep": rows}
+            if not args.no_dense:
+                out["mean_speedup_vs_dense"] = avg("speedup_vs_dense")
+                out["mean_speedup_vs_unfused"] = avg("speedup_vs_unfused")
+            print(json.dumps(out))
+            return
+        x = bench_xuv(dev, args.M or 4096, args.steps, args.warmup, dense=not args.no_dense, shape=shape)
         k = x["kernels"]
-        kfl = {"k_s1": 2 * x["M"] * x["d"] * x["r"], "k_in": 2 * x["M"] * x["d"] * x["r"], "k_out": 2 * x["M"] * x["r"] * x["n"]}
-        kname = max(k, key=k.get)
+        kfl = {"k_s1": 2 * x["M"] * x["d"] * x["r"], "k_in": 2 * x["M"] * x["d"] * x["r"], "k_out": 2 * x["M"] * x["r"] * x["n"],
+               "k_s5": 2 * x["M"] * x["r"] * x["n"]}
+        kname = max((n_ for n_ in k if n_ in kfl), key=k.get)
         out = {"metric": METRIC, "value": x["flops"] / x["ms"] / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
                "warmup": args.warmup, "ms_per_step": x["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
                "dtype": "bf16", "data": "synthetic",
@@ -227,10 +267,12 @@ def main():
                "wall_ms_per_step": x["wall_ms"], "ms_per_step_with_kernel_events": x["ms_ev"], "kernels_ms": k,
                "roofline": {"bound": "mfma", "kernel": kname, "achieved": kfl[kname] / k[kname] / 1e9, "peak": PEAK_BF16_TFLOPS,
                             "unit": "TFLOP/s", "frac": kfl[kname] / k[kname] / 1e9 / PEAK_BF16_TFLOPS, "traffic": None,
-                            "per_kernel_TFLOPs": {n_: kfl[n_] / v / 1e9 for n_, v in k.items() if v}}}
+                            "per_kernel_TFLOPs": {n_: kfl[n_] / v / 1e9 for n_, v in k.items() if v and n_ in kfl}}}
         if "dense" in x:
             out["dense_baseline"] = x["dense"]
             out["dense_baseline"]["speedup_of_factored"] = x["dense"]["ms_per_step"] / x["ms"]
+            out["unfused_baseline"] = x["unfused"]
+            out["unfused_baseline"]["speedup_of_this_library"] = x["unfused"]["ms_per_step"] / x["ms"]
         print(json.dumps(out))
         return
 

@@ -71,6 +71,10 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
       const int64_t s1 = s1_splits(mt, r / 128, d);
       if (s1 > 1 && s1 * mt * 128 > prow) prow = s1 * mt * 128;
     }
+    for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {   // ... or k_in does
+      const int64_t si = in_splits(mt * 256, d, r);
+      if (si > 1 && si * mt * 256 > prow) prow = si * mt * 256;
+    }
     p->off_Tdp = take((size_t)prow * r * 4);
     p->total_bytes = off;
     return SVDMLP_OK;
@@ -107,6 +111,10 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   for (int64_t mt = 1; mt <= p->Mpad / 128; ++mt) {
     const int64_t s1 = s1_splits(mt, 2 * r / 128, d);
     if (s1 > 1 && (size_t)(s1 * mt * 128) * 2 * r * 4 > part_bytes) part_bytes = (size_t)(s1 * mt * 128) * 2 * r * 4;
+  }
+  for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {   // ... or k_in does
+    const int64_t si = in_splits(mt * 256, d, 2 * r);
+    if (si > 1 && (size_t)(si * mt * 256) * 2 * r * 4 > part_bytes) part_bytes = (size_t)(si * mt * 256) * 2 * r * 4;
   }
   p->off_Tdp = take(part_bytes);
   p->off_Td = take((size_t)p->Mpad * rd * 2);

@@ -165,6 +165,8 @@ int launch_down1(const Ctx* c, int MT256, int splits, hipStream_t st);
 int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st);
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 bool in_supported(int64_t M, int64_t d, int64_t ncols);
+int in_splits(int64_t M, int64_t d, int64_t ncols);
+int launch_reduce(const Ctx* c, const float* part, char* out, int splits, int MT32, int nq, hipStream_t st);
 int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_strip, hipStream_t st);
 int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int launch_out_generic(const Ctx* c, const char* act, const char* w, int64_t M, void* Y, int MT256, int64_t n, int64_t k,

@@ -513,18 +513,23 @@ __global__ __launch_bounds__(G_THREADS) void k_down1(const char* __restrict__ H,
 // T = X [Ug | Uu]   (paper Alg. 3, first loop nest; for kind LINEAR: T = X U), 256 rows x 256 rank columns per
 // workgroup, contraction over d.  X row-major [M, d] bf16; wU: [rank tile][d / 16] natural-order frags.
 // T: per 32-row tile two strips of r_strip / 16 chain-order frags each (rank columns below / from r_strip).
-// Used when there are enough 256 x 256 tiles to fill the chip; k_s1 (128 x 128 tiles) otherwise.
+// Used when there are enough 256 x 256 tiles to fill the chip; k_s1 (128 x 128 tiles) otherwise.  With S > 1 the
+// contraction is cut into S ranges (few tiles, long contraction): workgroup (tile, range) writes its fp32 tile to
+// Tpart in k_reduce's layout ([range][32-row tile][32-column tile][4 register groups][lane][4]) and k_reduce adds
+// the ranges and writes T.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(G_THREADS) void k_in(const uint16_t* __restrict__ X, int M, int d, const char* __restrict__ wU,
-                                                  int r_strip, char* __restrict__ T, int MT, int PT) {
+                                                  int r_strip, char* __restrict__ T, int MT, int PT, int S,
+                                                  float* __restrict__ Tpart) {
   __shared__ __attribute__((aligned(1024))) char lds[G_LDS];
   const int lane = threadIdx.x % 64;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const int wm = w / 4, wn = w % 4;
   const int L = xcd_contiguous_id(blockIdx.x, gridDim.x);
-  const int pt = L % PT, mt = L / PT;
+  const int sp = L % S, pt = (L / S) % PT, mt = L / (S * PT);
   const int KBd = d / 16, KBr = r_strip / 16;
-  const int total_steps = d / 32;
+  const int s0 = (d / 32) * sp / S, s1 = (d / 32) * (sp + 1) / S;   // steps of this range
+  const int total_steps = s1 - s0;
   const unsigned lds_off = lds_offset_of(lds);
 
   // producer: rows 16 w + lane / 4 of each half of the tile, one 16-byte piece per lane (rows beyond M re-read row
@@ -534,8 +539,8 @@ __global__ __launch_bounds__(G_THREADS) void k_in(const uint16_t* __restrict__ X
   rowA = rowA < M ? rowA : M - 1;
   rowB = rowB < M ? rowB : M - 1;
   const unsigned voffA = (unsigned)rowA * (unsigned)d * 2u + piece * 16, voffB = (unsigned)rowB * (unsigned)d * 2u + piece * 16;
-  const char* bx = reinterpret_cast<const char*>(X);
-  const char* pw = wU + (long long)(8 * pt + w) * KBd * FRAG_BYTES;
+  const char* bx = reinterpret_cast<const char*>(X) + (long long)s0 * 64;
+  const char* pw = wU + ((long long)(8 * pt + w) * KBd + 2 * s0) * FRAG_BYTES;
   const unsigned lane16 = lane * 16;
   const unsigned dst = lds_off + w * FRAG_BYTES, dstw = lds_off + (8 + w) * FRAG_BYTES;
   int pslot = 0, issued = 0;
@@ -582,6 +587,24 @@ __global__ __launch_bounds__(G_THREADS) void k_in(const uint16_t* __restrict__ X
   }
   if (w < 4) lds_barrier();
 
+  if (S > 1) {
+    const long long MT32 = 8LL * MT;
+    const int nq = 8 * PT;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const long long mtile = 8 * mt + 4 * wm + j;
+        const int q = 8 * pt + 2 * wn + i;
+        f32x4* dstp = reinterpret_cast<f32x4*>(Tpart + (((long long)sp * MT32 + mtile) * nq + q) * 1024) + lane;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          dstp[g * 64] = v;
+        }
+      }
+    return;
+  }
   // registers 8t..8t+7 of tile (i, j) are the chain-order frag of rank contraction block 2 (rank tile) + t, row tile j
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
@@ -745,20 +768,34 @@ int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st) {
   return launch_out_generic(c, c->ws + p.off_Td, c->ws + p.off_wVd, M, Y, MT256, p.d, p.rd, st);
 }
 
-// ncols = rank columns of the product (2 r gated, r linear); r_strip = columns per strip of T
-bool in_supported(int64_t M, int64_t d, int64_t ncols) {
-  // 256 x 256 tiles must keep at least 70 % of the 256 CUs busy over their rounds (k_s1 with its 128 x 128 tiles
-  // reaches about 0.63 of this kernel's rate and fills the chip at any size); 32-bit byte offsets into X
-  if (ncols % 256 || d % 64 || M * d * 2 >= (int64_t(1) << 32)) return false;
+// ncols = rank columns of the product (2 r gated, r linear); r_strip = columns per strip of T.
+// 0: k_s1 does the first stage; 1: k_in over the whole contraction; S > 1: k_in with the contraction cut into S ranges.
+int in_splits(int64_t M, int64_t d, int64_t ncols) {
+  M = (M + 255) / 256 * 256;   // the answer depends on the number of row tiles only (the workspace is sized from it)
+  // 32-bit byte offsets into X
+  if (ncols % 256 || d % 64 || M * d * 2 >= (int64_t(1) << 32)) return 0;
   const int64_t tiles = ((M + 255) / 256) * (ncols / 256), rounds = (tiles + 255) / 256;
-  return tiles * 10 >= rounds * 256 * 7;
+  // 256 x 256 tiles must keep at least 70 % of the 256 CUs busy over their rounds (k_s1 with its 128 x 128 tiles
+  // reaches about 0.63 of this kernel's rate and fills the chip at any size)
+  if (tiles * 10 >= rounds * 256 * 7) return 1;
+  // Few tiles: ranges of the contraction fill the chip instead, at the price of writing and re-reading fp32 tiles
+  // (8 S bytes per element of T against 2 d / S contraction steps' worth of MFMAs): only for long ranges.
+  int64_t S = 256 / tiles;
+  if (S > 8) S = 8;
+  while (S > 1 && d / S < 2048) --S;
+  return S > 1 && tiles * S * 10 >= 256 * 7 ? (int)S : 0;
 }
+bool in_supported(int64_t M, int64_t d, int64_t ncols) { return in_splits(M, d, ncols) >= 1; }
 int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_strip, hipStream_t st) {
   const Plan& p = c->plan;
   const int MT = (int)((M + 255) / 256), PT = (int)(ncols / 256);
-  hipLaunchKernelGGL(k_in, dim3(MT * PT), dim3(G_THREADS), 0, st, (const uint16_t*)X, (int)M, (int)p.d, c->ws + p.off_wU,
-                     (int)r_strip, c->ws + p.off_T, MT, PT);
-  return (int)hipGetLastError();
+  const int S = in_splits(M, p.d, ncols);
+  if (S < 1) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_in, dim3(MT * PT * S), dim3(G_THREADS), 0, st, (const uint16_t*)X, (int)M, (int)p.d, c->ws + p.off_wU,
+                     (int)r_strip, c->ws + p.off_T, MT, PT, S, reinterpret_cast<float*>(c->ws + p.off_Tdp));
+  int e = (int)hipGetLastError();
+  if (e || S == 1) return e;
+  return launch_reduce(c, reinterpret_cast<const float*>(c->ws + p.off_Tdp), c->ws + p.off_T, S, 8 * MT, (int)(ncols / 32), st);
 }
 
 }  // namespace svdmlp

@@ -625,6 +625,13 @@ int s1_splits(int64_t mt128, int64_t pt, int64_t d) {
   return s < 1 ? 1 : (int)s;
 }
 
+int launch_reduce(const Ctx* c, const float* part, char* out, int splits, int MT32, int nq, hipStream_t st) {
+  (void)c;
+  const long long threads = (long long)MT32 * nq * 2 * 64;
+  hipLaunchKernelGGL(k_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, part, out, splits, MT32, nq);
+  return (int)hipGetLastError();
+}
+
 // First stage T = X [Ug|Uu] (ncols = 2 r_strip rank columns in two strips): k_in when its 256 x 256 tiles fill the
 // chip, else k_s1, with its contraction cut into ranges (+ k_reduce) when there are few tiles.
 static int first_stage(const Ctx* c, const void* X, int64_t M, int64_t r_strip, hipStream_t st) {

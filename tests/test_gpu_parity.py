@@ -160,6 +160,45 @@ def test_bf16_gated_many_tiles_uses_256_tile_first_stage():
     assert relmax(Yf, ref) <= BF16_TOL
 
 
+def kernel_names(mlp, X):
+    """Names of the kernels one forward launches (from the library's per-kernel event profile)."""
+    B.svdmlp_profile_begin(mlp.ctx, 1)
+    mlp(X)
+    k, _ = B.svdmlp_profile_end(mlp.ctx)
+    return list(k)
+
+
+def test_bf16_first_stage_cuts_a_long_contraction_when_tiles_are_few():
+    """32 tiles (256 x 256) of T and d = 16384: the eight-wave first-stage kernel runs over eight ranges of d and
+    k_reduce adds them (linear layer and gated MLP); ragged M; the oracle evaluates a sample of rows."""
+    dv = dev()
+    rows = list(range(0, 1000, 37)) + [255, 256, 999]
+    li = synth.make_linear_gaussian(1000, 16384, 2048, 2048, stream=46)
+    mlp = B.SvdMlp(max_M=1000, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
+    Xd = li.X.to(dv)
+    assert kernel_names(mlp, Xd)[0] == "k_in"
+    O = mlp(Xd)
+    torch.cuda.synchronize()
+    Oh = O[rows].cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.linear(synth.to_f64(li.X)[rows], synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
+
+    gi = synth.make_gated(1000, 16384, 1024, 1024, 256, stream=47)
+    f = {k: v.to(dv) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=1000, **f)
+    Xd = gi.X.to(dv)
+    assert kernel_names(mlp, Xd)[0] == "k_in"
+    Y = mlp(Xd)
+    Y2 = mlp(Xd)
+    torch.cuda.synchronize()
+    assert mlp.last_path == 5 and torch.equal(Y, Y2)
+    Yh = Y[rows].cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.gated(synth.to_f64(gi.X)[rows], **{k: synth.to_f64(v) for k, v in gi.factors().items()})
+    assert relmax(Yh, ref) <= BF16_TOL, relmax(Yh, ref)
+
+
 def test_bf16_linear_paper_kernel_shape_sampled_rows():
     """The paper's kernel-evaluation shape X[M,8192] U[8192,4096] V[4096,16384] (Sec. 5.2) at M = 1024; the
     oracle evaluates a sample of rows."""
