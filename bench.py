@@ -176,6 +176,21 @@ def bench_dense(dev, M, d, ffn, steps, warmup):
     return dict(ms_per_step=ms, TFLOPs=fl / ms / 1e9, flops=fl, provider="torch.matmul (third-party GEMM)")
 
 
+def bench_unfused(gi, dev, steps, warmup):
+    """The same factored MLP as six separate GEMMs plus one elementwise kernel (torch.matmul / torch ops: third party),
+    every intermediate (T, G, P, H, Td) through HBM: the counterpart of the paper's unfused "XUV" baseline."""
+    f = {k: v.to(dev) for k, v in gi.factors().items()}
+    X = gi.X.to(dev)
+
+    def step():
+        G = (X @ f["Ug"]) @ f["Vg"]
+        P = (X @ f["Uu"]) @ f["Vu"]
+        return ((torch.nn.functional.silu(G) * P) @ f["Ud"]) @ f["Vd"]
+
+    ms, _ = time_steps(step, steps, warmup)
+    return dict(ms_per_step=ms, provider="six torch.matmul calls + silu * mul (third-party kernels)")
+
+
 def cpu_baseline(gi, target_seconds=12.0):
     """The fp64 oracle as it stands, timed on the host cores on a bounded sample of rows of the same workload."""
     import oracle
@@ -350,6 +365,8 @@ def main():
     if not args.no_dense and args.workload != "decode":
         out["dense_baseline"] = bench_dense(dev, M, d, ffn, max(5, args.steps // 3), 3)
         out["dense_baseline"]["speedup_of_factored"] = out["dense_baseline"]["ms_per_step"] / ms
+        out["unfused_baseline"] = bench_unfused(gi, dev, max(5, args.steps // 3), 3)
+        out["unfused_baseline"]["speedup_of_this_library"] = out["unfused_baseline"]["ms_per_step"] / ms
     out["paper_context"] = {"kernel_speedup_vs_nki": 1.35, "e2e_speedup": 1.21, "hardware": "AWS Trainium trn1",
                             "note": "paper figures for its own kernels; not the target"}
     if args.copy_calibration:
