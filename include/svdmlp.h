@@ -110,6 +110,14 @@ int svdmlp_destroy(svdmlp_ctx *ctx);
 /* Static, never-NULL description of a status code. */
 const char *svdmlp_status_string(int status);
 
+/* Host only, no device needed: writes into buf (NUL-terminated, at most buf_bytes) one line that names the path a
+ * forward of M rows on a context of this description takes, its kernels in launch order and how each is cut over
+ * the chip (tile shape, number of tiles, contraction ranges, persistent workgroups): the planner's counterpart of the
+ * block-size choice of the paper's Sec. 4.2.2, evaluated for a 256-CU device.  Returns SVDMLP_OK, the status
+ * svdmlp_create would return for desc (the workspace fields are not looked at), or SVDMLP_INVALID_ARGUMENT if M is not
+ * in 1..max_M or the line does not fit. */
+int svdmlp_describe(const svdmlp_desc *desc, int64_t M, char *buf, size_t buf_bytes);
+
 /* The hipError_t (as int) of the last failing HIP call made for this context (0 if none). */
 int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
 

@@ -26,7 +26,7 @@ FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK, FLAG_STREAM_ONE_KERNE
 
 EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_status_string",
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
-           "svdmlp_profile_end", "svdmlp_profile_kernel_name"]
+           "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_profile_end.restype = ctypes.c_int
         L.svdmlp_profile_kernel_name.argtypes = [ctypes.c_void_p, ctypes.c_int]
         L.svdmlp_profile_kernel_name.restype = ctypes.c_char_p
+        L.svdmlp_describe.argtypes = [ctypes.POINTER(svdmlp_desc), ctypes.c_int64, ctypes.c_char_p, ctypes.c_size_t]
+        L.svdmlp_describe.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -89,6 +91,14 @@ def status_string(status: int) -> str:
 
 def svdmlp_workspace_bytes(desc: svdmlp_desc) -> int:
     return int(lib().svdmlp_workspace_bytes(ctypes.byref(desc)))
+
+
+def svdmlp_describe(desc: svdmlp_desc, M: int) -> str:
+    buf = ctypes.create_string_buffer(1024)
+    st = lib().svdmlp_describe(ctypes.byref(desc), int(M), buf, len(buf))
+    if st != SVDMLP_OK:
+        raise SvdMlpError(st, "svdmlp_describe")
+    return buf.value.decode()
 
 
 def svdmlp_create(desc: svdmlp_desc) -> ctypes.c_void_p:

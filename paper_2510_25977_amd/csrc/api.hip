@@ -2,6 +2,7 @@
 // Host code only; every arithmetic step of the forward runs in the kernels of the other files.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstring>
 #include <new>
 
@@ -153,6 +154,74 @@ size_t svdmlp_workspace_bytes(const svdmlp_desc* desc) {
   Plan p;
   if (make_plan(desc, &p) != SVDMLP_OK) return 0;
   return p.total_bytes;
+}
+
+// Which kernels a forward of M rows launches and how each one is cut over the chip: the same decision functions
+// the launchers call, evaluated for a 256-CU device.  Host only.
+int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_bytes) {
+  if (!desc || !buf || buf_bytes == 0) return SVDMLP_INVALID_ARGUMENT;
+  buf[0] = 0;
+  Plan p;
+  const int st = make_plan(desc, &p);
+  if (st != SVDMLP_OK) return st;
+  if (M <= 0 || M > p.max_M) return SVDMLP_INVALID_ARGUMENT;
+  size_t n = 0;
+  auto put = [&](const char* fmt, auto... a) {
+    if (n < buf_bytes) {
+      const int k = std::snprintf(buf + n, buf_bytes - n, fmt, a...);
+      if (k > 0) n += (size_t)k;
+    }
+  };
+  const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
+  auto first_stage = [&](int64_t ncols) {
+    const int S = in_splits(M, p.d, ncols);
+    if (S >= 1) {
+      put(" k_in[tile=256x256 tiles=%d ranges=%d]", MT256 * (int)(ncols / 256), S);
+      if (S > 1) put(" k_reduce");
+    } else {
+      const int PT = (int)(ncols / 128), S1 = s1_splits(MT128, PT, p.d);
+      put(" k_s1[tile=128x128 tiles=%d ranges=%d]", MT128 * PT, S1);
+      if (S1 > 1) put(" k_reduce");
+    }
+  };
+  if (p.dtype == SVDMLP_F32) {
+    put("path=1 fp32-debug:%s", p.kind == SVDMLP_GATED ? " k_f32_gemm x5 (SiLU-gate epilogue in the third)" : " k_f32_gemm x2");
+  } else if (p.kind == SVDMLP_LINEAR) {
+    put("path=6 bf16-linear:");
+    first_stage(p.r);
+    if (p.ffn % 256 == 0) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.ffn / 256));
+    else put(" k_s5[tile=128x128 tiles=%d]", MT128 * (int)(p.ffn / 128));
+  } else {
+    bool stream_path = M <= STREAM_MAX_M;
+    if (p.flags & SVDMLP_FLAG_FORCE_TILED) stream_path = false;
+    if (p.flags & SVDMLP_FLAG_FORCE_STREAM) {
+      if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+      stream_path = true;
+    }
+    if (stream_path) {
+      const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;
+      const int t1 = (int)(2 * p.r / 32), t2 = (int)(p.ffn / 32), t4 = (int)(p.rd / 32), t5 = (int)(p.d / 32);
+      put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tiles=%d ranges=%d] k_stream_d2[tiles=%d] k_stream_d4[tiles=%d ranges=%d]"
+          " k_stream_d5[tiles=%d]", rt, t1, stream_splits(t1, (int)(p.d / 16), rt), t2, t4, stream_splits(t4, (int)(p.ffn / 16), rt), t5);
+      if ((p.flags & SVDMLP_FLAG_STREAM_ONE_KERNEL) && M <= 32) put(" (one persistent kernel, path=4, if the device and the extents allow)");
+    } else if (staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED)) {
+      put("path=5 bf16-tiled-staged:");
+      first_stage(2 * p.r);
+      const GuPlan g = gate_up_plan(MT256, p.ffn, p.r, 256);
+      put(" k_gate_up[tile=256x256 tiles=%d workgroups=%d full=%d halves=%d xcd_grid=%dx%d]", g.ntiles, g.G, g.nfull,
+          g.halves ? 2 * g.rem : 0, g.ngm, g.ngm ? 8 / g.ngm : 0);
+      const int splits = gemm_splits(MT256, p.rd / 256, p.ffn / 32);
+      put(" k_down1[tile=256x256 tiles=%d ranges=%d] k_reduce", MT256 * (int)(p.rd / 256), splits);
+      if (p.d % 256 == 0) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.d / 256));
+      else put(" k_s5[tile=128x128 tiles=%d]", MT128 * (int)(p.d / 128));
+    } else {
+      put("path=2 bf16-tiled-fused:");
+      first_stage(2 * p.r);
+      put(" k_fused[rows=128 row_tiles=%d ffn_ranges=%d] k_reduce k_s5[tile=128x128 tiles=%d]", MT128,
+          tiled_splits(MT128, p.ffn / 64), MT128 * (int)(p.d / 128));
+    }
+  }
+  return n < buf_bytes ? SVDMLP_OK : SVDMLP_INVALID_ARGUMENT;
 }
 
 int svdmlp_create(const svdmlp_desc* desc, svdmlp_ctx** out) {

@@ -160,6 +160,10 @@ int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps);
 struct Ctx;
 int f32_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_repack_all(const Ctx* c, hipStream_t st);
+// schedule of k_gate_up: XCD grid (mx row tiles per XCD, ngm row groups; 0 = plain order), persistent workgroups G,
+// tiles run as full 256-row tiles (nfull) and leftover tiles run as two 128-row halves each (rem, if halves)
+struct GuPlan { int mx, ngm, ntiles, G, nfull, rem; bool halves; };
+GuPlan gate_up_plan(int MT256, int64_t ffn, int64_t r, int ncu);
 int launch_gate_up(const Ctx* c, int MT256, hipStream_t st);
 int launch_down1(const Ctx* c, int MT256, int splits, hipStream_t st);
 int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st);
@@ -177,7 +181,9 @@ int launch_out_generic(const Ctx* c, const char* act, const char* w, int64_t M, 
 constexpr size_t CNT_ONE_KERNEL_BYTES = 32768 + 3 * 256 * 128;
 constexpr int TICKET_STRIDE = 32;   // ints
 constexpr size_t CNT_BYTES = CNT_ONE_KERNEL_BYTES + 2 * 2048 * TICKET_STRIDE * 4;
-constexpr int STREAM_MAX_M = 128;   // rows the weight-streaming path takes (four 32-row tiles)
+constexpr int STREAM_MAX_M = 128;
+// workgroup-level contraction ranges of a streaming-path phase with `tiles` output tiles, KB contraction blocks, rt row tiles
+int stream_splits(int tiles, int KB, int rt);   // rows the weight-streaming path takes (four 32-row tiles)
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 bool bf16_decode_supported(const Ctx* c);

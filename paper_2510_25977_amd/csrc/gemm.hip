@@ -714,33 +714,42 @@ int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps) {
   return (int)s;
 }
 
+GuPlan gate_up_plan(int MT256, int64_t ffn, int64_t r, int ncu) {
+  GuPlan g;
+  const int NT = (int)(ffn / 256);
+  // the most row tiles per XCD whose strips (256 x 2r bf16 each) fit in half of its 4 MiB L2
+  g.mx = 0;
+  g.ngm = 0;
+  const long long strip = 256LL * 2 * r * 2;
+  for (int m = 8; m >= 1; m /= 2) {
+    if (MT256 % m || m * strip > (2LL << 20)) continue;
+    const int gr = MT256 / m;
+    if (gr > 8 || 8 % gr || NT % (8 / gr)) continue;
+    g.mx = m;
+    g.ngm = gr;
+    break;
+  }
+  if (ncu <= 0) ncu = 256;
+  g.ntiles = MT256 * NT;
+  g.G = g.ntiles < ncu ? g.ntiles : ncu;  // persistent: one workgroup per CU
+  const int q = g.ntiles / g.G;
+  g.rem = g.ntiles % g.G;
+  g.halves = g.rem > 0 && 2 * g.rem <= g.G && q > 0;  // see GuSched
+  g.nfull = g.halves ? q * g.G : g.ntiles;
+  return g;
+}
+
 int launch_gate_up(const Ctx* c, int MT256, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
   const int NT = (int)(p.ffn / 256);
-  // the most row tiles per XCD whose strips (256 x 2r bf16 each) fit in half of its 4 MiB L2
-  int mx = 0, ngm = 0;
-  const long long strip = 256LL * 2 * p.r * 2;
-  for (int m = 8; m >= 1; m /= 2) {
-    if (MT256 % m || m * strip > (2LL << 20)) continue;
-    const int g = MT256 / m;
-    if (g > 8 || 8 % g || NT % (8 / g)) continue;
-    mx = m;
-    ngm = g;
-    break;
-  }
-  const int ncu = c->n_cus > 0 ? c->n_cus : 256;
-  const int ntiles = MT256 * NT;
-  const int G = ntiles < ncu ? ntiles : ncu;  // persistent: one workgroup per CU
-  const int q = ntiles / G, rem = ntiles % G;
-  const bool halves = rem > 0 && 2 * rem <= G && q > 0;  // see GuSched
-  const int nfull = halves ? q * G : ntiles;
-  hipLaunchKernelGGL(k_gate_up<false>, dim3(G), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
-                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, mx, ngm, nfull, 0, 0);
+  const GuPlan g = gate_up_plan(MT256, p.ffn, p.r, c->n_cus);
+  hipLaunchKernelGGL(k_gate_up<false>, dim3(g.G), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
+                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.nfull, 0, 0);
   int e = (int)hipGetLastError();
-  if (e || !halves) return e;
-  hipLaunchKernelGGL(k_gate_up<true>, dim3(2 * rem), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
-                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, mx, ngm, ntiles, nfull, rem);
+  if (e || !g.halves) return e;
+  hipLaunchKernelGGL(k_gate_up<true>, dim3(2 * g.rem), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
+                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.ntiles, g.nfull, g.rem);
   return (int)hipGetLastError();
 }
 

@@ -225,12 +225,15 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
   *reinterpret_cast<bf16x8*>(static_cast<char*>(a.out) + (frag * 64 + lane) * 16) = o;
 }
 
-static int pick_splits(int tiles, int KB) {
+int stream_splits(int tiles, int KB, int rt) {
   int s = (256 + tiles - 1) / tiles;      // aim at one workgroup per CU
   int smax = KB / SW;                     // at least one contraction block per wave
   if (s > smax) s = smax;
   if (s > 64) s = 64;
-  return s < 1 ? 1 : s;
+  if (s < 1) s = 1;
+  const size_t part_floats = ((size_t)8 << 20) / 4;   // the partial-tile buffer of the workspace
+  while (s > 1 && (size_t)tiles * s * rt * 1024 > part_floats) --s;
+  return s;
 }
 
 template <int PH>
@@ -246,7 +249,6 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   char* ws = c->ws;
   int* cnt = reinterpret_cast<int*>(ws + p.off_cnt + CNT_ONE_KERNEL_BYTES);
   float* part = reinterpret_cast<float*>(ws + p.off_part);
-  const size_t part_floats = ((size_t)8 << 20) / 4;
   if (M > STREAM_MAX_M) return (int)hipErrorInvalidValue;
   const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;   // 32-row tiles the batch is padded to
   int e;
@@ -258,8 +260,7 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   // D1
   a = StreamArgs{ws + p.off_wU, nullptr, X, ws + p.off_T, part, cnt, (int)M, (int)(p.d / 16), (int)(2 * p.r / 32), 1,
                  (int)p.d, (int)p.r, 0, 0, fT};
-  a.S = pick_splits(a.tiles, a.KB);
-  while (a.S > 1 && (size_t)a.tiles * a.S * rt * 1024 > part_floats) --a.S;
+  a.S = stream_splits(a.tiles, a.KB, rt);
   if (a.tiles > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 0, 0, st);
   launch_stream<PH_D1>(rt, a, st);
@@ -275,8 +276,7 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   // D4
   a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048 * TICKET_STRIDE, (int)M, (int)(p.ffn / 16),
                  (int)(p.rd / 32), 1, 0, (int)p.r, 1, fH, fTd};
-  a.S = pick_splits(a.tiles, a.KB);
-  while (a.S > 1 && (size_t)a.tiles * a.S * rt * 1024 > part_floats) --a.S;
+  a.S = stream_splits(a.tiles, a.KB, rt);
   if (a.tiles > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 2, 0, st);
   launch_stream<PH_D4>(rt, a, st);

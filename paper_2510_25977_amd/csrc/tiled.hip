@@ -694,9 +694,8 @@ int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   char* ws = c->ws;
   const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
   const int PT = (int)(p.r / 128);
-  static const char* const names_s1[2] = {"k_s1", "k_out"};
-  static const char* const names_in[2] = {"k_in", "k_out"};
-  const int ps = prof_open_forward(c, 2, in_supported(M, p.d, p.r) ? names_in : names_s1);
+  const char* const names[2] = {in_supported(M, p.d, p.r) ? "k_in" : "k_s1", p.ffn % 256 == 0 ? "k_out" : "k_s5"};
+  const int ps = prof_open_forward(c, 2, names);
   int e;
   prof_mark(c, ps, 0, 0, st);
   e = first_stage(c, X, M, p.r / 2, st);
@@ -722,11 +721,11 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   const int PT = (int)(2 * p.r / 128);
   int e;
   const bool big = in_supported(M, p.d, 2 * p.r);
-  static const char* const names_fused[2][4] = {{"k_s1", "k_fused", "k_reduce", "k_s5"}, {"k_in", "k_fused", "k_reduce", "k_s5"}};
-  static const char* const names_staged[2][5] = {{"k_s1", "k_gate_up", "k_down1", "k_reduce", "k_out"},
-                                                 {"k_in", "k_gate_up", "k_down1", "k_reduce", "k_out"}};
+  const char* const s1name = big ? "k_in" : "k_s1";
+  const char* const names_fused[4] = {s1name, "k_fused", "k_reduce", "k_s5"};
+  const char* const names_staged[5] = {s1name, "k_gate_up", "k_down1", "k_reduce", p.d % 256 == 0 ? "k_out" : "k_s5"};
   const bool staged = staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
-  const int ps = staged ? prof_open_forward(c, 5, names_staged[big]) : prof_open_forward(c, 4, names_fused[big]);
+  const int ps = staged ? prof_open_forward(c, 5, names_staged) : prof_open_forward(c, 4, names_fused);
   prof_mark(c, ps, 0, 0, st);
   e = first_stage(c, X, M, p.r, st);
   prof_mark(c, ps, 0, 1, st);

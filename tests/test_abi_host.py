@@ -132,3 +132,47 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")
     with pytest.raises(FileNotFoundError):
         B.lib()
+
+
+def test_describe_names_the_plan_of_every_baseline_config():
+    """svdmlp_describe is host-only: the planner's choices for the BASELINE configurations, pinned so that a change
+    of a heuristic shows up here (tile shapes, contraction ranges, persistent workgroups, half-tile round)."""
+    pre = desc(max_M=4096, d=4096, ffn=14336, r=512, r_down=512)
+    s = B.svdmlp_describe(pre, 4096)
+    assert s.startswith("path=5 bf16-tiled-staged:")
+    assert "k_s1[tile=128x128 tiles=256 ranges=1]" in s
+    assert "k_gate_up[tile=256x256 tiles=896 workgroups=256 full=768 halves=256 xcd_grid=4x2]" in s
+    assert "k_down1[tile=256x256 tiles=32 ranges=8] k_reduce k_out[tile=256x256 tiles=256]" in s
+    # decode shape: one row tile, both split phases fill the chip
+    s = B.svdmlp_describe(pre, 16)
+    assert s.startswith("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tiles=32 ranges=8] k_stream_d2[tiles=448]")
+    assert "k_stream_d4[tiles=16 ranges=16] k_stream_d5[tiles=128]" in s
+    assert "row_tiles=2" in B.svdmlp_describe(pre, 64) and "row_tiles=4" in B.svdmlp_describe(pre, 128)
+    assert B.svdmlp_describe(pre, 129).startswith("path=5")
+    # config 2 (M = 128) streams; forced onto the tiled path it has one row tile
+    small = desc(max_M=128, d=2048, ffn=8192, r=256, r_down=256)
+    assert B.svdmlp_describe(small, 128).startswith("path=3 bf16-streaming: row_tiles=4")
+    small.flags |= B.FLAG_FORCE_TILED
+    assert "k_gate_up[tile=256x256 tiles=32 workgroups=32 full=32 halves=0" in B.svdmlp_describe(small, 128)
+    # wide config: 8 row tiles x 108 column tiles = 3 full rounds + 96 tiles as 192 halves
+    wide = desc(max_M=2048, d=5120, ffn=27648, r=1024, r_down=1024)
+    s = B.svdmlp_describe(wide, 2048)
+    assert "k_gate_up[tile=256x256 tiles=864 workgroups=256 full=768 halves=192" in s
+    # fused variant on request, and for extents the staged one does not take
+    pre.flags |= B.FLAG_TILED_FUSED
+    assert B.svdmlp_describe(pre, 4096).startswith("path=2 bf16-tiled-fused:")
+    odd = desc(max_M=512, d=256, ffn=384, r=128, r_down=128)
+    assert B.svdmlp_describe(odd, 512).startswith("path=2")
+    # single factored layer at the paper's kernel-evaluation shape: the first stage cuts d when tiles are few
+    lin = desc(kind=B.SVDMLP_LINEAR, max_M=32768, d=8192, ffn=16384, r=4096, r_down=0)
+    assert "k_in[tile=256x256 tiles=64 ranges=4] k_reduce k_out" in B.svdmlp_describe(lin, 1024)
+    assert "k_in[tile=256x256 tiles=256 ranges=1] k_out[tile=256x256 tiles=1024]" in B.svdmlp_describe(lin, 4096)
+    f32 = desc(dtype=B.SVDMLP_F32, max_M=10, d=96, ffn=200, r=24, r_down=40)
+    assert B.svdmlp_describe(f32, 10).startswith("path=1")
+    # errors
+    with pytest.raises(B.SvdMlpError) as e:
+        B.svdmlp_describe(pre, 5000)
+    assert e.value.status == B.SVDMLP_INVALID_ARGUMENT
+    with pytest.raises(B.SvdMlpError) as e:
+        B.svdmlp_describe(desc(r_down=192), 8)
+    assert e.value.status == B.SVDMLP_UNSUPPORTED

@@ -406,3 +406,25 @@ def test_zero_input_gives_zero_output():
         torch.cuda.synchronize()
         assert torch.all(Y == 0)
         mlp.close()
+
+
+@pytest.mark.parametrize("M,d,ffn,r,rd,flags", [
+    (300, 512, 1024, 192, 256, 0), (300, 384, 512, 128, 256, 0), (200, 256, 384, 128, 128, 0),
+    (300, 512, 1024, 192, 256, B.FLAG_TILED_FUSED), (100, 512, 1408, 192, 256, 0), (1000, 16384, 1024, 1024, 256, 0),
+])
+def test_describe_matches_the_kernels_that_run(M, d, ffn, r, rd, flags):
+    """The host-only plan description names exactly the kernels a forward launches, in order."""
+    import re
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=48)
+    dv = dev()
+    f = {k: v.to(dv) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=M, flags=flags, **f)
+    text = B.svdmlp_describe(mlp.desc, M)
+    ran = kernel_names(mlp, gi.X.to(dv))
+    assert int(re.match(r"path=(\d)", text).group(1)) == mlp.last_path
+    mlp.close()
+    said = re.findall(r" (k_[a-z0-9_]+)", text)
+    # the reduction that follows a first stage cut into ranges is timed together with it
+    if len(said) > 1 and said[1] == "k_reduce" and said[0] in ("k_in", "k_s1"):
+        said.pop(1)
+    assert said == ran, (text, ran)
