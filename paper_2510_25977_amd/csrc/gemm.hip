@@ -216,6 +216,13 @@ __device__ __forceinline__ void store16_sv(char* sbase, unsigned voff, const u32
   asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(voff), "v"(v), "s"(sbase) : "memory");
 }
 
+// The same with the non-temporal hint, for data that is written once and read by a later kernel (the gated
+// activation): the lines do not stay dirty in the writer's L2, which measurably shortens both this kernel and its
+// consumer.
+__device__ __forceinline__ void store16_sv_nt(char* sbase, unsigned voff, const u32x4& v) {
+  asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" ::"v"(voff), "v"(v), "s"(sbase) : "memory");
+}
+
 __device__ __forceinline__ unsigned silu_pair(float g0, float g1) {
   const float s0 = g0 * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g0 * -1.44269504088896f));
   const float s1 = g1 * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g1 * -1.44269504088896f));
@@ -434,7 +441,7 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
           u32x4 v = S[(a * 4 + b) * 2 + t2];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = mul_pair(v[e], acc[a][b][8 * t2 + 2 * e], acc[a][b][8 * t2 + 2 * e + 1]);
-          store16_sv(hbase + ((long long)(2 * a + t2) * 8 + b) * FRAG_BYTES, gp.prod.lane16, v);
+          store16_sv_nt(hbase + ((long long)(2 * a + t2) * 8 + b) * FRAG_BYTES, gp.prod.lane16, v);
         }
   }
   if (w < 4) lds_barrier();  // matches the extra barrier of waves 4..7
