@@ -23,7 +23,8 @@ int tiled_splits(int64_t mtiles128, int64_t nchunks) {
 
 bool staged_supported(int64_t rd, int64_t ffn) { return rd % 256 == 0 && ffn % 256 == 0; }
 
-static bool pow2_upto16(int64_t x) { return x == 2 || x == 4 || x == 8 || x == 16; }
+// 32-column tiles of the down rank that one workgroup of the fused tiled kernel can own
+static bool fused_rank_tiles(int64_t x) { return x == 4 || x == 8 || x == 16; }
 
 int make_plan(const svdmlp_desc* de, Plan* p) {
   if (!de || !p) return SVDMLP_INVALID_ARGUMENT;
@@ -83,7 +84,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   const int64_t d = de->d, ffn = de->ffn, r = de->r, rd = p->rd;
   if (d % 128 || ffn % 128 || r % 64 || r < 128) return SVDMLP_UNSUPPORTED;
   const int64_t nq = rd / 32;
-  if (rd % 64 || !(pow2_upto16(nq) || rd % 512 == 0)) return SVDMLP_UNSUPPORTED;
+  if (rd % 64 || !(fused_rank_tiles(nq) || rd % 512 == 0)) return SVDMLP_UNSUPPORTED;
 
   p->Mpad = (de->max_M + 255) / 256 * 256;
   size_t off = 0;

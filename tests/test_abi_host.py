@@ -91,7 +91,8 @@ def test_workspace_bytes_formula(lib):
     (dict(d=200), B.SVDMLP_UNSUPPORTED),                       # bf16 needs d % 128 == 0
     (dict(r=48), B.SVDMLP_UNSUPPORTED),                        # bf16 needs r % 64 == 0
     (dict(r=64), B.SVDMLP_UNSUPPORTED),                        # ... and r >= 128
-    (dict(r_down=192), B.SVDMLP_UNSUPPORTED),                  # r_down / 32 must be 2,4,8,16 or r_down % 512 == 0
+    (dict(r_down=192), B.SVDMLP_UNSUPPORTED),                  # r_down must be 128, 256, 512 or a multiple of 512
+    (dict(r_down=64), B.SVDMLP_UNSUPPORTED),
     (dict(kind=B.SVDMLP_LINEAR, r=64), B.SVDMLP_UNSUPPORTED),  # bf16 LINEAR needs r % 128 == 0
     (dict(flags=B.FLAG_SKIP_ARCH_CHECK | B.FLAG_FORCE_TILED | B.FLAG_FORCE_STREAM), B.SVDMLP_INVALID_ARGUMENT),
 ])

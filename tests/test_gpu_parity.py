@@ -428,3 +428,40 @@ def test_describe_matches_the_kernels_that_run(M, d, ffn, r, rd, flags):
     if len(said) > 1 and said[1] == "k_reduce" and said[0] in ("k_in", "k_s1"):
         said.pop(1)
     assert said == ran, (text, ran)
+
+
+def _random_shapes(n, seed):
+    """Seeded draw from the lattice of supported bf16 extents (d, ffn multiples of 128; r a multiple of 64, >= 128;
+    r_down in {128, 256, 512}), M anywhere from one row to a few row tiles."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        d = 128 * int(rng.integers(1, 9))
+        ffn = 128 * int(rng.integers(1, 13))
+        lim = min(d, ffn)
+        if lim < 128:
+            continue
+        r = 64 * int(rng.integers(2, lim // 64 + 1))
+        rd_choices = [x for x in (128, 256, 512) if x <= lim]
+        rd = int(rng.choice(rd_choices))
+        M = int(rng.choice([int(rng.integers(1, 33)), int(rng.integers(33, 129)), int(rng.integers(129, 700))]))
+        out.append((M, d, ffn, r, rd))
+    return out
+
+
+@pytest.mark.parametrize("M,d,ffn,r,rd", _random_shapes(24, 20251025))
+def test_bf16_random_supported_extents(M, d, ffn, r, rd):
+    """Whatever path the planner picks for a supported extent, the result matches the oracle; the plan description
+    agrees with the path taken."""
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=60)
+    dv = dev()
+    f = {k: v.to(dv) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=M, **f)
+    Y = mlp(gi.X.to(dv))
+    torch.cuda.synchronize()
+    path = mlp.last_path
+    assert B.svdmlp_describe(mlp.desc, M).startswith(f"path={path} ")
+    mlp.close()
+    ref = oracle.gated(synth.to_f64(gi.X), **{k: synth.to_f64(v) for k, v in gi.factors().items()})
+    Yh = Y.cpu().to(torch.float64).numpy()
+    assert relmax(Yh, ref) <= BF16_TOL, (path, relmax(Yh, ref))
