@@ -465,3 +465,37 @@ def test_bf16_random_supported_extents(M, d, ffn, r, rd):
     ref = oracle.gated(synth.to_f64(gi.X), **{k: synth.to_f64(v) for k, v in gi.factors().items()})
     Yh = Y.cpu().to(torch.float64).numpy()
     assert relmax(Yh, ref) <= BF16_TOL, (path, relmax(Yh, ref))
+
+
+@pytest.mark.parametrize("M,d,ffn,r,rd", _random_shapes(12, 977))
+@pytest.mark.parametrize("flags", [B.FLAG_FORCE_TILED, B.FLAG_FORCE_TILED | B.FLAG_TILED_FUSED])
+def test_bf16_random_extents_forced_tiled_variants(M, d, ffn, r, rd, flags):
+    """The same lattice with the tiled path forced (also for tiny M) in both of its variants."""
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=61)
+    Y, ref, path = run_gated(gi, flags=flags)
+    assert path in (2, 5) and (path == 2 or not flags & B.FLAG_TILED_FUSED)
+    assert relmax(Y, ref) <= BF16_TOL, (path, relmax(Y, ref))
+
+
+def _random_linear_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        d, nn = 128 * int(rng.integers(1, 17)), 128 * int(rng.integers(1, 13))
+        r = 128 * int(rng.integers(1, min(d, nn) // 128 + 1))
+        out.append((int(rng.integers(1, 600)), d, nn, r))
+    return out
+
+
+@pytest.mark.parametrize("M,d,n,r", _random_linear_shapes(10, 31337))
+def test_bf16_linear_random_supported_extents(M, d, n, r):
+    li = synth.make_linear_gaussian(M, d, n, r, stream=62)
+    dv = dev()
+    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
+    O = mlp(li.X.to(dv))
+    torch.cuda.synchronize()
+    assert mlp.last_path == 6
+    Oh = O.cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
