@@ -499,3 +499,37 @@ def test_bf16_linear_random_supported_extents(M, d, n, r):
     mlp.close()
     ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
     assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
+
+
+@pytest.mark.parametrize("M", [8, 100, 300])
+def test_forward_can_be_captured_in_a_graph_and_replayed(M):
+    """svdmlp_forward only enqueues kernels (no memset, no allocation, no synchronisation), so a caller may capture
+    it; every replay, interleaved with eager work and synchronisations, must reproduce the eager result bit for bit."""
+    gi = synth.make_gated(M, 512, 1024, 192, 256, stream=63)
+    dv = dev()
+    f = {k: v.to(dv) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=M, **f)
+    X = gi.X.to(dv)
+    Y = torch.empty_like(X)
+    eager = mlp(X).clone()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        mlp(X, Y)
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        mlp(X, Y)
+    for rep in range(4):
+        Y.fill_(3.0)
+        X2 = (X * 0.5).contiguous()          # eager work between replays
+        other = mlp(X2)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, eager), rep
+        assert not torch.equal(other, eager)
+    del g
+    mlp.close()
