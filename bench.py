@@ -105,11 +105,11 @@ def bench_xuv(dev, M, steps, warmup, dense=True, shape=(8192, 4096, 16384)):
             torch.matmul(X, U, out=T)
             torch.matmul(T, V, out=O)
 
-        ums, _ = time_steps(two_gemms, max(5, steps // 3), 3)
+        ums, _ = time_steps(two_gemms, max(5, steps // 3), max(3, warmup // 2))
         out["unfused"] = dict(ms_per_step=ums, TFLOPs=2 * M * r * (d + n) / ums / 1e9,
                               provider="two torch.matmul calls, T through HBM (third-party GEMM)")
         W = torch.randn((d, n), dtype=torch.bfloat16, device=dev) * (d ** -0.5)
-        dms, _ = time_steps(lambda: torch.matmul(X, W, out=O), max(5, steps // 3), 3)
+        dms, _ = time_steps(lambda: torch.matmul(X, W, out=O), max(5, steps // 3), max(3, warmup // 2))
         out["dense"] = dict(ms_per_step=dms, TFLOPs=2 * M * d * n / dms / 1e9, flops=2 * M * d * n,
                             provider="torch.matmul (third-party GEMM)")
         del W, T
@@ -148,9 +148,11 @@ def bench_decode_rotating(dev, M, steps, warmup, nsets=12, flags=0):
         n[0] += 1
 
     ms, _ = time_steps(step, steps, warmup)
-    # single set, warm in the memory-side cache, and its per-kernel split
-    B.svdmlp_profile_begin(ctxs[0].ctx, steps)
+    # single set, warm in the memory-side cache; then once more for its per-kernel split (the events cost a few
+    # microseconds per launch, so that pass is not the one timed)
     ms_warm, _ = time_steps(lambda: ctxs[0](X, Y), steps, warmup)
+    B.svdmlp_profile_begin(ctxs[0].ctx, steps)
+    time_steps(lambda: ctxs[0](X, Y), steps, 0)
     kernels, _ = B.svdmlp_profile_end(ctxs[0].ctx)
     for c in ctxs:
         c.close()
@@ -216,8 +218,8 @@ def cpu_baseline(gi, target_seconds=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="prefill", choices=["prefill", "wide", "mlp_small", "decode", "xuv"])
     ap.add_argument("--r", type=int, default=None)
     ap.add_argument("--M", type=int, default=None)
@@ -248,7 +250,7 @@ def main():
         if args.sweep:
             rows = []
             for Ms in (1024, 2048, 4096, 8192, 16384, 32768):
-                x = bench_xuv(dev, Ms, max(5, args.steps // 3), 3, dense=not args.no_dense, shape=shape)
+                x = bench_xuv(dev, Ms, max(5, args.steps // 3), max(3, args.warmup // 2), dense=not args.no_dense, shape=shape)
                 row = {"M": Ms, "ms": x["ms"], "TFLOPs": x["flops"] / x["ms"] / 1e9, "kernels_ms": x["kernels"]}
                 if "dense" in x:
                     row.update(dense_ms=x["dense"]["ms_per_step"], unfused_ms=x["unfused"]["ms_per_step"],
@@ -258,7 +260,7 @@ def main():
                 torch.cuda.empty_cache()
             avg = lambda key: sum(r_[key] for r_ in rows) / len(rows)
             out = {"metric": METRIC, "value": avg("TFLOPs"), "unit": "TFLOP/s", "n_gpus": 1, "steps": max(5, args.steps // 3),
-                   "warmup": 3, "ms_per_step": avg("ms"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                   "warmup": max(3, args.warmup // 2), "ms_per_step": avg("ms"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
                    "dtype": "bf16", "data": "synthetic",
                    "config": {"workload": f"xuv sweep: (X U) V, X[M,{shape[0]}] U[{shape[0]},{shape[1]}] V[{shape[1]},{shape[2]}], "
                                           "M = 1K .. 32K; value = mean over M"},
@@ -363,9 +365,9 @@ def main():
     elif not args.no_decode:
         out["decode"] = bench_decode_rotating(dev, 16, max(args.steps, 48), args.warmup, flags=dflags)
     if not args.no_dense and args.workload != "decode":
-        out["dense_baseline"] = bench_dense(dev, M, d, ffn, max(5, args.steps // 3), 3)
+        out["dense_baseline"] = bench_dense(dev, M, d, ffn, max(5, args.steps // 3), max(3, args.warmup // 2))
         out["dense_baseline"]["speedup_of_factored"] = out["dense_baseline"]["ms_per_step"] / ms
-        out["unfused_baseline"] = bench_unfused(gi, dev, max(5, args.steps // 3), 3)
+        out["unfused_baseline"] = bench_unfused(gi, dev, max(5, args.steps // 3), max(3, args.warmup // 2))
         out["unfused_baseline"]["speedup_of_this_library"] = out["unfused_baseline"]["ms_per_step"] / ms
     out["paper_context"] = {"kernel_speedup_vs_nki": 1.35, "e2e_speedup": 1.21, "hardware": "AWS Trainium trn1",
                             "note": "paper figures for its own kernels; not the target"}
