@@ -146,6 +146,9 @@ def test_describe_names_the_plan_of_every_baseline_config():
     assert "k_down1[tile=256x256 tiles=32 ranges=8] k_reduce k_out[tile=256x256 tiles=256]" in s
     # decode shape: one row tile, both split phases fill the chip
     s = B.svdmlp_describe(pre, 16)
+    assert s.startswith("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=64 ranges=4] k_stream_d2[tiles=448]")
+    assert "k_stream_d4[tile=16 tiles=32 ranges=8] k_stream_d5[tiles=128]" in s
+    s = B.svdmlp_describe(pre, 32)
     assert s.startswith("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tiles=32 ranges=8] k_stream_d2[tiles=448]")
     assert "k_stream_d4[tiles=16 ranges=16] k_stream_d5[tiles=128]" in s
     assert "row_tiles=2" in B.svdmlp_describe(pre, 64) and "row_tiles=4" in B.svdmlp_describe(pre, 128)
