@@ -226,7 +226,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// D1 and D4 for M <= 16: the same products on 16 x 16 x 32 MFMAs, one 16-column output tile per workgroup group.
+// D1 and D4 for M <= 32: the same products on 16 x 16 x 32 MFMAs, one 16-column output tile per workgroup group.
 // These two phases split their contraction over workgroups, and what the split costs (the partial tile written
 // through, and above all the read-back of all S partial tiles by one workgroup, whose CU keeps only about 8 KiB of
 // requests in flight) goes with the tile size: a 16 x 16 fp32 tile is 1 KiB instead of 4 KiB, and twice as many
@@ -239,10 +239,11 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int PH>
+template <int PH, int MT>   // MT = 16-row tiles of the batch (M <= 16 MT)
 __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   static_assert(PH == PH_D1 || PH == PH_D4, "only the phases that split their contraction over workgroups");
-  __shared__ f32x4 red[SW][64];
+  static_assert(MT == 1 || MT == 2, "one 32-row activation tile");
+  __shared__ f32x4 red[SW][MT][64];
   __shared__ int s_last;
   const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
   const int tile = blockIdx.x / a.S, sp = blockIdx.x % a.S;   // 16-column tile, contraction range
@@ -261,32 +262,50 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   const size_t wl = (size_t)(16 * hn + i + 32 * (g % 2)) * 16, al = (size_t)(i + 32 * (g % 2)) * 16;
   const char* wbase = a.W0 + (a.kb_major ? (size_t)tile32 : (size_t)tile32 * a.KB) * FRAG_BYTES + wl;
   const size_t wstride = a.kb_major ? (size_t)tiles32 * FRAG_BYTES : (size_t)FRAG_BYTES;   // per 16-k frag
-  const uint16_t* xrow = (PH == PH_D1) ? static_cast<const uint16_t*>(a.act) + (size_t)(i < a.M ? i : a.M - 1) * a.ldx + 8 * g : nullptr;
+  const uint16_t* xrow[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int row = 16 * mt + i;
+    xrow[mt] = (PH == PH_D1) ? static_cast<const uint16_t*>(a.act) + (size_t)(row < a.M ? row : a.M - 1) * a.ldx + 8 * g : nullptr;
+  }
   const char* abase = static_cast<const char*>(a.act) + al;
 
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  f32x4 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
   for (int kb = k0; kb < k1; ++kb) {
     const bf16x8 wv = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(2 * kb + fsel) * wstride);
-    bf16x8 av;
-    if (PH == PH_D1) av = *reinterpret_cast<const bf16x8*>(xrow + 32 * kb);
-    else av = *reinterpret_cast<const bf16x8*>(abase + (size_t)(2 * kb + fsel) * FRAG_BYTES);
-    acc = mfma16(wv, av, acc);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      bf16x8 av;
+      if (PH == PH_D1) av = *reinterpret_cast<const bf16x8*>(xrow[mt] + 32 * kb);
+      else av = *reinterpret_cast<const bf16x8*>(abase + (size_t)(2 * kb + fsel) * FRAG_BYTES + mt * 256);   // rows 16 mt ..
+      acc[mt] = mfma16(wv, av, acc[mt]);
+    }
   }
-  // lane (m = l % 16, g): acc[e] = element (output column 4 g + e of the tile, row m)
-  red[w][lane] = acc;
+  // lane (m = l % 16, g): acc[mt][e] = element (output column 4 g + e of the tile, row 16 mt + m)
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) red[w][mt][lane] = acc[mt];
   __syncthreads();
-  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  f32x4 v[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) v[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   if (w == 0) {
 #pragma unroll
-    for (int ww = 0; ww < SW; ++ww) v += red[ww][lane];
+    for (int ww = 0; ww < SW; ++ww)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) v[mt] += red[ww][mt][lane];
   }
   if (a.S > 1) {
     // same exchange as in k_stream: write-through partial, ticket, the last workgroup adds in range order
-    float* mine = a.part + ((size_t)tile * a.S + sp) * 256;
+    float* mine = a.part + ((size_t)tile * a.S + sp) * (MT * 256);
     if (w == 0) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) __hip_atomic_store(&mine[e * 64 + lane], v[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          __hip_atomic_store(&mine[(mt * 4 + e) * 64 + lane], v[mt][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     asm volatile("" ::: "memory");
     wait_vmcnt<0>();
@@ -295,43 +314,50 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
       s_last = (__hip_atomic_fetch_add(&a.cnt[tile * TICKET_STRIDE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.S - 1);
     __syncthreads();
     if (!s_last || w != 0) return;
-    v = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int q0 = 0; q0 < a.S; q0 += 8) {   // up to eight partial tiles (8 KiB) in flight; additions in range order
-      f32x4 tmp[8];
 #pragma unroll
-      for (int qq = 0; qq < 8; ++qq) {
+    for (int mt = 0; mt < MT; ++mt) v[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr int QB = 8 / MT;   // partial tiles in flight (8 KiB); additions in range order
+    for (int q0 = 0; q0 < a.S; q0 += QB) {
+      f32x4 tmp[QB][MT];
+#pragma unroll
+      for (int qq = 0; qq < QB; ++qq) {
         const int q = q0 + qq < a.S ? q0 + qq : a.S - 1;
-        const float* src = a.part + ((size_t)tile * a.S + q) * 256 + lane;
+        const float* src = a.part + ((size_t)tile * a.S + q) * (MT * 256) + lane;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) tmp[qq][e] = __hip_atomic_load(src + e * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            tmp[qq][mt][e] = __hip_atomic_load(src + (mt * 4 + e) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
 #pragma unroll
-      for (int qq = 0; qq < 8; ++qq)
-        if (q0 + qq < a.S) v += tmp[qq];
+      for (int qq = 0; qq < QB; ++qq)
+        if (q0 + qq < a.S) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) v[mt] += tmp[qq][mt];
+        }
     }
     if (lane == 0) __hip_atomic_store(&a.cnt[tile * TICKET_STRIDE], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next forward
   } else if (w != 0) {
     return;
   }
   // The tile is contraction block `frag` of the next product's activation, in chain order: element s of frag lane
-  // (m, h) is column 8 (s / 4) + 4 h + s % 4, i.e. the four values of lane (m, g = h), then those of lane (m, g = 2 + h).
-  // Lanes 0..31 of this wave write frag lanes m + 32 h (m < 16); lanes 32..63 clear the rows 16..31 of the frag.
-  const int m = lane % 16, h = (lane / 16) % 2;
-  f32x4 lo, hi;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    lo[e] = __shfl(v[e], m + 16 * h, 64);
-    hi[e] = __shfl(v[e], m + 16 * (2 + h), 64);
-  }
+  // (row, h) is column 8 (s / 4) + 4 h + s % 4, i.e. the four values of lane (m, g = h), then those of lane (m, g = 2 + h).
+  // Lanes 0..31 of this wave write the frag lanes of rows 0..15, lanes 32..63 those of rows 16..31 (zeros if MT = 1).
+  const int m = lane % 16, h = (lane / 16) % 2, up = lane / 32;
   bf16x8 o;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    o[e] = (__bf16)lo[e];
-    o[4 + e] = (__bf16)hi[e];
-  }
-  if (lane >= 32) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = (__bf16)0.f;
+    float lo = __shfl(v[0][e], m + 16 * h, 64), hi = __shfl(v[0][e], m + 16 * (2 + h), 64);
+    if (MT == 2) {
+      const float lo1 = __shfl(v[MT - 1][e], m + 16 * h, 64), hi1 = __shfl(v[MT - 1][e], m + 16 * (2 + h), 64);
+      lo = up ? lo1 : lo;
+      hi = up ? hi1 : hi;
+    } else if (up) {
+      lo = 0.f;
+      hi = 0.f;
+    }
+    o[e] = (__bf16)lo;
+    o[4 + e] = (__bf16)hi;
   }
   size_t frag;
   if (PH == PH_D1) {
@@ -341,24 +367,24 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   } else {
     frag = (size_t)tile;
   }
-  const int dl = (lane < 32 ? m : 16 + m) + 32 * h;
+  const int dl = 16 * up + m + 32 * h;
   *reinterpret_cast<bf16x8*>(static_cast<char*>(a.out) + (frag * 64 + dl) * 16) = o;
 }
 
-// ranges for k_stream16: `tiles` 16-column tiles, KB2 contraction blocks of 32
-int stream_splits16(int tiles, int KB2) {
+// ranges for k_stream16: `tiles` 16-column tiles, KB2 contraction blocks of 32, mt 16-row tiles
+int stream_splits16(int tiles, int KB2, int mt) {
   int s = (256 + tiles - 1) / tiles;
   int smax = KB2 / SW;
   if (s > smax) s = smax;
   if (s > 64) s = 64;
   if (s < 1) s = 1;
   const size_t part_floats = ((size_t)8 << 20) / 4;   // the partial-tile buffer of the workspace
-  while (s > 1 && (size_t)tiles * s * 256 > part_floats) --s;
+  while (s > 1 && (size_t)tiles * s * mt * 256 > part_floats) --s;
   return s;
 }
 // whether the two split phases of a forward of M rows run on 16-column tiles
 bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd) {
-  return M <= 16 && d % 32 == 0 && ffn % 32 == 0 && 2 * r / 16 <= 2048 && rd / 16 <= 2048;
+  return M <= 32 && d % 32 == 0 && ffn % 32 == 0 && 2 * r / 16 <= 2048 && rd / 16 <= 2048;
 }
 
 int stream_splits(int tiles, int KB, int rt) {
@@ -402,8 +428,9 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   prof_mark(c, ps, 0, 0, st);
   if (t16) {
     a.tiles *= 2;
-    a.S = stream_splits16(a.tiles, a.KB / 2);
-    hipLaunchKernelGGL(k_stream16<PH_D1>, dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+    a.S = stream_splits16(a.tiles, a.KB / 2, M <= 16 ? 1 : 2);
+    if (M <= 16) hipLaunchKernelGGL((k_stream16<PH_D1, 1>), dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+    else hipLaunchKernelGGL((k_stream16<PH_D1, 2>), dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
   } else {
     launch_stream<PH_D1>(rt, a, st);
   }
@@ -424,8 +451,9 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   prof_mark(c, ps, 2, 0, st);
   if (t16) {
     a.tiles *= 2;
-    a.S = stream_splits16(a.tiles, a.KB / 2);
-    hipLaunchKernelGGL(k_stream16<PH_D4>, dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+    a.S = stream_splits16(a.tiles, a.KB / 2, M <= 16 ? 1 : 2);
+    if (M <= 16) hipLaunchKernelGGL((k_stream16<PH_D4, 1>), dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+    else hipLaunchKernelGGL((k_stream16<PH_D4, 2>), dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
   } else {
     launch_stream<PH_D4>(rt, a, st);
   }
