@@ -203,9 +203,9 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
       const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;
       const int t1 = (int)(2 * p.r / 32), t2 = (int)(p.ffn / 32), t4 = (int)(p.rd / 32), t5 = (int)(p.d / 32);
       if (stream_uses_tile16(M, p.d, p.ffn, p.r, p.rd))   // the two split phases on 16-column tiles
-        put("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=%d ranges=%d] k_stream_d2[tiles=%d]"
-            " k_stream_d4[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d]", 2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), M <= 16 ? 1 : 2), t2,
-            2 * t4, stream_splits16(2 * t4, (int)(p.ffn / 32), M <= 16 ? 1 : 2), t5);
+        put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tile=16 tiles=%d ranges=%d] k_stream_d2[tiles=%d]"
+            " k_stream_d4[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d]", rt, 2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t2,
+            2 * t4, stream_splits16(2 * t4, (int)(p.ffn / 32), stream_tiles16(M)), t5);
       else
         put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tiles=%d ranges=%d] k_stream_d2[tiles=%d] k_stream_d4[tiles=%d ranges=%d]"
             " k_stream_d5[tiles=%d]", rt, t1, stream_splits(t1, (int)(p.d / 16), rt), t2, t4, stream_splits(t4, (int)(p.ffn / 16), rt), t5);

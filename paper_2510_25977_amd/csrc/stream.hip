@@ -226,7 +226,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// D1 and D4 for M <= 32: the same products on 16 x 16 x 32 MFMAs, one 16-column output tile per workgroup group.
+// D1 and D4: the same products on 16 x 16 x 32 MFMAs, one 16-column output tile per workgroup group.
 // These two phases split their contraction over workgroups, and what the split costs (the partial tile written
 // through, and above all the read-back of all S partial tiles by one workgroup, whose CU keeps only about 8 KiB of
 // requests in flight) goes with the tile size: a 16 x 16 fp32 tile is 1 KiB instead of 4 KiB, and twice as many
@@ -242,7 +242,7 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 template <int PH, int MT>   // MT = 16-row tiles of the batch (M <= 16 MT)
 __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   static_assert(PH == PH_D1 || PH == PH_D4, "only the phases that split their contraction over workgroups");
-  static_assert(MT == 1 || MT == 2, "one 32-row activation tile");
+  static_assert(MT == 1 || MT == 2 || MT == 4 || MT == 8, "up to four 32-row activation tiles");
   __shared__ f32x4 red[SW][MT][64];
   __shared__ int s_last;
   const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
@@ -280,7 +280,8 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
     for (int mt = 0; mt < MT; ++mt) {
       bf16x8 av;
       if (PH == PH_D1) av = *reinterpret_cast<const bf16x8*>(xrow[mt] + 32 * kb);
-      else av = *reinterpret_cast<const bf16x8*>(abase + (size_t)(2 * kb + fsel) * FRAG_BYTES + mt * 256);   // rows 16 mt ..
+      else  // row tile mt / 2, rows 16 (mt % 2) .. of it
+        av = *reinterpret_cast<const bf16x8*>(abase + ((size_t)(mt / 2) * a.act_rt + 2 * kb + fsel) * FRAG_BYTES + (mt % 2) * 256);
       acc[mt] = mfma16(wv, av, acc[mt]);
     }
   }
@@ -316,7 +317,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
     if (!s_last || w != 0) return;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) v[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int QB = 8 / MT;   // partial tiles in flight (8 KiB); additions in range order
+    constexpr int QB = MT >= 8 ? 1 : 8 / MT;   // partial tiles in flight (8 KiB); additions in range order
     for (int q0 = 0; q0 < a.S; q0 += QB) {
       f32x4 tmp[QB][MT];
 #pragma unroll
@@ -342,23 +343,9 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   }
   // The tile is contraction block `frag` of the next product's activation, in chain order: element s of frag lane
   // (row, h) is column 8 (s / 4) + 4 h + s % 4, i.e. the four values of lane (m, g = h), then those of lane (m, g = 2 + h).
-  // Lanes 0..31 of this wave write the frag lanes of rows 0..15, lanes 32..63 those of rows 16..31 (zeros if MT = 1).
+  // Per 32-row tile: lanes 0..31 of this wave write the frag lanes of its rows 0..15, lanes 32..63 those of its rows
+  // 16..31 (zeros if MT = 1).
   const int m = lane % 16, h = (lane / 16) % 2, up = lane / 32;
-  bf16x8 o;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    float lo = __shfl(v[0][e], m + 16 * h, 64), hi = __shfl(v[0][e], m + 16 * (2 + h), 64);
-    if (MT == 2) {
-      const float lo1 = __shfl(v[MT - 1][e], m + 16 * h, 64), hi1 = __shfl(v[MT - 1][e], m + 16 * (2 + h), 64);
-      lo = up ? lo1 : lo;
-      hi = up ? hi1 : hi;
-    } else if (up) {
-      lo = 0.f;
-      hi = 0.f;
-    }
-    o[e] = (__bf16)lo;
-    o[4 + e] = (__bf16)hi;
-  }
   size_t frag;
   if (PH == PH_D1) {
     const int p0 = 16 * tile;
@@ -368,7 +355,25 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
     frag = (size_t)tile;
   }
   const int dl = 16 * up + m + 32 * h;
-  *reinterpret_cast<bf16x8*>(static_cast<char*>(a.out) + (frag * 64 + dl) * 16) = o;
+#pragma unroll
+  for (int rt = 0; rt < (MT + 1) / 2; ++rt) {
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float lo = __shfl(v[2 * rt][e], m + 16 * h, 64), hi = __shfl(v[2 * rt][e], m + 16 * (2 + h), 64);
+      if (MT >= 2) {
+        const float lo1 = __shfl(v[MT >= 2 ? 2 * rt + 1 : 0][e], m + 16 * h, 64), hi1 = __shfl(v[MT >= 2 ? 2 * rt + 1 : 0][e], m + 16 * (2 + h), 64);
+        lo = up ? lo1 : lo;
+        hi = up ? hi1 : hi;
+      } else if (up) {
+        lo = 0.f;
+        hi = 0.f;
+      }
+      o[e] = (__bf16)lo;
+      o[4 + e] = (__bf16)hi;
+    }
+    *reinterpret_cast<bf16x8*>(static_cast<char*>(a.out) + (((size_t)rt * a.out_rt + frag) * 64 + dl) * 16) = o;
+  }
 }
 
 // ranges for k_stream16: `tiles` 16-column tiles, KB2 contraction blocks of 32, mt 16-row tiles
@@ -382,9 +387,12 @@ int stream_splits16(int tiles, int KB2, int mt) {
   while (s > 1 && (size_t)tiles * s * mt * 256 > part_floats) --s;
   return s;
 }
+// 16-row tiles k_stream16 pads a batch to
+int stream_tiles16(int64_t M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8; }
 // whether the two split phases of a forward of M rows run on 16-column tiles
 bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd) {
-  return M <= 32 && d % 32 == 0 && ffn % 32 == 0 && 2 * r / 16 <= 2048 && rd / 16 <= 2048;
+  // beyond 64 rows the activation frags, re-read for every 16-column weight tile, cost more than the smaller partials save
+  return M <= 64 && d % 32 == 0 && ffn % 32 == 0 && 2 * r / 16 <= 2048 && rd / 16 <= 2048;
 }
 
 int stream_splits(int tiles, int KB, int rt) {
@@ -406,6 +414,15 @@ static void launch_stream(int rt, const StreamArgs& a, hipStream_t st) {
   else hipLaunchKernelGGL((k_stream<PH, 4>), grid, block, 0, st, a);
 }
 
+template <int PH>
+static void launch_stream16(int mt, const StreamArgs& a, hipStream_t st) {
+  const dim3 grid(a.tiles * a.S), block(SW * 64);
+  if (mt == 1) hipLaunchKernelGGL((k_stream16<PH, 1>), grid, block, 0, st, a);
+  else if (mt == 2) hipLaunchKernelGGL((k_stream16<PH, 2>), grid, block, 0, st, a);
+  else if (mt == 4) hipLaunchKernelGGL((k_stream16<PH, 4>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((k_stream16<PH, 8>), grid, block, 0, st, a);
+}
+
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
@@ -414,6 +431,7 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   if (M > STREAM_MAX_M) return (int)hipErrorInvalidValue;
   const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;   // 32-row tiles the batch is padded to
   const bool t16 = stream_uses_tile16(M, p.d, p.ffn, p.r, p.rd);
+  const int mt16 = stream_tiles16(M);
   int e;
   static const char* const names[4] = {"k_stream_d1", "k_stream_d2", "k_stream_d4", "k_stream_d5"};
   const int ps = prof_open_forward(c, 4, names);
@@ -428,9 +446,8 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   prof_mark(c, ps, 0, 0, st);
   if (t16) {
     a.tiles *= 2;
-    a.S = stream_splits16(a.tiles, a.KB / 2, M <= 16 ? 1 : 2);
-    if (M <= 16) hipLaunchKernelGGL((k_stream16<PH_D1, 1>), dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
-    else hipLaunchKernelGGL((k_stream16<PH_D1, 2>), dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+    a.S = stream_splits16(a.tiles, a.KB / 2, mt16);
+    launch_stream16<PH_D1>(mt16, a, st);
   } else {
     launch_stream<PH_D1>(rt, a, st);
   }
@@ -451,9 +468,8 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   prof_mark(c, ps, 2, 0, st);
   if (t16) {
     a.tiles *= 2;
-    a.S = stream_splits16(a.tiles, a.KB / 2, M <= 16 ? 1 : 2);
-    if (M <= 16) hipLaunchKernelGGL((k_stream16<PH_D4, 1>), dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
-    else hipLaunchKernelGGL((k_stream16<PH_D4, 2>), dim3(a.tiles * a.S), dim3(SW * 64), 0, st, a);
+    a.S = stream_splits16(a.tiles, a.KB / 2, mt16);
+    launch_stream16<PH_D4>(mt16, a, st);
   } else {
     launch_stream<PH_D4>(rt, a, st);
   }

@@ -149,9 +149,7 @@ def test_describe_names_the_plan_of_every_baseline_config():
     assert s.startswith("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=64 ranges=4] k_stream_d2[tiles=448]")
     assert "k_stream_d4[tile=16 tiles=32 ranges=8] k_stream_d5[tiles=128]" in s
     assert B.svdmlp_describe(pre, 32) == s
-    s = B.svdmlp_describe(pre, 33)
-    assert s.startswith("path=3 bf16-streaming: row_tiles=2 k_stream_d1[tiles=32 ranges=8] k_stream_d2[tiles=448]")
-    assert "k_stream_d4[tiles=16 ranges=16] k_stream_d5[tiles=128]" in s
+    assert B.svdmlp_describe(pre, 33) == s.replace("row_tiles=1", "row_tiles=2")
     assert "row_tiles=2" in B.svdmlp_describe(pre, 64) and "row_tiles=4" in B.svdmlp_describe(pre, 128)
     assert B.svdmlp_describe(pre, 129).startswith("path=5")
     # config 2 (M = 128) streams; forced onto the tiled path it has one row tile
