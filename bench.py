@@ -1,14 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the fused SVD-factored gated MLP forward on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload prefill|wide|mlp_small|decode] [--r R] [--M M]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload prefill|wide|mlp_small|decode|xuv] [--r R] [--M M]
+                    [--fused] [--one-kernel-decode] [--sweep] [--shape d,r,n] [--no-cpu-baseline] [--no-dense] [--no-decode]
 
 A step is one pass of the whole hot path (svdmlp_forward: rank-r strips, gate/up second stage with
 the SiLU gate, down projection) over one batch of seeded synthetic input already resident in HBM.
 Prints ONE JSON line.  `value` is TFLOP/s of the prefill workload (algorithmic FLOPs 6 M r (d + ffn)
 divided by the step time); the same line also carries the decode-shape GB/s, a dense bf16 MLP on the
 same GPU (third-party GEMMs through torch), the roofline of the dominant kernel and the CPU oracle
-timed on the host cores.
+timed on the host cores.  Defaults: 50 warm-up and 200 timed steps (the clocks need a few tens of
+forwards to settle; short runs read about 15 % slower).
 """
 from __future__ import annotations
 
@@ -236,8 +238,8 @@ def main():
                          "command can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the forward shards over rows with no communication; "
-              "see DESIGN.md); --gpus N with N > 1 is not supported", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (rows of X are independent, so the forward shards over rows with no "
+              "communication and one GPU shows its share at the real shape); --gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
