@@ -1,4 +1,5 @@
-// bf16 MFMA-tiled (prefill) path of the factored gated MLP (paper Alg. 2 / Alg. 3), gfx950.
+// bf16 MFMA-tiled (prefill) path of the factored gated MLP (paper Alg. 2 / Alg. 3), gfx950: the kernels with
+// 128-row tiles and the host code that strings a forward together.
 //
 //   k_s1      T^T  = [Ug|Uu]^T X^T            rank-r strips of gate and up, written as chain-order frags
 //   k_fused   H^T  = SiLU(Vg^T Tg^T) .* (Vu^T Tu^T)   per ffn chunk, kept in registers, immediately
@@ -6,11 +7,13 @@
 //   k_reduce  Td   = sum of the partials, rounded to bf16 frags (fixed order: deterministic)
 //   k_s5      Y    = Td Vd
 //
-// All four are the same machine: operands arrive as 1 KiB frags (common.h) through a ring of 16 KiB
+// These four are the same machine: operands arrive as 1 KiB frags (common.h) through a ring of 16 KiB
 // LDS slots filled by asynchronous global->LDS copies, waves read frags back with ds_read_b128 and feed
 // v_mfma_f32_32x32x16_bf16.  The paper's "caching" of the rank-r strip (Sec. 4.2.1) becomes: the strip
-// T is produced once by k_s1 and re-read from L2 by the 128-row tile that owns it; the ffn-wide
-// activation H (which the paper writes to HBM in Alg. 3) never leaves the register file.
+// T is produced once by the first stage and re-read from L2 by the tiles that own its rows.  With k_fused the
+// ffn-wide activation H (which the paper writes to HBM in Alg. 3) never leaves the register file; the default
+// forward stages H through the workspace with the 256-row kernels of gemm.hip, which measure faster, and uses
+// k_fused and k_s5 only on request or for extents those kernels do not take (staged_tail / bf16_tiled_forward below).
 #include "common.h"
 
 namespace svdmlp {
