@@ -43,8 +43,8 @@ typedef struct svdmlp_ctx svdmlp_ctx; /* opaque; host memory only */
  *   F32 : debug path, fp32 storage and fp32 arithmetic everywhere, no matrix cores. */
 enum { SVDMLP_BF16 = 0, SVDMLP_F32 = 1 };
 
-/* GATED: Alg. 2 (bf16: d and ffn multiples of 128; r a multiple of 64, at least 128; r_down 128, 256, 512 or a
- * multiple of 512).  LINEAR: the single factored layer O = (X U) V of Sec. 4.2.1 (bf16: d, ffn, r multiples of 128).
+/* GATED: Alg. 2 (bf16: d and ffn multiples of 128; r a multiple of 64, at least 128; r_down 128, 256, 512, a
+ * multiple of 512, or any multiple of 256 when ffn is a multiple of 256 (the fused variant then is not available)).  LINEAR: the single factored layer O = (X U) V of Sec. 4.2.1 (bf16: d, ffn, r multiples of 128).
  * Other extents: SVDMLP_UNSUPPORTED from svdmlp_create (F32 takes any). */
 enum { SVDMLP_GATED = 0, SVDMLP_LINEAR = 1 };
 

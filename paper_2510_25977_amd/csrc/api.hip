@@ -84,7 +84,11 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   const int64_t d = de->d, ffn = de->ffn, r = de->r, rd = p->rd;
   if (d % 128 || ffn % 128 || r % 64 || r < 128) return SVDMLP_UNSUPPORTED;
   const int64_t nq = rd / 32;
-  if (rd % 64 || !(fused_rank_tiles(nq) || rd % 512 == 0)) return SVDMLP_UNSUPPORTED;
+  // the down rank must suit the staged variant (256-wide rank tiles) or the fused one (a workgroup owns 4, 8 or 16
+  // 32-wide rank tiles, or groups of 16)
+  const bool fused_ok = fused_rank_tiles(nq) || rd % 512 == 0;
+  if (rd % 64 || !(fused_ok || staged_supported(rd, ffn))) return SVDMLP_UNSUPPORTED;
+  if (!fused_ok && (de->flags & SVDMLP_FLAG_TILED_FUSED)) return SVDMLP_UNSUPPORTED;
 
   p->Mpad = (de->max_M + 255) / 256 * 256;
   size_t off = 0;

@@ -93,6 +93,8 @@ def test_workspace_bytes_formula(lib):
     (dict(r=64), B.SVDMLP_UNSUPPORTED),                        # ... and r >= 128
     (dict(r_down=192), B.SVDMLP_UNSUPPORTED),                  # r_down must be 128, 256, 512 or a multiple of 512
     (dict(r_down=64), B.SVDMLP_UNSUPPORTED),
+    (dict(d=1024, ffn=1024, r_down=768, flags=B.FLAG_SKIP_ARCH_CHECK | B.FLAG_TILED_FUSED), B.SVDMLP_UNSUPPORTED),  # staged only
+    (dict(d=1024, ffn=1152, r_down=768), B.SVDMLP_UNSUPPORTED),  # ... and the staged variant needs ffn % 256 == 0
     (dict(kind=B.SVDMLP_LINEAR, r=64), B.SVDMLP_UNSUPPORTED),  # bf16 LINEAR needs r % 128 == 0
     (dict(flags=B.FLAG_SKIP_ARCH_CHECK | B.FLAG_FORCE_TILED | B.FLAG_FORCE_STREAM), B.SVDMLP_INVALID_ARGUMENT),
 ])

@@ -537,3 +537,14 @@ def test_forward_can_be_captured_in_a_graph_and_replayed(M):
         assert not torch.equal(other, eager)
     del g
     mlp.close()
+
+
+@pytest.mark.parametrize("M,d,ffn,r,rd", [(300, 1024, 1024, 256, 768), (530, 1536, 1536, 384, 1280), (20, 1024, 1024, 256, 768),
+                                          (100, 1024, 1024, 256, 768)])
+def test_bf16_down_rank_of_three_or_five_256_tiles(M, d, ffn, r, rd):
+    """Down ranks that only the staged variant takes (a multiple of 256 that is neither 256, 512 nor a multiple of 512),
+    on the tiled and on the streaming path."""
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=64)
+    Y, ref, path = run_gated(gi)
+    assert path == (5 if M > 128 else 3)
+    assert relmax(Y, ref) <= BF16_TOL, (path, relmax(Y, ref))
