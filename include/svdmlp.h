@@ -43,9 +43,12 @@ typedef struct svdmlp_ctx svdmlp_ctx; /* opaque; host memory only */
  *   F32 : debug path, fp32 storage and fp32 arithmetic everywhere, no matrix cores. */
 enum { SVDMLP_BF16 = 0, SVDMLP_F32 = 1 };
 
-/* GATED: Alg. 2 (bf16: d and ffn multiples of 128; r a multiple of 64, at least 128; r_down 128, 256, 512, a
- * multiple of 512, or any multiple of 256 when ffn is a multiple of 256 (the fused variant then is not available)).  LINEAR: the single factored layer O = (X U) V of Sec. 4.2.1 (bf16: d, ffn, r multiples of 128).
- * Other extents: SVDMLP_UNSUPPORTED from svdmlp_create (F32 takes any). */
+/* GATED: Alg. 2.  LINEAR: the single factored layer O = (X U) V of Sec. 4.2.1.
+ * bf16 extents: d and ffn multiples of 128 (else SVDMLP_UNSUPPORTED from svdmlp_create; F32 takes any).  Ranks are free
+ * (1 <= r, r_down <= min(d, ffn)): the library's re-tiled copies of the factors carry the rank rounded up to what its
+ * tiles take (r: a multiple of 64, at least 128, LINEAR: a multiple of 128; r_down: a multiple of 256, or 128 / 256 /
+ * 512 / a multiple of 512 where the fused tiled variant runs) with zero columns and rows, which changes no result but
+ * costs the time and the workspace of the rounded-up rank: block-aligned ranks (the rank rule of Sec. 4.1) lose nothing. */
 enum { SVDMLP_GATED = 0, SVDMLP_LINEAR = 1 };
 
 /* Status codes (0 = success, negative = failure). */

@@ -42,6 +42,8 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
 
   p->max_M = de->max_M; p->d = de->d; p->ffn = de->ffn; p->r = de->r;
   p->rd = gated ? de->r_down : 0;
+  p->r_in = p->r;
+  p->rd_in = p->rd;
   p->kind = de->kind; p->dtype = de->dtype; p->flags = de->flags;
 
   if (de->dtype == SVDMLP_F32) {
@@ -59,8 +61,10 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   // ---- bf16 ----
   if (!gated) {
     // single factored layer O = (X U) V: the first and the last kernel of the tiled path back to back
-    const int64_t d = de->d, n = de->ffn, r = de->r;
-    if (d % 128 || n % 128 || r % 128) return SVDMLP_UNSUPPORTED;
+    const int64_t d = de->d, n = de->ffn;
+    if (d % 128 || n % 128) return SVDMLP_UNSUPPORTED;
+    const int64_t r = (de->r + 127) / 128 * 128;   // zero-padded rank
+    p->r = r;
     p->Mpad = (de->max_M + 255) / 256 * 256;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -81,14 +85,18 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
     p->total_bytes = off;
     return SVDMLP_OK;
   }
-  const int64_t d = de->d, ffn = de->ffn, r = de->r, rd = p->rd;
-  if (d % 128 || ffn % 128 || r % 64 || r < 128) return SVDMLP_UNSUPPORTED;
-  const int64_t nq = rd / 32;
-  // the down rank must suit the staged variant (256-wide rank tiles) or the fused one (a workgroup owns 4, 8 or 16
-  // 32-wide rank tiles, or groups of 16)
-  const bool fused_ok = fused_rank_tiles(nq) || rd % 512 == 0;
-  if (rd % 64 || !(fused_ok || staged_supported(rd, ffn))) return SVDMLP_UNSUPPORTED;
-  if (!fused_ok && (de->flags & SVDMLP_FLAG_TILED_FUSED)) return SVDMLP_UNSUPPORTED;
+  const int64_t d = de->d, ffn = de->ffn;
+  if (d % 128 || ffn % 128) return SVDMLP_UNSUPPORTED;
+  // Ranks are rounded up to what the tiles take (zero columns of U, zero rows of V change nothing): r to a multiple
+  // of 64, at least 128; the down rank to a multiple of 256 for the staged variant (256-wide rank tiles), else to
+  // what the fused one takes (a workgroup owns 4, 8 or 16 32-wide rank tiles, or groups of 16).
+  const int64_t r = de->r <= 128 ? 128 : (de->r + 63) / 64 * 64;
+  const bool want_fused = (de->flags & SVDMLP_FLAG_TILED_FUSED) || !staged_supported(256, ffn);
+  int64_t rd = p->rd;
+  if (want_fused) rd = rd <= 128 ? 128 : rd <= 256 ? 256 : (rd + 511) / 512 * 512;
+  else rd = (rd + 255) / 256 * 256;
+  p->r = r;
+  p->rd = rd;
 
   p->Mpad = (de->max_M + 255) / 256 * 256;
   size_t off = 0;

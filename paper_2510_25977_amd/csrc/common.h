@@ -131,8 +131,10 @@ __device__ __forceinline__ int xcd_contiguous_id(int hw, int n) {
 
 // ---- host-side plan -------------------------------------------------------------------------
 struct Plan {
-  // extents
+  // extents.  bf16: r and rd are the ranks the kernels run with: the given ranks (r_in, rd_in) rounded up to what the
+  // tiles take, the added factor columns / rows being zeros in the re-tiled copies
   int64_t max_M, d, ffn, r, rd;
+  int64_t r_in, rd_in;
   int kind, dtype;
   uint32_t flags;
   // bf16: byte offsets into the workspace (all 256-byte aligned)

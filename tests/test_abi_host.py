@@ -89,13 +89,6 @@ def test_workspace_bytes_formula(lib):
     (dict(workspace=0x100010), B.SVDMLP_INVALID_ARGUMENT),     # workspace not 256-byte aligned
     (dict(workspace_bytes=1024), B.SVDMLP_WORKSPACE_TOO_SMALL),
     (dict(d=200), B.SVDMLP_UNSUPPORTED),                       # bf16 needs d % 128 == 0
-    (dict(r=48), B.SVDMLP_UNSUPPORTED),                        # bf16 needs r % 64 == 0
-    (dict(r=64), B.SVDMLP_UNSUPPORTED),                        # ... and r >= 128
-    (dict(r_down=192), B.SVDMLP_UNSUPPORTED),                  # r_down must be 128, 256, 512 or a multiple of 512
-    (dict(r_down=64), B.SVDMLP_UNSUPPORTED),
-    (dict(d=1024, ffn=1024, r_down=768, flags=B.FLAG_SKIP_ARCH_CHECK | B.FLAG_TILED_FUSED), B.SVDMLP_UNSUPPORTED),  # staged only
-    (dict(d=1024, ffn=1152, r_down=768), B.SVDMLP_UNSUPPORTED),  # ... and the staged variant needs ffn % 256 == 0
-    (dict(kind=B.SVDMLP_LINEAR, r=64), B.SVDMLP_UNSUPPORTED),  # bf16 LINEAR needs r % 128 == 0
     (dict(flags=B.FLAG_SKIP_ARCH_CHECK | B.FLAG_FORCE_TILED | B.FLAG_FORCE_STREAM), B.SVDMLP_INVALID_ARGUMENT),
 ])
 def test_create_rejects_bad_descriptions(lib, kw, status):
@@ -179,5 +172,21 @@ def test_describe_names_the_plan_of_every_baseline_config():
         B.svdmlp_describe(pre, 5000)
     assert e.value.status == B.SVDMLP_INVALID_ARGUMENT
     with pytest.raises(B.SvdMlpError) as e:
-        B.svdmlp_describe(desc(r_down=192), 8)
+        B.svdmlp_describe(desc(ffn=200), 8)
     assert e.value.status == B.SVDMLP_UNSUPPORTED
+
+
+def test_ranks_are_rounded_up_to_the_tiles():
+    """Any rank up to min(d, ffn) is accepted on the bf16 path: the plan runs with the rank rounded up (zero columns /
+    rows in the re-tiled factors), which shows in the workspace size and in the plan description."""
+    base = B.svdmlp_workspace_bytes(desc(max_M=300, d=1024, ffn=1024, r=256, r_down=768))
+    for r, rd in ((200, 768), (256, 600), (193, 513)):
+        assert B.svdmlp_workspace_bytes(desc(max_M=300, d=1024, ffn=1024, r=r, r_down=rd)) == base, (r, rd)
+    assert B.svdmlp_workspace_bytes(desc(max_M=300, d=1024, ffn=1024, r=257, r_down=768)) > base
+    # staged variant: down rank to a multiple of 256; fused variant (on request, or ffn not a multiple of 256): to 128, 256,
+    # 512 or a multiple of 512
+    assert "k_down1[tile=256x256 tiles=6 ranges" in B.svdmlp_describe(desc(max_M=300, d=1024, ffn=1024, r=200, r_down=600), 300)
+    s = B.svdmlp_describe(desc(max_M=300, d=1024, ffn=1152, r=200, r_down=600), 300)
+    assert s.startswith("path=2 bf16-tiled-fused:")
+    lin = desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=640, r=100, r_down=0)
+    assert B.svdmlp_workspace_bytes(lin) == B.svdmlp_workspace_bytes(desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=640, r=128, r_down=0))

@@ -548,3 +548,29 @@ def test_bf16_down_rank_of_three_or_five_256_tiles(M, d, ffn, r, rd):
     Y, ref, path = run_gated(gi)
     assert path == (5 if M > 128 else 3)
     assert relmax(Y, ref) <= BF16_TOL, (path, relmax(Y, ref))
+
+
+@pytest.mark.parametrize("M,d,ffn,r,rd", [
+    (300, 512, 1024, 200, 300), (40, 512, 640, 17, 33), (700, 1024, 1024, 129, 513), (129, 384, 1152, 100, 384),
+    (16, 512, 1408, 250, 100), (100, 256, 512, 1, 1), (520, 640, 768, 320, 640),
+])
+@pytest.mark.parametrize("flags", [0, B.FLAG_FORCE_TILED | B.FLAG_TILED_FUSED])
+def test_bf16_arbitrary_ranks(M, d, ffn, r, rd, flags):
+    """Ranks that are not multiples of anything: the library rounds them up to its tiles with zero columns / rows in its
+    re-tiled copies of the factors, which must not change the result."""
+    gi = synth.make_gated(M, d, ffn, r, rd, stream=65)
+    Y, ref, path = run_gated(gi, flags=flags)
+    assert relmax(Y, ref) <= BF16_TOL, (path, relmax(Y, ref))
+
+
+@pytest.mark.parametrize("M,d,n,r", [(300, 512, 640, 100), (70, 256, 512, 7), (513, 1024, 768, 300)])
+def test_bf16_linear_arbitrary_rank(M, d, n, r):
+    li = synth.make_linear_gaussian(M, d, n, r, stream=66)
+    dv = dev()
+    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
+    O = mlp(li.X.to(dv))
+    torch.cuda.synchronize()
+    Oh = O.cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
