@@ -44,7 +44,8 @@ typedef struct svdmlp_ctx svdmlp_ctx; /* opaque; host memory only */
 enum { SVDMLP_BF16 = 0, SVDMLP_F32 = 1 };
 
 /* GATED: Alg. 2.  LINEAR: the single factored layer O = (X U) V of Sec. 4.2.1.
- * bf16 extents: d and ffn multiples of 128 (else SVDMLP_UNSUPPORTED from svdmlp_create; F32 takes any).  Ranks are free
+ * bf16 extents: d a multiple of 128, for LINEAR ffn as well (else SVDMLP_UNSUPPORTED from svdmlp_create; F32 takes any);
+ * for GATED ffn is free (it is internal: the re-tiled factors carry it rounded up to a multiple of 256).  Ranks are free
  * (1 <= r, r_down <= min(d, ffn)): the library's re-tiled copies of the factors carry the rank rounded up to what its
  * tiles take (r: a multiple of 64, at least 128, LINEAR: a multiple of 128; r_down: a multiple of 256, or 128 / 256 /
  * 512 / a multiple of 512 where the fused tiled variant runs) with zero columns and rows, which changes no result but

@@ -44,6 +44,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   p->rd = gated ? de->r_down : 0;
   p->r_in = p->r;
   p->rd_in = p->rd;
+  p->ffn_in = p->ffn;
   p->kind = de->kind; p->dtype = de->dtype; p->flags = de->flags;
 
   if (de->dtype == SVDMLP_F32) {
@@ -85,13 +86,17 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
     p->total_bytes = off;
     return SVDMLP_OK;
   }
-  const int64_t d = de->d, ffn = de->ffn;
-  if (d % 128 || ffn % 128) return SVDMLP_UNSUPPORTED;
+  const int64_t d = de->d;
+  if (d % 128) return SVDMLP_UNSUPPORTED;
+  // The ffn-wide activation is internal, so ffn is rounded up to the 256-wide tiles of the staged variant: zero
+  // columns of Vg and Vu give H = SiLU(0) * 0 = 0 there, and the matching rows of Ud are zeros as well.
+  const int64_t ffn = (de->ffn + 255) / 256 * 256;
+  p->ffn = ffn;
   // Ranks are rounded up to what the tiles take (zero columns of U, zero rows of V change nothing): r to a multiple
   // of 64, at least 128; the down rank to a multiple of 256 for the staged variant (256-wide rank tiles), else to
   // what the fused one takes (a workgroup owns 4, 8 or 16 32-wide rank tiles, or groups of 16).
   const int64_t r = de->r <= 128 ? 128 : (de->r + 63) / 64 * 64;
-  const bool want_fused = (de->flags & SVDMLP_FLAG_TILED_FUSED) || !staged_supported(256, ffn);
+  const bool want_fused = (de->flags & SVDMLP_FLAG_TILED_FUSED) != 0;
   int64_t rd = p->rd;
   if (want_fused) rd = rd <= 128 ? 128 : rd <= 256 ? 256 : (rd + 511) / 512 * 512;
   else rd = (rd + 255) / 256 * 256;

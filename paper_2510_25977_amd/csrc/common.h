@@ -135,6 +135,7 @@ struct Plan {
   // tiles take, the added factor columns / rows being zeros in the re-tiled copies
   int64_t max_M, d, ffn, r, rd;
   int64_t r_in, rd_in;
+  int64_t ffn_in;   // gated bf16: ffn likewise runs rounded up to a multiple of 256 (zero columns of Vg, Vu, zero rows of Ud)
   int kind, dtype;
   uint32_t flags;
   // bf16: byte offsets into the workspace (all 256-byte aligned)

@@ -63,12 +63,12 @@ int bf16_repack_all(const Ctx* c, hipStream_t st) {
   if ((e = repack(de.Uu, p.d, p.r_in, p.d, p.r, ws + p.off_wU, ORDER_NATURAL, TILE_MAJOR, (int)(p.r / 32), pt, st))) return e;
   // Vg^T, Vu^T: rows n in [0, ffn), contraction over r, meet T produced by an MFMA -> chain order
   const int nt = (int)(p.ffn / 32);
-  if ((e = repack(de.Vg, p.r_in, p.ffn, p.r, p.ffn, ws + p.off_wVg, ORDER_CHAIN, TILE_MAJOR, 0, nt, st))) return e;
-  if ((e = repack(de.Vu, p.r_in, p.ffn, p.r, p.ffn, ws + p.off_wVu, ORDER_CHAIN, TILE_MAJOR, 0, nt, st))) return e;
+  if ((e = repack(de.Vg, p.r_in, p.ffn_in, p.r, p.ffn, ws + p.off_wVg, ORDER_CHAIN, TILE_MAJOR, 0, nt, st))) return e;
+  if ((e = repack(de.Vu, p.r_in, p.ffn_in, p.r, p.ffn, ws + p.off_wVu, ORDER_CHAIN, TILE_MAJOR, 0, nt, st))) return e;
   // Ud^T: rows q in [0, rd), contraction over ffn, meets H from registers -> chain order; contraction-block major
   // so that the frags one ffn chunk needs are contiguous
   const int qt = (int)(p.rd / 32);
-  if ((e = repack(de.Ud, p.ffn, p.rd_in, p.ffn, p.rd, ws + p.off_wUd, ORDER_CHAIN, KB_MAJOR, 0, qt, st))) return e;
+  if ((e = repack(de.Ud, p.ffn_in, p.rd_in, p.ffn, p.rd, ws + p.off_wUd, ORDER_CHAIN, KB_MAJOR, 0, qt, st))) return e;
   // Vd^T: rows c in [0, d), contraction over rd, meets Td produced by an MFMA -> chain order
   if ((e = repack(de.Vd, p.rd_in, p.d, p.rd, p.d, ws + p.off_wVd, ORDER_CHAIN, TILE_MAJOR, 0, (int)(p.d / 32), st))) return e;
   // tickets of the streaming paths start at zero and are left at zero by every forward; the completion counters

@@ -159,8 +159,8 @@ def test_describe_names_the_plan_of_every_baseline_config():
     # fused variant on request, and for extents the staged one does not take
     pre.flags |= B.FLAG_TILED_FUSED
     assert B.svdmlp_describe(pre, 4096).startswith("path=2 bf16-tiled-fused:")
-    odd = desc(max_M=512, d=256, ffn=384, r=128, r_down=128)
-    assert B.svdmlp_describe(odd, 512).startswith("path=2")
+    odd = desc(max_M=512, d=256, ffn=384, r=128, r_down=128)   # ffn and r_down run rounded up to 512 and 256
+    assert B.svdmlp_describe(odd, 512).startswith("path=5")
     # single factored layer at the paper's kernel-evaluation shape: the first stage cuts d when tiles are few
     lin = desc(kind=B.SVDMLP_LINEAR, max_M=32768, d=8192, ffn=16384, r=4096, r_down=0)
     assert "k_in[tile=256x256 tiles=64 ranges=4] k_reduce k_out" in B.svdmlp_describe(lin, 1024)
@@ -172,7 +172,7 @@ def test_describe_names_the_plan_of_every_baseline_config():
         B.svdmlp_describe(pre, 5000)
     assert e.value.status == B.SVDMLP_INVALID_ARGUMENT
     with pytest.raises(B.SvdMlpError) as e:
-        B.svdmlp_describe(desc(ffn=200), 8)
+        B.svdmlp_describe(desc(d=200), 8)
     assert e.value.status == B.SVDMLP_UNSUPPORTED
 
 
@@ -186,7 +186,11 @@ def test_ranks_are_rounded_up_to_the_tiles():
     # staged variant: down rank to a multiple of 256; fused variant (on request, or ffn not a multiple of 256): to 128, 256,
     # 512 or a multiple of 512
     assert "k_down1[tile=256x256 tiles=6 ranges" in B.svdmlp_describe(desc(max_M=300, d=1024, ffn=1024, r=200, r_down=600), 300)
-    s = B.svdmlp_describe(desc(max_M=300, d=1024, ffn=1152, r=200, r_down=600), 300)
-    assert s.startswith("path=2 bf16-tiled-fused:")
+    # ffn is internal to the gated forward: rounded up to a multiple of 256 as well (1100 -> 1280 = 5 column tiles)
+    s = B.svdmlp_describe(desc(max_M=300, d=1024, ffn=1100, r=200, r_down=600), 300)
+    assert s.startswith("path=5 bf16-tiled-staged:") and "k_gate_up[tile=256x256 tiles=10 " in s
+    fused = desc(max_M=300, d=1024, ffn=1100, r=200, r_down=600)
+    fused.flags |= B.FLAG_TILED_FUSED
+    assert B.svdmlp_describe(fused, 300).startswith("path=2 bf16-tiled-fused:")
     lin = desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=640, r=100, r_down=0)
     assert B.svdmlp_workspace_bytes(lin) == B.svdmlp_workspace_bytes(desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=640, r=128, r_down=0))

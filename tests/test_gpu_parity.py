@@ -553,11 +553,12 @@ def test_bf16_down_rank_of_three_or_five_256_tiles(M, d, ffn, r, rd):
 @pytest.mark.parametrize("M,d,ffn,r,rd", [
     (300, 512, 1024, 200, 300), (40, 512, 640, 17, 33), (700, 1024, 1024, 129, 513), (129, 384, 1152, 100, 384),
     (16, 512, 1408, 250, 100), (100, 256, 512, 1, 1), (520, 640, 768, 320, 640),
+    (300, 512, 1000, 200, 300), (50, 256, 200, 100, 64), (200, 384, 1153, 130, 257),   # ffn is free as well
 ])
 @pytest.mark.parametrize("flags", [0, B.FLAG_FORCE_TILED | B.FLAG_TILED_FUSED])
 def test_bf16_arbitrary_ranks(M, d, ffn, r, rd, flags):
-    """Ranks that are not multiples of anything: the library rounds them up to its tiles with zero columns / rows in its
-    re-tiled copies of the factors, which must not change the result."""
+    """Ranks (and ffn) that are not multiples of anything: the library rounds them up to its tiles with zero columns /
+    rows in its re-tiled copies of the factors, which must not change the result."""
     gi = synth.make_gated(M, d, ffn, r, rd, stream=65)
     Y, ref, path = run_gated(gi, flags=flags)
     assert relmax(Y, ref) <= BF16_TOL, (path, relmax(Y, ref))
