@@ -40,6 +40,9 @@ MEASURED_TRAFFIC = {
     ("k_gate_up", 4096, 4096, 14336, 512): {"read_MB": 184.9, "written_MB": 117.4, "algorithmic_read_MB": 37.7,
                                             "algorithmic_written_MB": 117.4,
                                             "source": "profiles/prefill_r512_pmc_traffic_mfma.txt"},
+    ("k_stream_d2", 16, 4096, 14336, 512): {"read_MB": 29.95, "written_MB": 0.92, "algorithmic_read_MB": 29.38,
+                                            "algorithmic_written_MB": 0.46,
+                                            "source": "profiles/decode_m16_kernel_trace_pmc.txt"},
 }
 
 
@@ -360,7 +363,8 @@ def main():
         k_bytes = kbytes[kname]
         out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": k_bytes / k_ms / 1e6 if k_ms else None,
                            "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                           "frac": k_bytes / k_ms / 1e6 / PEAK_HBM_GBS if k_ms else None, "traffic": None,
+                           "frac": k_bytes / k_ms / 1e6 / PEAK_HBM_GBS if k_ms else None,
+                           "traffic": MEASURED_TRAFFIC.get((kname, M, d, ffn, r)),
                            "whole_forward_GBps": nbytes / ms / 1e6,
                            "note": "per-kernel time from HIP events" + (" of the warm single-set run" if args.workload == "decode" else "")}
     else:
