@@ -194,3 +194,34 @@ def test_ranks_are_rounded_up_to_the_tiles():
     assert B.svdmlp_describe(fused, 300).startswith("path=2 bf16-tiled-fused:")
     lin = desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=640, r=100, r_down=0)
     assert B.svdmlp_workspace_bytes(lin) == B.svdmlp_workspace_bytes(desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=640, r=128, r_down=0))
+
+
+def test_header_is_plain_c_and_a_c_program_links(lib, tmp_path):
+    """include/svdmlp.h compiles as C99 with gcc, and a C caller can use the host-only entry points."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "svdmlp.h"
+int main(void) {
+  svdmlp_desc de;
+  memset(&de, 0, sizeof de);
+  de.kind = SVDMLP_GATED; de.dtype = SVDMLP_BF16;
+  de.max_M = 4096; de.d = 4096; de.ffn = 14336; de.r = 512; de.r_down = 512;
+  de.flags = SVDMLP_FLAG_SKIP_ARCH_CHECK;
+  char line[1024];
+  if (svdmlp_describe(&de, 4096, line, sizeof line) != SVDMLP_OK) return 1;
+  printf("%d %zu %s\n", svdmlp_abi_version(), svdmlp_workspace_bytes(&de), line);
+  return svdmlp_destroy(NULL);
+}
+''')
+    exe = tmp_path / "use"
+    libdir = B.LIB_PATH.parent
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", str(ROOT / "include"), str(src), "-o", str(exe),
+                    "-L", str(libdir), "-lsvdmlp", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(" ", 2)
+    assert int(out[0]) == 1 and int(out[1]) > 0 and out[2].startswith("path=5 bf16-tiled-staged:")
