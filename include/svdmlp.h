@@ -67,11 +67,9 @@ enum {
   SVDMLP_FLAG_FORCE_TILED = 1u << 0,    /* bf16: always take the MFMA-tiled (prefill) path */
   SVDMLP_FLAG_FORCE_STREAM = 1u << 1,   /* bf16: always take the weight-streaming (decode) path; needs M <= 128 */
   SVDMLP_FLAG_SKIP_ARCH_CHECK = 1u << 2,/* do not require gfx950 (host-only unit tests of argument handling) */
-  SVDMLP_FLAG_STREAM_ONE_KERNEL = 1u << 3,/* weight-streaming path as one persistent kernel instead of four launches
-                                           (used when M <= 32 and the extents fit its per-wave register budget).  Its
-                                           workgroups wait for each other (bounded polls), so it wants the device to
-                                           itself, and each launch carries a forward number from the host: such a
-                                           forward must not be captured into a graph */
+  SVDMLP_FLAG_STREAM_ONE_KERNEL = 1u << 3,/* weight-streaming path as one kernel that works through a queue of tiles
+                                           instead of four launches (used when M <= 32 and the extents fit its
+                                           per-wave register budget); slower than the four launches as measured */
   SVDMLP_FLAG_TILED_FUSED = 1u << 4     /* MFMA-tiled path: keep the gated activation in registers (one fused kernel)
                                            instead of staging it through the workspace */
 };
@@ -110,8 +108,7 @@ int svdmlp_create(const svdmlp_desc *desc, svdmlp_ctx **out);
  * the host and allocates nothing.  1 <= M <= max_M; M == 0 is accepted and does nothing.  At most one
  * forward per context may be in flight at a time (the workspace holds its intermediates), so
  * successive calls must be ordered on one stream or by events.  The call only launches kernels (no memset, no
- * copy), so it may be recorded into a HIP graph by stream capture (not with SVDMLP_FLAG_STREAM_ONE_KERNEL, and
- * not while a per-kernel profile is open). */
+ * copy), so it may be recorded into a HIP graph by stream capture (not while a per-kernel profile is open). */
 int svdmlp_forward(svdmlp_ctx *ctx, const void *X, int64_t M, void *Y, void *hip_stream);
 
 /* Release the context's host memory.  Does not free or touch device memory; the caller must make

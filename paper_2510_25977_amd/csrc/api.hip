@@ -313,7 +313,7 @@ int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip
       if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
       stream_path = true;
     }
-    const bool one_kernel = stream_path && M <= 32 && (c->plan.flags & SVDMLP_FLAG_STREAM_ONE_KERNEL) && bf16_decode_supported(c);
+    const bool one_kernel = stream_path && M <= 32 && (c->plan.flags & SVDMLP_FLAG_STREAM_ONE_KERNEL) && bf16_decode_supported(c, M);
     const bool staged = staged_supported(c->plan.rd, c->plan.ffn) && !(c->plan.flags & SVDMLP_FLAG_TILED_FUSED);
     c->last_path = stream_path ? (one_kernel ? 4 : 3) : (staged ? 5 : 2);
     e = !stream_path ? bf16_tiled_forward(c, X, M, Y, st)

@@ -192,7 +192,7 @@ int stream_tiles16(int64_t M);
 bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd);   // rows the weight-streaming path takes (four 32-row tiles)
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
-bool bf16_decode_supported(const Ctx* c);
+bool bf16_decode_supported(const Ctx* c, int64_t M);
 
 // Optional per-kernel timing: HIP events recorded on the caller's stream around every kernel launch of
 // a forward (only while a profile is open; see svdmlp_profile_begin in svdmlp.h).
@@ -212,7 +212,6 @@ struct Ctx {
   int last_hip_error;
   int last_path;
   int n_cus = 0;                                 // compute units of the device the context was created on
-  mutable unsigned long long decode_gen = 0;     // forwards launched on the single-kernel decode path
   mutable Prof prof;
 };
 

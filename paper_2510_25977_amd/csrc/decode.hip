@@ -1,450 +1,418 @@
-// bf16 decode path in ONE persistent launch (M <= 32): the four products of the factored MLP
-// (paper Alg. 2) as four phases of a single kernel, one workgroup per CU.
+// bf16 decode path in ONE launch (M <= 32): the four products of the factored MLP (paper Alg. 2) as the four
+// phases of a single kernel that works through a queue of tiles.
 //
-//   D1  T^T  = [Ug|Uu]^T X^T          split-K over d, over workgroups
-//   D2  H^T  = SiLU(Vg^T Tg^T) .* (Vu^T Tu^T)
-//   D4  Td^T = Ud^T H^T               split-K over ffn, over workgroups
-//   D5  Y^T  = Vd^T Td^T
+//   P1  T^T  = [Ug|Uu]^T X^T          16-column tiles, contraction over d cut into S1 ranges    (16 x 16 x 32 MFMAs)
+//   P2  H^T  = SiLU(Vg^T Tg^T) .* (Vu^T Tu^T)     32-column tiles                               (32 x 32 x 16 MFMAs)
+//   P4  Td^T = Ud^T H^T               16-column tiles, contraction over ffn cut into S4 ranges
+//   P5  Y^T  = Vd^T Td^T              32-column tiles
 //
-// The forward is weight-bandwidth bound (every factor element is read exactly once) and the phases depend on
-// each other only through tiny activations, so the kernel keeps HBM busy while it synchronises: every wave
-// knows from its block id which weight frags it will need in every phase; the frags of the first two phases
-// are requested at kernel start and those of each later phase as soon as the previous phase's MFMAs are
-// issued, i.e. always one phase ahead of the dependency they wait for.
+// Four dependent launches cost about 11 us on this machine before any work is done, more than streaming the
+// factors takes; one launch pays that once.  It does not pay off, though: handing a phase's result over inside the
+// kernel (write-through store, acknowledgement, counter, poll, read) takes as long as a launch does, and a workgroup
+// goes through its four or five items one after the other, so this variant measures slower than the four launches
+// and is used on request only (SVDMLP_FLAG_STREAM_ONE_KERNEL).  The phases depend on each other through the (tiny)
+// activations, so workgroups have to wait for each other inside the kernel.  That is made safe without assuming that the whole
+// grid is resident: work items (tiles, in phase order) are handed out by an atomic counter, and an item only ever
+// waits for items with smaller numbers.  A smaller number has been claimed earlier, by a workgroup that is running
+// and that finishes its claimed items in order, so every wait ends whatever number of workgroups the device can
+// hold at once, and whatever else runs beside the kernel.  Every wait is bounded all the same (POLL_LIMIT): on a
+// timeout the context's error word is set and the workgroups drain the queue without computing.
 //
-// Wave 0 of a workgroup is the *reducer*: it never loads weights, so its memory counter is never blocked behind
-// a prefetch (loads, stores and atomics of a wave complete in order).  It sums the streamers' partial tiles
-// from LDS, exchanges partials with other workgroups, takes tickets, signals and polls.  Waves 1..11 are
-// *streamers*: they only load frags and issue MFMAs, and meet the reducer at workgroup barriers that do not
-// drain outstanding loads.
-//
-// Phases are separated by completion counters in device memory (monotonic across forwards, compared with a
-// generation number: no reset, no second kernel).  Activations and partial tiles cross workgroups (and XCDs,
-// whose L2s are not coherent with each other) as device-scope relaxed atomic stores (write-through).  Readers
-// need no cache invalidate: caches are invalidated at kernel start, and within the kernel nobody reads an
-// activation buffer before the counter that publishes it has been seen, so no stale line can exist; nobody pays
-// an L2 write-back or invalidate.  Cross-workgroup sums are
-// added in a fixed order by the last workgroup to take a ticket, so results are bit-reproducible.
-//
-// Every wait is bounded: a reducer that polls longer than POLL_LIMIT gives up, raises the context's error word
-// and its workgroup skips the remaining phases, so every wave of the grid exits even if the grid could not
-// become co-resident.
+// A workgroup requests the weight frags of its item before it waits for the item's dependency (weights depend on
+// nothing), and claims its next item while it works on the current one, so HBM keeps streaming while the
+// counters settle.  Activations and split-K partial tiles cross workgroups (and XCDs, whose L2s are not coherent
+// with each other) as device-scope relaxed atomic stores (write-through); readers need no cache invalidate: caches
+// are invalidated at kernel start, and nobody reads an activation before the counter that publishes it has been
+// seen.  Cross-workgroup sums are added in range order by the last workgroup to take a tile's ticket, so results
+// are bit-reproducible.  All counters are back at zero when the kernel ends (the last workgroup to leave resets
+// them), so a forward carries no state from the host and can be recorded into a graph.
 #include "common.h"
 
 namespace svdmlp {
 
-constexpr int DW = 12;                   // waves per workgroup: 1 reducer + 11 streamers
-constexpr int NS = DW - 1;               // streamer waves
-constexpr int CAP1 = 4, CAP2 = 4, CAP4 = 6, CAP5 = 4;   // weight frags a streamer may hold per phase (per work item)
-constexpr int VB2 = 2;                   // D2 work items per workgroup
-constexpr int POLL_LIMIT = 1 << 21;
+constexpr int QW = 8;                    // waves per workgroup
+constexpr int QCAP = 8;                  // contraction blocks (of the phase's MFMA) a wave may hold per item
+constexpr int POLL_LIMIT = 1 << 20;
+constexpr int CTR_STRIDE = 32;           // uints: every counter in a cache line of its own
+enum { C_QHEAD = 0, C_DONE1 = 1, C_DONE2 = 2, C_DONE4 = 3, C_EXIT = 4, C_ERR = 5 };
 
-struct DecodeArgs {
+struct DqArgs {
   const char *wU, *wVg, *wVu, *wUd, *wVd;
   const uint16_t* X;
   uint16_t* Y;
-  char *T, *H, *Td;                      // activation frags
-  float* part;                           // split-K partial tiles
-  unsigned long long* done;              // [0] D1 tiles done, [1] D2 items done, [2] D4 tiles done (monotonic)
-  unsigned long long* flags;             // [phase][workgroup], one 128-byte line each: generation whose phase is complete
-  int* tickets;                          // [0, t1) D1 tiles, [2048, 2048 + t4) D4 tiles (zero between forwards)
-  int* err;
-  unsigned long long gen;                // 1-based forward number of this context
-  int M, d, r, G;
-  int KB1, t1, S1, kbs1, kw1;            // contraction blocks, tiles, splits, blocks per split / per streamer
-  int KB2, t2, kw2;
-  int KB4, t4, S4, kbs4, kw4;
-  int KB5, t5, kw5;
+  char *T, *H, *Td;                      // activation frags (one 32-row tile)
+  float* part;                           // split-K partial tiles: P1's, then P4's
+  int *tick1, *tick4;                    // tickets per 16-column tile, TICKET_STRIDE ints apart (zero between forwards)
+  unsigned* ctr;                         // counters, CTR_STRIDE uints apart (zero between forwards; C_ERR is sticky)
+  int M, d, r;
+  int KB1, KBr, KBf, KBq;                // contraction blocks of 16: d, r, ffn, rd
+  int t1, S1, t2, t4, S4, t5;            // tiles and ranges per phase
+  int n1, n2, n4, n5;                    // items per phase
 };
 
-// workgroup barrier for LDS hand-offs: waits for this wave's LDS traffic only, never for its global loads
-__device__ __forceinline__ void bar_lds() {
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
+__device__ __forceinline__ f32x4 mfma16q(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ void store_frag_wt(char* dst, const bf16x8& v) {
-  const u32x4 u = __builtin_bit_cast(u32x4, v);  // 16 bytes as four write-through dword stores
+// 16 bytes as four write-through dword stores
+__device__ __forceinline__ void store16_wt(char* dst, const bf16x8& v) {
+  const u32x4 u = __builtin_bit_cast(u32x4, v);
   unsigned* p = reinterpret_cast<unsigned*>(dst);
 #pragma unroll
   for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, u[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// LDS staging of accumulator tiles: red[acc][streamer][lane][16]
-typedef float RedBuf[2][NS][64][16];
+struct DqShared {
+  f32x4 red[2][QW][4][64];               // staging of the waves' accumulator tiles (64 KiB)
+  int item, ok, last;
+};
 
-__device__ __forceinline__ void red_write(RedBuf& red, int n, int ws, int lane, const f32x16& acc) {
-  f32x4* dst = reinterpret_cast<f32x4*>(&red[n][ws][lane][0]);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) dst[q] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-}
-// sum over the first nw streamers, in order
-__device__ __forceinline__ void red_sum(const RedBuf& red, int n, int nw, int lane, float (&v)[16]) {
-#pragma unroll
-  for (int e = 0; e < 16; ++e) v[e] = 0.f;
-  for (int ww = 0; ww < nw; ++ww) {
-    const f32x4* src = reinterpret_cast<const f32x4*>(&red[n][ww][lane][0]);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const f32x4 x = src[q];
-      v[4 * q] += x[0]; v[4 * q + 1] += x[1]; v[4 * q + 2] += x[2]; v[4 * q + 3] += x[3];
+// Thread 0 polls counter `which` until it shows `target`; everybody learns the outcome.  Two barriers.
+__device__ __forceinline__ bool dq_wait(DqShared& sh, const DqArgs& a, int which, unsigned target) {
+  if (threadIdx.x == 0) {
+    int ok = 0;
+    for (int polls = 0; polls < POLL_LIMIT; ++polls) {
+      if (__hip_atomic_load(a.ctr + which * CTR_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) { ok = 1; break; }
+      __builtin_amdgcn_s_sleep(1);
     }
+    if (!ok) __hip_atomic_store(a.ctr + C_ERR * CTR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sh.ok = ok;
   }
+  __syncthreads();
+  const bool ok = sh.ok != 0;
+  __syncthreads();
+  return ok;
 }
 
-// Reducer only.  Cross-workgroup part of a split-K tile: publish this workgroup's partial, take a ticket, and
-// if it was the last one add all S partials in split order into v.  Returns whether this workgroup finishes the tile.
-__device__ __forceinline__ bool exchange_partials(float* part_tile, int S, int sp, int* ticket, int lane, float (&v)[16]) {
-  if (S == 1) return true;
-  float* mine = part_tile + (size_t)sp * 1024;
-#pragma unroll
-  for (int e = 0; e < 16; ++e) __hip_atomic_store(&mine[e * 64 + lane], v[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  asm volatile("" ::: "memory");
-  wait_vmcnt<0>();   // the stores have been acknowledged by memory
-  int old = 0;
-  if (lane == 0) old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  old = __builtin_amdgcn_readfirstlane(old);
-  if (old != S - 1) return false;
-#pragma unroll
-  for (int e = 0; e < 16; ++e) v[e] = 0.f;
-  for (int q0 = 0; q0 < S; q0 += 2) {   // two partial tiles of loads in flight; additions stay in split order
-    float tmp[2][16];
-#pragma unroll
-    for (int qq = 0; qq < 2; ++qq) {
-      const int q = q0 + qq < S ? q0 + qq : S - 1;
-      const float* src = part_tile + (size_t)q * 1024 + lane;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) tmp[qq][e] = __hip_atomic_load(src + e * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-#pragma unroll
-    for (int qq = 0; qq < 2; ++qq)
-      if (q0 + qq < S) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] += tmp[qq][e];
-      }
-  }
-  if (lane == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next forward
-  return true;
-}
-
-constexpr int FLAG_STRIDE = 16;   // in 8-byte words: every workgroup polls a cache line of its own
-
-// Reducer only: the stores above are in memory -> bump a completion counter.  Whoever brings it to `target`
-// tells every workgroup by writing the generation into that workgroup's own flag line, so that the waiting
-// reducers do not all poll (and delay the atomics on) one address.
-__device__ __forceinline__ void signal_done(unsigned long long* ctr, unsigned long long n, unsigned long long target,
-                                            unsigned long long* flags, unsigned long long gen, int G, int lane) {
+// The calling wave's output stores have been acknowledged by memory -> count one finished tile.
+__device__ __forceinline__ void dq_signal(const DqArgs& a, int which, int lane) {
   asm volatile("" ::: "memory");
   wait_vmcnt<0>();
-  if (n == 0) return;
-  unsigned long long old = 0;
-  if (lane == 0) old = __hip_atomic_fetch_add(ctr, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)old), hi = __builtin_amdgcn_readfirstlane((unsigned)(old >> 32));
-  old = ((unsigned long long)hi << 32) | lo;
-  if (old + n == target)
-    for (int g = lane; g < G; g += 64)
-      __hip_atomic_store(&flags[(size_t)g * FLAG_STRIDE], gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (lane == 0) __hip_atomic_fetch_add(a.ctr + which * CTR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Reducer only: poll this workgroup's flag until it shows generation `gen`; false on timeout.
-__device__ __forceinline__ bool poll_flag(const unsigned long long* flag, unsigned long long gen) {
-  int polls = 0;
-  while (true) {
-    unsigned long long c = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)c), hi = __builtin_amdgcn_readfirstlane((unsigned)(c >> 32));
-    c = ((unsigned long long)hi << 32) | lo;
-    if (c >= gen) return true;
-    if (++polls >= POLL_LIMIT) return false;
-    __builtin_amdgcn_s_sleep(2);
+// ------------------------------------------------------------------------------------------------
+// P1 / P4: one 16-column tile over one contraction range, MT 16-row tiles of the batch.
+// Lane l of a wave: row / column i = l % 16, contraction group g = l / 16 (k = 32 kb2 + 8 g .. + 7); a 16-row weight
+// operand of block pair (2 kb2, 2 kb2 + 1) is lanes 16 hn .. and 32 + 16 hn .. of those two 32-row frags.
+// ------------------------------------------------------------------------------------------------
+template <bool FIRST, int MT>
+__device__ __forceinline__ void dq_split_phase(DqShared& sh, const DqArgs& a, int it, bool& failed, unsigned& known) {
+  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+  const int S = FIRST ? a.S1 : a.S4;
+  const int tile = it / S, sp = it % S;
+  const int KB = FIRST ? a.KB1 : a.KBf, KB2 = KB / 2;
+  const int kbs = (KB2 + S - 1) / S, kw = (kbs + QW - 1) / QW;
+  int k0 = sp * kbs + w * kw, k1 = k0 + kw;
+  const int kend = (sp + 1) * kbs < KB2 ? (sp + 1) * kbs : KB2;
+  if (k1 > kend) k1 = kend;
+  const int i = lane % 16, g = lane / 16, fsel = g / 2;
+  const int tile32 = tile / 2, hn = tile % 2;
+  const size_t wl = (size_t)(16 * hn + i + 32 * (g % 2)) * 16;
+  // wU: [32-column tile][KB1] frags; wUd: [KBf][32-column tile] frags
+  const char* wbase = FIRST ? a.wU + (size_t)tile32 * KB * FRAG_BYTES + wl : a.wUd + (size_t)tile32 * FRAG_BYTES + wl;
+  const size_t wstride = FIRST ? (size_t)FRAG_BYTES : (size_t)(a.t4 / 2) * FRAG_BYTES;
+
+  bf16x8 W[QCAP];
+#pragma unroll
+  for (int j = 0; j < QCAP; ++j)
+    if (k0 + j < k1) W[j] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(2 * (k0 + j) + fsel) * wstride);
+  if (!FIRST) {   // the ffn-wide activation must be complete
+    if (!failed && !(known & (1u << C_DONE2))) {
+      if (dq_wait(sh, a, C_DONE2, (unsigned)a.t2)) known |= 1u << C_DONE2;
+      else failed = true;
+    }
+  }
+  f32x4 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (!failed) {
+#pragma unroll
+    for (int j = 0; j < QCAP; ++j)
+      if (k0 + j < k1) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          bf16x8 av;
+          if (FIRST) {
+            const int row = 16 * mt + i;
+            av = *reinterpret_cast<const bf16x8*>(a.X + (size_t)(row < a.M ? row : a.M - 1) * a.d + 32 * (k0 + j) + 8 * g);
+          } else {
+            av = *reinterpret_cast<const bf16x8*>(a.H + (size_t)(2 * (k0 + j) + fsel) * FRAG_BYTES + (16 * mt + i + 32 * (g % 2)) * 16);
+          }
+          acc[mt] = mfma16q(W[j], av, acc[mt]);
+        }
+      }
+  }
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) sh.red[0][w][mt][lane] = acc[mt];
+  __syncthreads();
+  f32x4 v[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) v[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (w == 0) {
+#pragma unroll
+    for (int ww = 0; ww < QW; ++ww)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) v[mt] += sh.red[0][ww][mt][lane];
+  }
+  bool finish = w == 0;
+  if (S > 1) {
+    float* tpart = (FIRST ? a.part : a.part + (size_t)a.n1 * MT * 256) + (size_t)tile * S * (MT * 256);
+    int* ticket = (FIRST ? a.tick1 : a.tick4) + tile * TICKET_STRIDE;
+    if (w == 0) {
+      float* mine = tpart + (size_t)sp * (MT * 256);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          __hip_atomic_store(&mine[(mt * 4 + e) * 64 + lane], v[mt][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      asm volatile("" ::: "memory");
+      wait_vmcnt<0>();   // the stores have been acknowledged by memory
+      if (lane == 0) sh.last = (__hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == S - 1);
+    }
+    __syncthreads();
+    finish = w == 0 && sh.last != 0;
+    if (finish) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) v[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      constexpr int QB = 8 / MT;   // partial tiles in flight (8 KiB); additions in range order
+      for (int q0 = 0; q0 < S; q0 += QB) {
+        f32x4 tmp[QB][MT];
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq) {
+          const int q = q0 + qq < S ? q0 + qq : S - 1;
+          const float* src = tpart + (size_t)q * (MT * 256) + lane;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              tmp[qq][mt][e] = __hip_atomic_load(src + (mt * 4 + e) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq)
+          if (q0 + qq < S) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) v[mt] += tmp[qq][mt];
+          }
+      }
+      if (lane == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next forward
+    }
+  }
+  if (finish) {
+    // The tile is contraction block `frag` of the next product's activation, in chain order: element s of frag lane
+    // (row, h) is column 8 (s / 4) + 4 h + s % 4: the four values of lane (m, g = h), then those of lane (m, g = 2 + h).
+    // Lanes 0..31 write the frag lanes of rows 0..15, lanes 32..63 those of rows 16..31 (zeros if MT = 1).
+    const int m = lane % 16, h = (lane / 16) % 2, up = lane / 32;
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float lo = __shfl(v[0][e], m + 16 * h, 64), hi = __shfl(v[0][e], m + 16 * (2 + h), 64);
+      if (MT == 2) {
+        const float lo1 = __shfl(v[MT - 1][e], m + 16 * h, 64), hi1 = __shfl(v[MT - 1][e], m + 16 * (2 + h), 64);
+        lo = up ? lo1 : lo;
+        hi = up ? hi1 : hi;
+      } else if (up) {
+        lo = 0.f;
+        hi = 0.f;
+      }
+      o[e] = (__bf16)lo;
+      o[4 + e] = (__bf16)hi;
+    }
+    size_t frag;
+    if (FIRST) {
+      const int p0 = 16 * tile;
+      const int which = p0 >= a.r ? 1 : 0;
+      frag = (size_t)which * (a.r / 16) + (p0 - which * a.r) / 16;
+    } else {
+      frag = (size_t)tile;
+    }
+    store16_wt((FIRST ? a.T : a.Td) + (frag * 64 + 16 * up + m + 32 * h) * 16, o);
+    dq_signal(a, FIRST ? C_DONE1 : C_DONE4, lane);
   }
 }
 
-__global__ __launch_bounds__(DW * 64) void k_decode(DecodeArgs a) {
-  __shared__ __attribute__((aligned(16))) RedBuf red;
-  __shared__ int s_ok;
-  const int lane = threadIdx.x % 64;
-  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-  const bool reducer = w == 0;
-  const int ws = w - 1;                                   // streamer index
-  const int il = lane % 32, h = lane / 32;
-  const int b = blockIdx.x;
+// ------------------------------------------------------------------------------------------------
+// P2 / P5: one 32-column tile over the whole contraction (r resp. rd), 32 x 32 x 16 MFMAs, lane = activation row.
+// ------------------------------------------------------------------------------------------------
+template <bool GATE>
+__device__ __forceinline__ void dq_whole_phase(DqShared& sh, const DqArgs& a, int tile, bool& failed, unsigned& known) {
+  constexpr int NACC = GATE ? 2 : 1;
+  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+  const int KB = GATE ? a.KBr : a.KBq;
+  const int kw = (KB + QW - 1) / QW;
+  const int k0 = w * kw;
+  const int k1 = k0 + kw < KB ? k0 + kw : KB;
   const size_t lane16 = (size_t)lane * 16;
-
-  // ---------------- work items ----------------
-  const bool has1 = b < a.t1 * a.S1;                       // D1: tile b / S1, split b % S1
-  const int tile1 = b / a.S1, sp1 = b % a.S1;
-  const int k1b = sp1 * a.kbs1 + ws * a.kw1;
-  int k1e = k1b + a.kw1;
-  { const int e = (sp1 + 1) * a.kbs1 < a.KB1 ? (sp1 + 1) * a.kbs1 : a.KB1; k1e = k1e < e ? k1e : e; }
-  const int k2b = ws * a.kw2;                              // D2: tiles b and b + G, whole contraction
-  const int k2e = (k2b + a.kw2 < a.KB2) ? k2b + a.kw2 : a.KB2;
-  const bool has4 = b < a.t4 * a.S4;                       // D4: tile b / S4, split b % S4
-  const int tile4 = b / a.S4, sp4 = b % a.S4;
-  const int k4b = sp4 * a.kbs4 + ws * a.kw4;
-  int k4e = k4b + a.kw4;
-  { const int e = (sp4 + 1) * a.kbs4 < a.KB4 ? (sp4 + 1) * a.kbs4 : a.KB4; k4e = k4e < e ? k4e : e; }
-  const bool has5 = b < a.t5;                              // D5: tile b, whole contraction
-  const int k5b = ws * a.kw5;
-  const int k5e = (k5b + a.kw5 < a.KB5) ? k5b + a.kw5 : a.KB5;
-  const int n1 = (a.kbs1 + a.kw1 - 1) / a.kw1, n2 = (a.KB2 + a.kw2 - 1) / a.kw2;   // streamers that hold data
-  const int n4 = (a.kbs4 + a.kw4 - 1) / a.kw4, n5 = (a.KB5 + a.kw5 - 1) / a.kw5;
-
-  bf16x8 W1[CAP1], X1[CAP1], W2g[VB2][CAP2], W2u[VB2][CAP2];
-  if (!reducer) {
-    // ---- requests at kernel start: D1 weights and X ----
-    const uint16_t* xrow = a.X + (size_t)(il < a.M ? il : a.M - 1) * a.d + 8 * h;   // natural order: X[il][16 kb + 8 h ..]
+  const char* w0 = (GATE ? a.wVg : a.wVd) + (size_t)tile * KB * FRAG_BYTES + lane16;
+  const char* w1 = GATE ? a.wVu + (size_t)tile * KB * FRAG_BYTES + lane16 : nullptr;
+  bf16x8 W0[QCAP], W1[GATE ? QCAP : 1];
 #pragma unroll
-    for (int j = 0; j < CAP1; ++j)
-      if (has1 && k1b + j < k1e) {
-        W1[j] = *reinterpret_cast<const bf16x8*>(a.wU + ((size_t)tile1 * a.KB1 + k1b + j) * FRAG_BYTES + lane16);
-        X1[j] = *reinterpret_cast<const bf16x8*>(xrow + 16 * (k1b + j));
-      }
-    // ---- D1 ----
-    if (has1) {
-      f32x16 acc;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-      for (int j = 0; j < CAP1; ++j)
-        if (k1b + j < k1e) acc = mfma32(W1[j], X1[j], acc);
-      if (ws < n1) red_write(red, 0, ws, lane, acc);
+  for (int j = 0; j < QCAP; ++j)
+    if (k0 + j < k1) {
+      W0[j] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)(k0 + j) * FRAG_BYTES);
+      if (GATE) W1[j] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)(k0 + j) * FRAG_BYTES);
     }
-    // ---- D2 weights: requested only now, so that they do not queue in front of the (small) D1 weights; they
-    // stream while the reducers exchange the D1 partials ----
+  constexpr int DEP = GATE ? C_DONE1 : C_DONE4;
+  if (!failed && !(known & (1u << DEP))) {
+    if (dq_wait(sh, a, DEP, (unsigned)(GATE ? a.t1 : a.t4))) known |= 1u << DEP;
+    else failed = true;
+  }
+  f32x16 acc[NACC];
 #pragma unroll
-    for (int v = 0; v < VB2; ++v) {
-      const int tile = b + v * a.G;
+  for (int n = 0; n < NACC; ++n)
 #pragma unroll
-      for (int j = 0; j < CAP2; ++j)
-        if (tile < a.t2 && k2b + j < k2e) {
-          const size_t off = ((size_t)tile * a.KB2 + k2b + j) * FRAG_BYTES + lane16;
-          W2g[v][j] = *reinterpret_cast<const bf16x8*>(a.wVg + off);
-          W2u[v][j] = *reinterpret_cast<const bf16x8*>(a.wVu + off);
+    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+  if (!failed) {
+    const char* act = (GATE ? a.T : a.Td) + lane16;
+#pragma unroll
+    for (int j = 0; j < QCAP; ++j)
+      if (k0 + j < k1) {
+        const bf16x8 av = *reinterpret_cast<const bf16x8*>(act + (size_t)(k0 + j) * FRAG_BYTES);
+        acc[0] = mfma32(W0[j], av, acc[0]);
+        if (GATE) {
+          const bf16x8 au = *reinterpret_cast<const bf16x8*>(act + (size_t)(KB + k0 + j) * FRAG_BYTES);
+          acc[NACC - 1] = mfma32(W1[j], au, acc[NACC - 1]);
         }
-    }
+      }
   }
-  bar_lds();
-  if (reducer) {
-    bool ok = true;
-    if (has1) {
-      float v[16];
-      red_sum(red, 0, n1, lane, v);
-      if (exchange_partials(a.part + (size_t)tile1 * a.S1 * 1024, a.S1, sp1, &a.tickets[tile1], lane, v)) {
-        const int p0 = 32 * tile1;
-        const int which = p0 >= a.r ? 1 : 0;
-        const size_t frag = (size_t)which * (a.r / 16) + (p0 - which * a.r) / 16;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          bf16x8 o;
+  for (int n = 0; n < NACC; ++n)
 #pragma unroll
-          for (int s = 0; s < 8; ++s) o[s] = (__bf16)v[8 * t + s];
-          store_frag_wt(a.T + ((frag + t) * 64 + lane) * 16, o);
-        }
-        signal_done(&a.done[0], 1, a.gen * (unsigned long long)a.t1, a.flags, a.gen, a.G, lane);
-      }
-    }
-    ok = poll_flag(&a.flags[(size_t)b * FLAG_STRIDE], a.gen);
-    if (lane == 0) s_ok = ok;
-  }
-  bar_lds();
-  bool ok = s_ok != 0;
-
-  // ---------------- D2 ----------------
-  bf16x8 W4[CAP4];
-  if (!reducer && ok) {
-    bf16x8 A2g[CAP2], A2u[CAP2];
+    for (int pl = 0; pl < 4; ++pl)
+      sh.red[n][w][pl][lane] = f32x4{acc[n][4 * pl], acc[n][4 * pl + 1], acc[n][4 * pl + 2], acc[n][4 * pl + 3]};
+  __syncthreads();
+  // wave t < 2 finishes registers 8 t .. 8 t + 7 of the tile (= one chain-order frag)
+  if (w < 2) {
+    float v[NACC][8];
 #pragma unroll
-    for (int j = 0; j < CAP2; ++j)
-      if (k2b + j < k2e) {
-        A2g[j] = *reinterpret_cast<const bf16x8*>(a.T + (size_t)(k2b + j) * FRAG_BYTES + lane16);
-        A2u[j] = *reinterpret_cast<const bf16x8*>(a.T + (size_t)(a.KB2 + k2b + j) * FRAG_BYTES + lane16);
-      }
-    // items are processed one after the other so that only one (G, P) accumulator pair is live
-    static_assert(VB2 == 2, "barrier sequence below is written for two items");
+    for (int n = 0; n < NACC; ++n) {
 #pragma unroll
-    for (int v = 0; v < VB2; ++v) {
-      f32x16 g, p;
+      for (int s = 0; s < 8; ++s) v[n][s] = 0.f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { g[e] = 0.f; p[e] = 0.f; }
-      if (b + v * a.G < a.t2) {
+      for (int ww = 0; ww < QW; ++ww) {
+        const f32x4 x0 = sh.red[n][ww][2 * w][lane], x1 = sh.red[n][ww][2 * w + 1][lane];
 #pragma unroll
-        for (int j = 0; j < CAP2; ++j)
-          if (k2b + j < k2e) {
-            g = mfma32(W2g[v][j], A2g[j], g);
-            p = mfma32(W2u[v][j], A2u[j], p);
-          }
-      }
-      if (v == 1) {
-        // D4 weights: one phase ahead (Ud frags are contraction-block major: [kb][q tile])
-#pragma unroll
-        for (int j = 0; j < CAP4; ++j)
-          if (has4 && k4b + j < k4e)
-            W4[j] = *reinterpret_cast<const bf16x8*>(a.wUd + ((size_t)(k4b + j) * a.t4 + tile4) * FRAG_BYTES + lane16);
-        bar_lds();                   // B0: reducer has read item 0
-      }
-      if (ws < n2) { red_write(red, 0, ws, lane, g); red_write(red, 1, ws, lane, p); }
-      bar_lds();                     // A_v: item v staged
-    }
-  } else if (!reducer) {
-    bar_lds(); bar_lds(); bar_lds();
-  } else {
-    unsigned long long items = 0;
-#pragma unroll
-    for (int v = 0; v < VB2; ++v) {
-      bar_lds();                     // A_v
-      const int tile = b + v * a.G;
-      float gs[16], ps[16];
-      const bool live = ok && tile < a.t2;
-      if (live) { red_sum(red, 0, n2, lane, gs); red_sum(red, 1, n2, lane, ps); }
-      if (v + 1 < VB2) bar_lds();    // B_v
-      if (live) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          bf16x8 o;
-#pragma unroll
-          for (int s = 0; s < 8; ++s) {
-            const float x = gs[8 * t + s];
-            o[s] = (__bf16)(x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)) * ps[8 * t + s]);
-          }
-          store_frag_wt(a.H + (((size_t)2 * tile + t) * 64 + lane) * 16, o);
-        }
-        ++items;
+        for (int s = 0; s < 4; ++s) { v[n][s] += x0[s]; v[n][4 + s] += x1[s]; }
       }
     }
-    signal_done(&a.done[1], items, a.gen * (unsigned long long)a.t2, a.flags + (size_t)a.G * FLAG_STRIDE, a.gen, a.G, lane);
-    if (ok) ok = poll_flag(&a.flags[((size_t)a.G + b) * FLAG_STRIDE], a.gen);
-    if (lane == 0) s_ok = ok;
-  }
-  bar_lds();
-  ok = s_ok != 0;
-
-  // ---------------- D4 ----------------
-  bf16x8 W5[CAP5];
-  if (!reducer) {
-    if (ok && has4) {
-      bf16x8 A4[CAP4];
+    if (GATE) {
+      bf16x8 o;
 #pragma unroll
-      for (int j = 0; j < CAP4; ++j)
-        if (k4b + j < k4e) A4[j] = *reinterpret_cast<const bf16x8*>(a.H + (size_t)(k4b + j) * FRAG_BYTES + lane16);
-      f32x16 acc;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-      for (int j = 0; j < CAP4; ++j)
-        if (k4b + j < k4e) acc = mfma32(W4[j], A4[j], acc);
-      if (ws < n4) red_write(red, 0, ws, lane, acc);
-    }
-    // D5 weights: one phase ahead
-#pragma unroll
-    for (int j = 0; j < CAP5; ++j)
-      if (ok && has5 && k5b + j < k5e) W5[j] = *reinterpret_cast<const bf16x8*>(a.wVd + ((size_t)b * a.KB5 + k5b + j) * FRAG_BYTES + lane16);
-  }
-  bar_lds();
-  if (reducer) {
-    if (ok && has4) {
-      float v[16];
-      red_sum(red, 0, n4, lane, v);
-      float* part4 = a.part + (size_t)a.t1 * a.S1 * 1024;   // D4's partials follow D1's
-      if (exchange_partials(part4 + (size_t)tile4 * a.S4 * 1024, a.S4, sp4, &a.tickets[2048 + tile4], lane, v)) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          bf16x8 o;
-#pragma unroll
-          for (int s = 0; s < 8; ++s) o[s] = (__bf16)v[8 * t + s];
-          store_frag_wt(a.Td + (((size_t)2 * tile4 + t) * 64 + lane) * 16, o);
-        }
-        signal_done(&a.done[2], 1, a.gen * (unsigned long long)a.t4, a.flags + (size_t)2 * a.G * FLAG_STRIDE, a.gen, a.G, lane);
+      for (int s = 0; s < 8; ++s) {
+        const float gq = v[0][s];
+        o[s] = (__bf16)(gq * __builtin_amdgcn_rcpf(1.0f + __expf(-gq)) * v[NACC - 1][s]);
       }
-    }
-    if (ok) ok = poll_flag(&a.flags[((size_t)2 * a.G + b) * FLAG_STRIDE], a.gen);
-    if (lane == 0) s_ok = ok;
-  }
-  bar_lds();
-  ok = s_ok != 0;
-
-  // ---------------- D5 ----------------
-  if (!reducer && ok && has5) {
-    f32x16 acc;
+      store16_wt(a.H + (((size_t)2 * tile + w) * 64 + lane) * 16, o);
+      asm volatile("" ::: "memory");
+      wait_vmcnt<0>();
+    } else {
+      // lane = row m; slots s <-> columns 32 tile + 16 w + 8 (s / 4) + 4 h + s % 4
+      const int il = lane % 32, h = lane / 32;
+      if (il < a.M) {
+        uint16_t* y = a.Y + (size_t)il * a.d + 32 * tile + 16 * w + 4 * h;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-    for (int j = 0; j < CAP5; ++j)
-      if (k5b + j < k5e) {
-        const bf16x8 av = *reinterpret_cast<const bf16x8*>(a.Td + (size_t)(k5b + j) * FRAG_BYTES + lane16);
-        acc = mfma32(W5[j], av, acc);
-      }
-    if (ws < n5) red_write(red, 0, ws, lane, acc);
-  }
-  bar_lds();
-  if (reducer) {
-    if (ok && has5 && il < a.M) {
-      // lane = row m; register 8 t + s <-> column 32 tile + 16 t + 8 (s / 4) + 4 h + s % 4
-      float v[16];
-      red_sum(red, 0, n5, lane, v);
-      uint16_t* y = a.Y + (size_t)il * a.d + 32 * b + 4 * h;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
+        for (int gq = 0; gq < 2; ++gq) {
           bf16x4 o;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) o[i] = (__bf16)v[8 * t + 4 * g + i];
-          *reinterpret_cast<bf16x4*>(y + 16 * t + 8 * g) = o;
+          for (int q = 0; q < 4; ++q) o[q] = (__bf16)v[0][4 * gq + q];
+          *reinterpret_cast<bf16x4*>(y + 8 * gq) = o;
         }
+      }
     }
-    if (!ok && lane == 0) __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (GATE) {
+    __syncthreads();   // both frags of the tile have been acknowledged
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(a.ctr + C_DONE2 * CTR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+template <int MT>
+__global__ __launch_bounds__(QW * 64) void k_decode(DqArgs a) {
+  __shared__ DqShared sh;
+  const int total = a.n1 + a.n2 + a.n4 + a.n5;
+  if (threadIdx.x == 0)
+    sh.item = (int)__hip_atomic_fetch_add(a.ctr + C_QHEAD * CTR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  bool failed = false;
+  unsigned known = 0;   // phases this workgroup has already seen complete (bit = counter index)
+  while (true) {
+    const int it = sh.item;
+    __syncthreads();   // everybody has read the item before the slot is written again
+    if (it >= total) break;
+    // The next item is claimed now; its number is looked at when this item is done.  Not during the first phase:
+    // the workgroups that start first would take a second item of it each, and the phase would take two rounds.
+    unsigned nxt = 0;
+    const bool ahead = it >= a.n1;
+    if (ahead && threadIdx.x == 0)
+      nxt = __hip_atomic_fetch_add(a.ctr + C_QHEAD * CTR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (it < a.n1) dq_split_phase<true, MT>(sh, a, it, failed, known);
+    else if (it < a.n1 + a.n2) dq_whole_phase<true>(sh, a, it - a.n1, failed, known);
+    else if (it < a.n1 + a.n2 + a.n4) dq_split_phase<false, MT>(sh, a, it - a.n1 - a.n2, failed, known);
+    else dq_whole_phase<false>(sh, a, it - a.n1 - a.n2 - a.n4, failed, known);
+    __syncthreads();   // the staging buffer and the flags are free again
+    if (!ahead && threadIdx.x == 0)
+      nxt = __hip_atomic_fetch_add(a.ctr + C_QHEAD * CTR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) sh.item = (int)nxt;
+    __syncthreads();
+  }
+  // the last workgroup to leave puts the counters back to zero for the next forward
+  if (threadIdx.x == 0) {
+    const unsigned old = __hip_atomic_fetch_add(a.ctr + C_EXIT * CTR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == gridDim.x - 1) {
+      for (int c = C_QHEAD; c <= C_EXIT; ++c)
+        __hip_atomic_store(a.ctr + c * CTR_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 }
 
 static int ceil_div(int x, int y) { return (x + y - 1) / y; }
 
-// Decomposition of the four phases over G workgroups; false if the shape does not fit the kernel's register caps.
-static bool plan_decode(const Plan& p, int G, DecodeArgs* a) {
-  a->G = G;
-  a->KB1 = (int)(p.d / 16); a->t1 = (int)(2 * p.r / 32);
-  a->KB2 = (int)(p.r / 16); a->t2 = (int)(p.ffn / 32);
-  a->KB4 = (int)(p.ffn / 16); a->t4 = (int)(p.rd / 32);
-  a->KB5 = (int)(p.rd / 16); a->t5 = (int)(p.d / 32);
-  if (a->t1 > G || a->t4 > G || a->t5 > G || a->t2 > VB2 * G || a->t1 > 2048 || a->t4 > 2048) return false;
-  a->S1 = G / a->t1; a->kbs1 = ceil_div(a->KB1, a->S1); a->kw1 = ceil_div(a->kbs1, NS);
-  a->kw2 = ceil_div(a->KB2, NS);
-  a->S4 = G / a->t4; a->kbs4 = ceil_div(a->KB4, a->S4); a->kw4 = ceil_div(a->kbs4, NS);
-  a->kw5 = ceil_div(a->KB5, NS);
-  if (a->kw1 > CAP1 || a->kw2 > CAP2 || a->kw4 > CAP4 || a->kw5 > CAP5) return false;
+// Decomposition of the four phases; false if the shape does not fit the kernel's per-wave register caps.
+static bool plan_decode(const Plan& p, int64_t M, DqArgs* a) {
+  if (M > 32 || p.d % 32 || p.ffn % 32) return false;
+  const int mt = M <= 16 ? 1 : 2;
+  a->KB1 = (int)(p.d / 16); a->KBr = (int)(p.r / 16); a->KBf = (int)(p.ffn / 16); a->KBq = (int)(p.rd / 16);
+  a->t1 = (int)(2 * p.r / 16); a->t2 = (int)(p.ffn / 32); a->t4 = (int)(p.rd / 16); a->t5 = (int)(p.d / 32);
+  if (a->t1 > 2048 || a->t4 > 2048) return false;
+  a->S1 = stream_splits16(a->t1, a->KB1 / 2, mt);
+  a->S4 = stream_splits16(a->t4, a->KBf / 2, mt);
+  // more ranges if a wave would otherwise hold more than QCAP blocks
+  while (ceil_div(ceil_div(a->KB1 / 2, a->S1), QW) > QCAP && a->S1 < 64) ++a->S1;
+  while (ceil_div(ceil_div(a->KBf / 2, a->S4), QW) > QCAP && a->S4 < 64) ++a->S4;
+  if (ceil_div(ceil_div(a->KB1 / 2, a->S1), QW) > QCAP || ceil_div(ceil_div(a->KBf / 2, a->S4), QW) > QCAP) return false;
+  if (ceil_div(a->KBr, QW) > QCAP || ceil_div(a->KBq, QW) > QCAP) return false;
+  a->n1 = a->t1 * a->S1; a->n2 = a->t2; a->n4 = a->t4 * a->S4; a->n5 = a->t5;
   const size_t part_floats = ((size_t)8 << 20) / 4;
-  if (((size_t)a->t1 * a->S1 + (size_t)a->t4 * a->S4) * 1024 > part_floats) return false;
+  if (((size_t)a->n1 + (size_t)a->n4) * mt * 256 > part_floats) return false;
   return true;
 }
 
-bool bf16_decode_supported(const Ctx* c) {
-  DecodeArgs a;
-  return c->n_cus >= 64 && plan_decode(c->plan, c->n_cus < 256 ? c->n_cus : 256, &a);
+bool bf16_decode_supported(const Ctx* c, int64_t M) {
+  DqArgs a;
+  return c->n_cus >= 8 && plan_decode(c->plan, M, &a);
 }
 
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
-  DecodeArgs a;
-  if (!plan_decode(p, c->n_cus < 256 ? c->n_cus : 256, &a)) return (int)hipErrorInvalidValue;
+  DqArgs a;
+  if (!plan_decode(p, M, &a)) return (int)hipErrorInvalidValue;
   a.wU = ws + p.off_wU; a.wVg = ws + p.off_wVg; a.wVu = ws + p.off_wVu; a.wUd = ws + p.off_wUd; a.wVd = ws + p.off_wVd;
   a.X = static_cast<const uint16_t*>(X); a.Y = static_cast<uint16_t*>(Y);
   a.T = ws + p.off_T; a.H = ws + p.off_H; a.Td = ws + p.off_Td;
   a.part = reinterpret_cast<float*>(ws + p.off_part);
-  a.tickets = reinterpret_cast<int*>(ws + p.off_cnt);                       // ints [0, 4096)
-  a.done = reinterpret_cast<unsigned long long*>(ws + p.off_cnt + 16384);   // three 64-bit counters
-  a.err = reinterpret_cast<int*>(ws + p.off_cnt + 16384 + 64);
-  a.flags = reinterpret_cast<unsigned long long*>(ws + p.off_cnt + 32768);       // 3 phases x 256 workgroups x 128 B
-  a.gen = ++c->decode_gen;
+  a.ctr = reinterpret_cast<unsigned*>(ws + p.off_cnt);                       // six counter lines
+  a.tick1 = reinterpret_cast<int*>(ws + p.off_cnt + CNT_ONE_KERNEL_BYTES);   // the ticket lines of the four-launch path
+  a.tick4 = a.tick1 + 2048 * TICKET_STRIDE;
   a.M = (int)M; a.d = (int)p.d; a.r = (int)p.r;
   static const char* const names[1] = {"k_decode"};
   const int ps = prof_open_forward(c, 1, names);
+  const int G = c->n_cus > 0 ? (c->n_cus < 256 ? c->n_cus : 256) : 256;     // one workgroup per CU; any number works
   prof_mark(c, ps, 0, 0, st);
-  hipLaunchKernelGGL(k_decode, dim3(a.G), dim3(DW * 64), 0, st, a);
+  if (M <= 16) hipLaunchKernelGGL(k_decode<1>, dim3(G), dim3(QW * 64), 0, st, a);
+  else hipLaunchKernelGGL(k_decode<2>, dim3(G), dim3(QW * 64), 0, st, a);
   prof_mark(c, ps, 0, 1, st);
-  const int e = (int)hipGetLastError();
-  if (e) --c->decode_gen;
-  return e;
+  return (int)hipGetLastError();
 }
 
 }  // namespace svdmlp

@@ -505,14 +505,14 @@ def test_bf16_linear_random_supported_extents(M, d, n, r):
     assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
 
 
-@pytest.mark.parametrize("M", [8, 100, 300])
-def test_forward_can_be_captured_in_a_graph_and_replayed(M):
+@pytest.mark.parametrize("M,flags", [(8, 0), (100, 0), (300, 0), (8, B.FLAG_STREAM_ONE_KERNEL), (20, B.FLAG_STREAM_ONE_KERNEL)])
+def test_forward_can_be_captured_in_a_graph_and_replayed(M, flags):
     """svdmlp_forward only enqueues kernels (no memset, no allocation, no synchronisation), so a caller may capture
     it; every replay, interleaved with eager work and synchronisations, must reproduce the eager result bit for bit."""
     gi = synth.make_gated(M, 512, 1024, 192, 256, stream=63)
     dv = dev()
     f = {k: v.to(dv) for k, v in gi.factors().items()}
-    mlp = B.SvdMlp(max_M=M, **f)
+    mlp = B.SvdMlp(max_M=M, flags=flags, **f)
     X = gi.X.to(dv)
     Y = torch.empty_like(X)
     eager = mlp(X).clone()
@@ -575,3 +575,30 @@ def test_bf16_linear_arbitrary_rank(M, d, n, r):
     mlp.close()
     ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
     assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
+
+
+def test_one_kernel_decode_successive_forwards_with_different_inputs():
+    """The one-launch streaming variant hands activations from workgroup to workgroup inside the kernel; a second
+    forward with other inputs on the same context must not see anything of the first (activation buffers, counters,
+    tickets), for one and for two 16-row tiles, and must agree bit for bit with a fresh context."""
+    d_, ffn, r, rd = 512, 1408, 192, 256
+    gi = synth.make_gated(32, d_, ffn, r, rd, stream=67)
+    gj = synth.make_gated(32, d_, ffn, r, rd, stream=68)
+    dv = dev()
+    f = {k: v.to(dv) for k, v in gi.factors().items()}
+    a = {k: synth.to_f64(v) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=32, flags=B.FLAG_STREAM_ONE_KERNEL, **f)
+    outs = []
+    for X in (gi.X, gj.X, gi.X[:9], gj.X[:16], gi.X[:17], gj.X):
+        Y = mlp(X.to(dv).contiguous())
+        torch.cuda.synchronize()
+        assert mlp.last_path == 4
+        ref = oracle.gated(synth.to_f64(X), **a)
+        assert relmax(Y.cpu().to(torch.float64).numpy(), ref) <= BF16_TOL, X.shape
+        outs.append(Y.clone())
+    mlp.close()
+    fresh = B.SvdMlp(max_M=32, flags=B.FLAG_STREAM_ONE_KERNEL, **f)
+    Y = fresh(gj.X.to(dv))
+    torch.cuda.synchronize()
+    fresh.close()
+    assert torch.equal(Y, outs[1]) and torch.equal(Y, outs[5])
