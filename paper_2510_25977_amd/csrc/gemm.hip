@@ -743,6 +743,11 @@ GuPlan gate_up_plan(int MT256, int64_t ffn, int64_t r, int ncu) {
   g.rem = g.ntiles % g.G;
   g.halves = g.rem > 0 && 2 * g.rem <= g.G && q > 0;  // see GuSched
   g.nfull = g.halves ? q * g.G : g.ntiles;
+  if (2 * g.ntiles <= ncu) {   // fewer tiles than half the CUs: every tile as two halves, twice the workgroups
+    g.halves = true;
+    g.nfull = 0;
+    g.rem = g.ntiles;
+  }
   return g;
 }
 
@@ -751,9 +756,12 @@ int launch_gate_up(const Ctx* c, int MT256, hipStream_t st) {
   char* ws = c->ws;
   const int NT = (int)(p.ffn / 256);
   const GuPlan g = gate_up_plan(MT256, p.ffn, p.r, c->n_cus);
-  hipLaunchKernelGGL(k_gate_up<false>, dim3(g.G), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
-                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.nfull, 0, 0);
-  int e = (int)hipGetLastError();
+  int e = 0;
+  if (g.nfull > 0) {
+    hipLaunchKernelGGL(k_gate_up<false>, dim3(g.G), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
+                       ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.nfull, 0, 0);
+    e = (int)hipGetLastError();
+  }
   if (e || !g.halves) return e;
   hipLaunchKernelGGL(k_gate_up<true>, dim3(2 * g.rem), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
                      ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.ntiles, g.nfull, g.rem);

@@ -151,7 +151,8 @@ def test_describe_names_the_plan_of_every_baseline_config():
     small = desc(max_M=128, d=2048, ffn=8192, r=256, r_down=256)
     assert B.svdmlp_describe(small, 128).startswith("path=3 bf16-streaming: row_tiles=4")
     small.flags |= B.FLAG_FORCE_TILED
-    assert "k_gate_up[tile=256x256 tiles=32 workgroups=32 full=32 halves=0" in B.svdmlp_describe(small, 128)
+    # fewer tiles than half the CUs: every tile of k_gate_up as two 128-row halves
+    assert "k_gate_up[tile=256x256 tiles=32 workgroups=32 full=0 halves=64" in B.svdmlp_describe(small, 128)
     # wide config: 8 row tiles x 108 column tiles = 3 full rounds + 96 tiles as 192 halves
     wide = desc(max_M=2048, d=5120, ffn=27648, r=1024, r_down=1024)
     s = B.svdmlp_describe(wide, 2048)
