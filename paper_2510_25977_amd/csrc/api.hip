@@ -235,7 +235,7 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
           g.halves ? 2 * g.rem : 0, g.ngm, g.ngm ? 8 / g.ngm : 0);
       const int splits = gemm_splits(MT256, p.rd / 256, p.ffn / 32);
       put(" k_down1[tile=256x256 tiles=%d ranges=%d] k_reduce", MT256 * (int)(p.rd / 256), splits);
-      if (p.d % 256 == 0) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.d / 256));
+      if (out_uses_256(M, p.d)) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.d / 256));
       else put(" k_s5[tile=128x128 tiles=%d]", MT128 * (int)(p.d / 128));
     } else {
       put("path=2 bf16-tiled-fused:");

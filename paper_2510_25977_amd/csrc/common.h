@@ -170,6 +170,9 @@ GuPlan gate_up_plan(int MT256, int64_t ffn, int64_t r, int ncu);
 int launch_gate_up(const Ctx* c, int MT256, hipStream_t st);
 int launch_down1(const Ctx* c, int MT256, int splits, hipStream_t st);
 int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st);
+// whether the last product of the gated forward runs on k_out (256 x 256 tiles) rather than k_s5 (128 x 128): the wide
+// tile needs d % 256 == 0 and enough rows to give it tiles (up to 1024 rows the small one measures faster)
+inline bool out_uses_256(int64_t M, int64_t d) { return d % 256 == 0 && M > 1024; }
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 bool in_supported(int64_t M, int64_t d, int64_t ncols);
 int in_splits(int64_t M, int64_t d, int64_t ncols);

@@ -678,7 +678,7 @@ static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st)
   prof_mark(c, ps, 3, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   prof_mark(c, ps, 4, 0, st);
-  if (p.d % 256 == 0) {
+  if (out_uses_256(M, p.d)) {
     e = launch_out(c, M, Y, MT256, st);
   } else {
     const int CT = (int)(p.d / 128);
@@ -726,7 +726,7 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   const bool big = in_supported(M, p.d, 2 * p.r);
   const char* const s1name = big ? "k_in" : "k_s1";
   const char* const names_fused[4] = {s1name, "k_fused", "k_reduce", "k_s5"};
-  const char* const names_staged[5] = {s1name, "k_gate_up", "k_down1", "k_reduce", p.d % 256 == 0 ? "k_out" : "k_s5"};
+  const char* const names_staged[5] = {s1name, "k_gate_up", "k_down1", "k_reduce", out_uses_256(M, p.d) ? "k_out" : "k_s5"};
   const bool staged = staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
   const int ps = staged ? prof_open_forward(c, 5, names_staged) : prof_open_forward(c, 4, names_fused);
   prof_mark(c, ps, 0, 0, st);
