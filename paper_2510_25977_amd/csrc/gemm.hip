@@ -716,7 +716,9 @@ int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps) {
   // one workgroup per CU on 256 CUs; every split keeps at least four steps
   int64_t s = (256 + mt256 * qt - 1) / (mt256 * qt);
   if (s > nsteps / 4) s = nsteps / 4;
-  if (s > 16) s = 16;
+  // more ranges mean more fp32 partial tiles to write and add; with very few tiles they still pay
+  const int64_t cap = mt256 * qt <= 4 ? 32 : 16;
+  if (s > cap) s = cap;
   if (s < 1) s = 1;
   return (int)s;
 }

@@ -470,6 +470,10 @@ __global__ __launch_bounds__(256) void k_fused(const char* __restrict__ T, const
 
 // Td frags = fixed-order sum of the ffn-range partials, rounded to bf16.  One thread per (row tile, q tile,
 // contraction block t, lane): registers 8t..8t+7 of the accumulator tile are the chain-order frag.
+// BATCH: eight ranges' worth of loads in flight at a time, for many ranges over few rows (few threads, where one load
+// per addition makes the kernel a chain of memory round trips); otherwise the plain loop, which is what a grid that is
+// bound by HBM wants.  The additions are in range order either way.
+template <bool BATCH>
 __global__ __launch_bounds__(256) void k_reduce(const float* __restrict__ Tdp, char* __restrict__ Td, int splits, int MT32,
                                                 int nq_total) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -480,13 +484,35 @@ __global__ __launch_bounds__(256) void k_reduce(const float* __restrict__ Tdp, c
   const long long tile = idx / 128;  // mtile * nq_total + qt
   float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   const size_t split_stride = (size_t)MT32 * nq_total * 1024;
-  for (int sp = 0; sp < splits; ++sp) {
-    const f32x4* src = reinterpret_cast<const f32x4*>(Tdp + sp * split_stride + (size_t)tile * 1024) + 2 * t * 64 + lane;
-    const f32x4 a = src[0], b = src[64];
+  if (BATCH) {
+    for (int sp0 = 0; sp0 < splits; sp0 += 8) {
+      f32x4 a[8], b[8];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      v[e] += a[e];
-      v[4 + e] += b[e];
+      for (int j = 0; j < 8; ++j) {
+        const int sp = sp0 + j < splits ? sp0 + j : splits - 1;
+        const f32x4* src = reinterpret_cast<const f32x4*>(Tdp + sp * split_stride + (size_t)tile * 1024) + 2 * t * 64 + lane;
+        a[j] = src[0];
+        b[j] = src[64];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (sp0 + j < splits) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[e] += a[j][e];
+            v[4 + e] += b[j][e];
+          }
+        }
+    }
+  } else {
+    for (int sp = 0; sp < splits; ++sp) {
+      const f32x4* src = reinterpret_cast<const f32x4*>(Tdp + sp * split_stride + (size_t)tile * 1024) + 2 * t * 64 + lane;
+      const f32x4 a = src[0], b = src[64];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[e] += a[e];
+        v[4 + e] += b[e];
+      }
     }
   }
   bf16x8 o;
@@ -631,7 +657,9 @@ int s1_splits(int64_t mt128, int64_t pt, int64_t d) {
 int launch_reduce(const Ctx* c, const float* part, char* out, int splits, int MT32, int nq, hipStream_t st) {
   (void)c;
   const long long threads = (long long)MT32 * nq * 2 * 64;
-  hipLaunchKernelGGL(k_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, part, out, splits, MT32, nq);
+  const dim3 grid((unsigned)((threads + 255) / 256));
+  if (splits > 8) hipLaunchKernelGGL(k_reduce<true>, grid, dim3(256), 0, st, part, out, splits, MT32, nq);
+  else hipLaunchKernelGGL(k_reduce<false>, grid, dim3(256), 0, st, part, out, splits, MT32, nq);
   return (int)hipGetLastError();
 }
 
@@ -648,10 +676,7 @@ static int first_stage(const Ctx* c, const void* X, int64_t M, int64_t r_strip, 
   int e = (int)hipGetLastError();
   if (e || S == 1) return e;
   const int MT32 = 4 * MT128, nq = (int)(2 * r_strip / 32);
-  const long long threads = (long long)MT32 * nq * 2 * 64;
-  hipLaunchKernelGGL(k_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                     reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_T, S, MT32, nq);
-  return (int)hipGetLastError();
+  return launch_reduce(c, reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_T, S, MT32, nq, st);
 }
 
 // Everything after k_s1 when the gated activation is staged through HBM (gemm.hip).
@@ -671,12 +696,10 @@ static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st)
   prof_mark(c, ps, 2, 1, st);
   if (e) return e;
   const int MT32 = 8 * MT256;
-  const long long threads = (long long)MT32 * nq_total * 2 * 64;
   prof_mark(c, ps, 3, 0, st);
-  hipLaunchKernelGGL(k_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                     reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_Td, splits, MT32, nq_total);
+  e = launch_reduce(c, reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_Td, splits, MT32, nq_total, st);
   prof_mark(c, ps, 3, 1, st);
-  if ((e = (int)hipGetLastError())) return e;
+  if (e) return e;
   prof_mark(c, ps, 4, 0, st);
   if (out_uses_256(M, p.d)) {
     e = launch_out(c, M, Y, MT256, st);
@@ -750,12 +773,10 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   if (e) return e;
 
   const int MT32 = 4 * MT128;
-  const long long threads = (long long)MT32 * nq_total * 2 * 64;
   prof_mark(c, ps, 2, 0, st);
-  hipLaunchKernelGGL(k_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                     reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_Td, splits, MT32, nq_total);
+  e = launch_reduce(c, reinterpret_cast<const float*>(ws + p.off_Tdp), ws + p.off_Td, splits, MT32, nq_total, st);
   prof_mark(c, ps, 2, 1, st);
-  if ((e = (int)hipGetLastError())) return e;
+  if (e) return e;
 
   const int CT = (int)(p.d / 128);
   prof_mark(c, ps, 3, 0, st);
