@@ -121,11 +121,12 @@ __device__ __forceinline__ bf16x8 pack_chain(const f32x16& c, int t) {
 
 __device__ __forceinline__ float silu_f32(float x) { return x / (1.0f + __expf(-x)); }
 
-// XCD-aware block numbering: consecutive hardware block ids go round-robin over the 8 XCDs,
-// so logical id = (hw % 8) * (n / 8) + hw / 8 puts a contiguous range of logical ids on one XCD
-// (and its private L2).  Requires n % 8 == 0; otherwise the identity is used.
+// XCD-aware block numbering: consecutive hardware block ids go round-robin over the 8 XCDs, so XCD x runs blocks
+// x, x + 8, ...: n / 8 of them, one more if x < n % 8.  The logical id numbers an XCD's blocks consecutively, after
+// those of the XCDs before it, which puts a contiguous range of logical ids on one XCD (and its private L2).
 __device__ __forceinline__ int xcd_contiguous_id(int hw, int n) {
-  return (n % 8 == 0) ? (hw % 8) * (n / 8) + hw / 8 : hw;
+  const int q = n / 8, rem = n % 8, x = hw % 8;
+  return x * q + (x < rem ? x : rem) + hw / 8;
 }
 #endif
 

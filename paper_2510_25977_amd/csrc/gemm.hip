@@ -713,8 +713,9 @@ __global__ __launch_bounds__(G_THREADS) void k_out(const char* __restrict__ Td, 
 }
 
 int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps) {
-  // one workgroup per CU on 256 CUs; every split keeps at least four steps
-  int64_t s = (256 + mt256 * qt - 1) / (mt256 * qt);
+  // at most one workgroup per CU on 256 CUs (a few workgroups too many would cost a second round); every range keeps at
+  // least four steps
+  int64_t s = 256 / (mt256 * qt);
   if (s > nsteps / 4) s = nsteps / 4;
   // more ranges mean more fp32 partial tiles to write and add; with very few tiles they still pay
   const int64_t cap = mt256 * qt <= 4 ? 32 : 16;
@@ -726,17 +727,17 @@ int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps) {
 GuPlan gate_up_plan(int MT256, int64_t ffn, int64_t r, int ncu) {
   GuPlan g;
   const int NT = (int)(ffn / 256);
-  // the most row tiles per XCD whose strips (256 x 2r bf16 each) fit in half of its 4 MiB L2
+  // XCD grid: ngm row groups x 8 / ngm column groups, mx = MT256 / ngm row tiles per XCD.  The fewest row groups (most
+  // row tiles per XCD, fewest XCDs streaming the same weight columns) whose strips (256 x 2r bf16 per row tile) fit in
+  // half of an XCD's 4 MiB L2; if none fits, the most row groups that divide the tiles; plain order if nothing divides.
   g.mx = 0;
   g.ngm = 0;
   const long long strip = 256LL * 2 * r * 2;
-  for (int m = 8; m >= 1; m /= 2) {
-    if (MT256 % m || m * strip > (2LL << 20)) continue;
-    const int gr = MT256 / m;
-    if (gr > 8 || 8 % gr || NT % (8 / gr)) continue;
-    g.mx = m;
+  for (int gr = 1; gr <= 8; gr *= 2) {
+    if (MT256 % gr || NT % (8 / gr)) continue;
+    g.mx = MT256 / gr;
     g.ngm = gr;
-    break;
+    if ((long long)g.mx * strip <= (2LL << 20)) break;
   }
   if (ncu <= 0) ncu = 256;
   g.ntiles = MT256 * NT;
