@@ -797,20 +797,27 @@ int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st) {
 
 // ncols = rank columns of the product (2 r gated, r linear); r_strip = columns per strip of T.
 // 0: k_s1 does the first stage; 1: k_in over the whole contraction; S > 1: k_in with the contraction cut into S ranges.
+// The choice is by estimated time, from measured figures: a round of k_s1 (one 128 x 128 tile per CU) over a
+// contraction of 4096 takes 45 us, a round of k_in (256 x 256) over 2048 takes 50 us (four times the work in 2.2 times
+// the time, which is why it is preferred when its tiles fill the chip); a cut contraction adds a launch (5 us) and
+// the fp32 tiles of every range, written and read back once at about 5 TB/s.
 int in_splits(int64_t M, int64_t d, int64_t ncols) {
   M = (M + 255) / 256 * 256;   // the answer depends on the number of row tiles only (the workspace is sized from it)
   // 32-bit byte offsets into X
   if (ncols % 256 || d % 64 || M * d * 2 >= (int64_t(1) << 32)) return 0;
-  const int64_t tiles = ((M + 255) / 256) * (ncols / 256), rounds = (tiles + 255) / 256;
-  // 256 x 256 tiles must keep at least 70 % of the 256 CUs busy over their rounds (k_s1 with its 128 x 128 tiles
-  // reaches about 0.63 of this kernel's rate and fills the chip at any size)
-  if (tiles * 10 >= rounds * 256 * 7) return 1;
-  // Few tiles: ranges of the contraction fill the chip instead, at the price of writing and re-reading fp32 tiles
-  // (8 S bytes per element of T against 2 d / S contraction steps' worth of MFMAs): only for long ranges.
-  int64_t S = 256 / tiles;
-  if (S > 8) S = 8;
-  while (S > 1 && d / S < 2048) --S;
-  return S > 1 && tiles * S * 10 >= 256 * 7 ? (int)S : 0;
+  const int64_t wgs1 = (M / 128) * (ncols / 128);
+  const int64_t S1 = s1_splits(M / 128, ncols / 128, d);
+  auto cut_cost = [&](int64_t S) { return S > 1 ? 5.0 + (double)S * M * ncols * 8.0 / 5.0e6 : 0.0; };
+  const double t_s1 = (double)((wgs1 * S1 + 255) / 256) * 45.0 * ((double)d / S1) / 4096.0 + cut_cost(S1);
+  const int64_t tiles = (M / 256) * (ncols / 256);
+  int best = 0;
+  double best_t = t_s1;
+  for (int64_t S = 1; S <= 8; ++S) {
+    if (d / S < 512) break;   // at least eight steps per range
+    const double t = (double)((tiles * S + 255) / 256) * 50.0 * ((double)d / S) / 2048.0 + cut_cost(S);
+    if (t < best_t) { best_t = t; best = (int)S; }
+  }
+  return best;
 }
 bool in_supported(int64_t M, int64_t d, int64_t ncols) { return in_splits(M, d, ncols) >= 1; }
 int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_strip, hipStream_t st) {
