@@ -340,6 +340,20 @@ def test_workload_prefill_sampled_rows(r):
     assert relfro(Y, ref) <= WORKLOAD_FRO_TOL, relfro(Y, ref)
 
 
+@pytest.mark.parametrize("M", [200, 1100, 3000, 5000, 16384])
+def test_workload_prefill_extents_other_row_counts_sampled_rows(M):
+    """d=4096 ffn=14336 r=512 at row counts off the benchmark's: few rows (leftover rounds as half tiles, many
+    contraction ranges), ragged last tiles, row counts that are no multiple of the chip's tile rounds, and a large
+    one (first stage on 256 x 256 tiles).  The oracle evaluates rows at the tile borders and the last rows."""
+    gi = synth.make_workload("prefill", M=M, r=512)
+    rows = sorted({r for r in (0, 1, 31, 32, 127, 128, 255, 256, 1023, 1024, 2999, 4095, 4096, 4999, 8191, 8192, 12345,
+                               M - 257, M - 129, M - 33, M - 2, M - 1) if 0 <= r < M})
+    Y, ref, path = run_gated(gi, rows=rows)
+    assert path == 5
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+    assert relfro(Y, ref) <= WORKLOAD_FRO_TOL, relfro(Y, ref)
+
+
 def test_workload_prefill_fused_variant_sampled_rows():
     """The same workload with the gated activation kept in registers (one fused kernel, path 2)."""
     gi = synth.make_workload("prefill", r=512)
