@@ -160,7 +160,7 @@ def bench_decode_rotating(dev, M, steps, warmup, nsets=12, flags=0):
     f = {k: v.to(dev) for k, v in gi.factors().items()}
     for i in range(nsets):
         # the same values in every set; only the addresses (hence the cache lines) differ
-        ctxs.append(B.SvdMlp(max_M=16, keep_factors=False, flags=flags, **f))
+        ctxs.append(B.SvdMlp(max_M=max(16, M), keep_factors=False, flags=flags, **f))
     del f
     n = [0]
 

@@ -221,11 +221,15 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
       const int t1 = (int)(2 * p.r / 32), t2 = (int)(p.ffn / 32), t4 = (int)(p.rd / 32), t5 = (int)(p.d / 32);
       if (stream_uses_tile16(M, p.d, p.ffn, p.r, p.rd))   // the two split phases on 16-column tiles
         put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tile=16 tiles=%d ranges=%d] k_stream_d2[tiles=%d]"
-            " k_stream_d4[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d]", rt, 2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t2,
-            2 * t4, stream_splits16(2 * t4, (int)(p.ffn / 32), stream_tiles16(M)), t5);
-      else
-        put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tiles=%d ranges=%d] k_stream_d2[tiles=%d] k_stream_d4[tiles=%d ranges=%d]"
-            " k_stream_d5[tiles=%d]", rt, t1, stream_splits(t1, (int)(p.d / 16), rt), t2, t4, stream_splits(t4, (int)(p.ffn / 16), rt), t5);
+            " k_stream_d4[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt, 2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t2,
+            2 * t4, stream_splits16(2 * t4, (int)(p.ffn / 32), stream_tiles16(M)), t5, stream_row_groups_whole(rt, t5));
+      else {
+        const int g1 = stream_row_groups(rt, t1, (int)(p.d / 16)), g4 = stream_row_groups(rt, t4, (int)(p.ffn / 16));
+        put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tiles=%d row_groups=%d ranges=%d] k_stream_d2[tiles=%d]"
+            " k_stream_d4[tiles=%d row_groups=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt, t1, g1,
+            stream_splits(t1 * g1, (int)(p.d / 16), rt / g1), t2, t4, g4, stream_splits(t4 * g4, (int)(p.ffn / 16), rt / g4), t5,
+            stream_row_groups_whole(rt, t5));
+      }
       if ((p.flags & SVDMLP_FLAG_STREAM_ONE_KERNEL) && M <= 32) put(" (one persistent kernel, path=4, if the device and the extents allow)");
     } else if (staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED)) {
       put("path=5 bf16-tiled-staged:");

@@ -14,6 +14,7 @@
 // bit-reproducible.  Products are computed transposed (lane = activation row), so each output tile is
 // already the chain-order frag the next product consumes.
 #include "common.h"
+#include <type_traits>
 
 namespace svdmlp {
 
@@ -32,6 +33,7 @@ struct StreamArgs {
   int r;                // D1: rank (separates gate tiles from up tiles)
   int kb_major;         // weight frag order (1 for Ud)
   int act_rt, out_rt;   // frags between consecutive 32-row tiles of the activation / of the output
+  int rtw;              // k_stream: groups of RT row tiles, each group with workgroups of its own (the batch has rtw RT row tiles)
 };
 
 template <int PH, int RT>
@@ -50,8 +52,17 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
   // staging of accumulator tiles: [tile][wave][registers 4 p .. 4 p + 3][lane], 16 bytes per lane
   __shared__ f32x4 red[NB][SW][4][64];
   __shared__ int s_last;
-  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
-  const int tile = blockIdx.x / a.S, sp = blockIdx.x % a.S;
+  // the wave index as a scalar: the contraction loop below then has wave-uniform bounds
+  const int lane = threadIdx.x % 64, w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+  // Workgroups b, b + 8, .. b + 8 (rtw - 1) run on the same XCD and take the rtw row-tile groups of one (tile, range):
+  // the first of them brings the weight frags into that XCD's L2, the others find them there.
+  // (Not for D2, which has more tiles than there are CUs at any batch size: rtw = 1 there, at compile time.)
+  constexpr bool GROUPS = PH != PH_D2;
+  const int idx = GROUPS ? (blockIdx.x / (8 * a.rtw)) * 8 + blockIdx.x % 8 : blockIdx.x;
+  if (GROUPS && idx >= a.tiles * a.S) return;
+  const int rt0 = GROUPS ? (blockIdx.x / 8) % a.rtw * RT : 0;   // first row tile of this workgroup
+  const int tile = idx / a.S, sp = idx % a.S;
+  const int unit = tile * a.rtw + rt0 / RT;               // output tile x row-tile group: owner of partials and ticket
   const int kbs = (a.KB + a.S - 1) / a.S;                 // contraction blocks of this workgroup
   const int kw = (kbs + SW - 1) / SW;                     // ... of each wave
   int k0 = sp * kbs + w * kw;
@@ -66,12 +77,12 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
   const uint16_t* xrow[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const int row = 32 * rt + il;
+    const int row = 32 * (rt0 + rt) + il;
     xrow[rt] = (PH == PH_D1) ? static_cast<const uint16_t*>(a.act) + (size_t)(row < a.M ? row : a.M - 1) * a.ldx + 8 * h : nullptr;
   }
   const char* af = static_cast<const char*>(a.act) + lane * 16;
   // wave t < 2 RT finishes registers 8 (t % 2) .. + 7 (= one chain-order frag) of row tile t / 2
-  const int t = threadIdx.x / 64;
+  const int t = w;
   const int rtf = t / 2, hf = t % 2;
   float v[NACC][8];
 
@@ -86,23 +97,40 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
         for (int e = 0; e < 16; ++e) acc[n][rt][e] = 0.f;
     const char* wa = (SEQ && pass == 1) ? wp1 : wp0;
     const int aoff = SEQ ? pass * a.KB : 0;
-#pragma unroll 4
-    for (int kb = k0; kb < k1; ++kb) {
-      const bf16x8 wv = *reinterpret_cast<const bf16x8*>(wa + (size_t)kb * wstride);
-      bf16x8 wu;
-      if (PH == PH_D2 && !SEQ) wu = *reinterpret_cast<const bf16x8*>(wp1 + (size_t)kb * FRAG_BYTES);
+    // U contraction blocks at a time: every load of the group (weights first: they come from HBM) is issued before
+    // the first MFMA, so a wave has U (2 U for D2) weight frags in flight instead of one.  The whole range of a wave
+    // is a handful of blocks; with one load in flight it was that many memory round trips long.
+    auto step = [&](auto uc, int kb) __attribute__((always_inline)) {
+      constexpr int U = decltype(uc)::value;
+      constexpr bool BOTH = PH == PH_D2 && !SEQ;
+      bf16x8 wv[U], wu[BOTH ? U : 1], av[U][RT], au[BOTH ? U : 1][RT];
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        bf16x8 av;
-        if (PH == PH_D1) av = *reinterpret_cast<const bf16x8*>(xrow[rt] + 16 * kb);
-        else av = *reinterpret_cast<const bf16x8*>(af + ((size_t)rt * a.act_rt + aoff + kb) * FRAG_BYTES);
-        acc[0][rt] = mfma32(wv, av, acc[0][rt]);
-        if (PH == PH_D2 && !SEQ) {
-          const bf16x8 au = *reinterpret_cast<const bf16x8*>(af + ((size_t)rt * a.act_rt + a.KB + kb) * FRAG_BYTES);
-          acc[NA - 1][rt] = mfma32(wu, au, acc[NA - 1][rt]);
-        }
+      for (int u = 0; u < U; ++u) {
+        wv[u] = *reinterpret_cast<const bf16x8*>(wa + (size_t)(kb + u) * wstride);
+        if (BOTH) wu[u] = *reinterpret_cast<const bf16x8*>(wp1 + (size_t)(kb + u) * FRAG_BYTES);
       }
-    }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          if (PH == PH_D1) av[u][rt] = *reinterpret_cast<const bf16x8*>(xrow[rt] + 16 * (kb + u));
+          else av[u][rt] = *reinterpret_cast<const bf16x8*>(af + ((size_t)(rt0 + rt) * a.act_rt + aoff + kb + u) * FRAG_BYTES);
+          if (BOTH) au[u][rt] = *reinterpret_cast<const bf16x8*>(af + ((size_t)(rt0 + rt) * a.act_rt + a.KB + kb + u) * FRAG_BYTES);
+        }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          acc[0][rt] = mfma32(wv[u], av[u][rt], acc[0][rt]);
+          if (BOTH) acc[NA - 1][rt] = mfma32(wu[u], au[u][rt], acc[NA - 1][rt]);
+        }
+    };
+    constexpr int UMAX = (RT * NA <= 2) ? 4 : 2;   // what the register budget (two workgroups per CU) allows
+    int kb = k0;
+    if (UMAX >= 4)
+      for (; kb + 4 <= k1; kb += 4) step(std::integral_constant<int, UMAX >= 4 ? 4 : 1>{}, kb);
+    for (; kb + 2 <= k1; kb += 2) step(std::integral_constant<int, 2>{}, kb);
+    if (kb < k1) step(std::integral_constant<int, 1>{}, kb);
 
     // ---- sum the 8 waves' partial tiles through LDS (fixed order) ----
 #pragma unroll
@@ -143,7 +171,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
     // so no cache write-back / invalidate (which a device-scope fence would cost every workgroup) is needed.
     // Ordering: each thread waits for its own stores to be acknowledged, the workgroup barrier collects
     // them, then one thread takes the ticket.
-    float* mine = a.part + ((size_t)tile * a.S + sp) * NT * 1024;
+    float* mine = a.part + ((size_t)unit * a.S + sp) * NT * 1024;
     const int eo = (8 * hf) * 64 + lane;
     if (t < 2 * RT) {
 #pragma unroll
@@ -156,7 +184,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
     wait_vmcnt<0>();
     __syncthreads();
     if (threadIdx.x == 0)
-      s_last = (__hip_atomic_fetch_add(&a.cnt[tile * TICKET_STRIDE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.S - 1);
+      s_last = (__hip_atomic_fetch_add(&a.cnt[unit * TICKET_STRIDE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.S - 1);
     __syncthreads();
     if (!s_last) return;
     if (t < 2 * RT) {
@@ -170,7 +198,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
 #pragma unroll
           for (int qq = 0; qq < 4; ++qq) {
             const int q = q0 + qq < a.S ? q0 + qq : a.S - 1;
-            const float* src = a.part + (((size_t)tile * a.S + q) * NT + n * RT + rtf) * 1024 + eo;
+            const float* src = a.part + (((size_t)unit * a.S + q) * NT + n * RT + rtf) * 1024 + eo;
 #pragma unroll
             for (int s = 0; s < 8; ++s) tmp[qq][s] = __hip_atomic_load(src + s * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
@@ -183,14 +211,14 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
         }
       }
     }
-    if (threadIdx.x == 0) __hip_atomic_store(&a.cnt[tile * TICKET_STRIDE], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next forward
+    if (threadIdx.x == 0) __hip_atomic_store(&a.cnt[unit * TICKET_STRIDE], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next forward
   }
   if (t >= 2 * RT) return;
 
   // ---- epilogue ----
   if (PH == PH_D5) {
     // lane = row m; slots s <-> columns 32 tile + 16 hf + 8 (s / 4) + 4 h + s % 4
-    const int row = 32 * rtf + il;
+    const int row = 32 * (rt0 + rtf) + il;
     if (row < a.M) {
       uint16_t* y = static_cast<uint16_t*>(a.out) + (size_t)row * a.ldx + 32 * tile + 16 * hf + 4 * h;
 #pragma unroll
@@ -214,7 +242,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
 #pragma unroll
     for (int s = 0; s < 8; ++s) o[s] = (__bf16)v[0][s];
   }
-  size_t frag = (size_t)rtf * a.out_rt;
+  size_t frag = (size_t)(rt0 + rtf) * a.out_rt;
   if (PH == PH_D1) {
     const int p0 = 32 * tile;
     const int which = p0 >= a.r ? 1 : 0;
@@ -245,7 +273,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   static_assert(MT == 1 || MT == 2 || MT == 4 || MT == 8, "up to four 32-row activation tiles");
   __shared__ f32x4 red[SW][MT][64];
   __shared__ int s_last;
-  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+  const int lane = threadIdx.x % 64, w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const int tile = blockIdx.x / a.S, sp = blockIdx.x % a.S;   // 16-column tile, contraction range
   const int KB2 = a.KB / 2;                                // contraction blocks of 32
   const int kbs = (KB2 + a.S - 1) / a.S;
@@ -273,18 +301,33 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   f32x4 acc[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-  for (int kb = k0; kb < k1; ++kb) {
-    const bf16x8 wv = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(2 * kb + fsel) * wstride);
+  // U contraction blocks at a time, every load of the group issued before the first MFMA (see k_stream)
+  auto step = [&](auto uc, int kb) __attribute__((always_inline)) {
+    constexpr int U = decltype(uc)::value;
+    bf16x8 wv[U], av[U][MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      bf16x8 av;
-      if (PH == PH_D1) av = *reinterpret_cast<const bf16x8*>(xrow[mt] + 32 * kb);
-      else  // row tile mt / 2, rows 16 (mt % 2) .. of it
-        av = *reinterpret_cast<const bf16x8*>(abase + ((size_t)(mt / 2) * a.act_rt + 2 * kb + fsel) * FRAG_BYTES + (mt % 2) * 256);
-      acc[mt] = mfma16(wv, av, acc[mt]);
-    }
-  }
+    for (int u = 0; u < U; ++u) wv[u] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(2 * (kb + u) + fsel) * wstride);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        if (PH == PH_D1) av[u][mt] = *reinterpret_cast<const bf16x8*>(xrow[mt] + 32 * (kb + u));
+        else  // row tile mt / 2, rows 16 (mt % 2) .. of it
+          av[u][mt] = *reinterpret_cast<const bf16x8*>(abase + ((size_t)(mt / 2) * a.act_rt + 2 * (kb + u) + fsel) * FRAG_BYTES + (mt % 2) * 256);
+      }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[mt] = mfma16(wv[u], av[u][mt], acc[mt]);
+  };
+  constexpr int UMAX = MT <= 2 ? 8 : MT == 4 ? 4 : 2;
+  int kb = k0;
+  if (UMAX >= 8)
+    for (; kb + 8 <= k1; kb += 8) step(std::integral_constant<int, UMAX >= 8 ? 8 : 1>{}, kb);
+  if (UMAX >= 4)
+    for (; kb + 4 <= k1; kb += 4) step(std::integral_constant<int, UMAX >= 4 ? 4 : 1>{}, kb);
+  for (; kb + 2 <= k1; kb += 2) step(std::integral_constant<int, 2>{}, kb);
+  if (kb < k1) step(std::integral_constant<int, 1>{}, kb);
   // lane (m = l % 16, g): acc[mt][e] = element (output column 4 g + e of the tile, row 16 mt + m)
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) red[w][mt][lane] = acc[mt];
@@ -395,6 +438,28 @@ bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd
   return M <= 64 && d % 32 == 0 && ffn % 32 == 0 && 2 * r / 16 <= 2048 && rd / 16 <= 2048;
 }
 
+// Row-tile groups of the two split phases (k_stream; `rt` row tiles in the batch, `tiles` 32-column tiles, KB
+// contraction blocks).  With all row tiles in one workgroup the weights are fetched once, but the workgroup that adds
+// the partial tiles reads ranges x rt of them through one CU's few requests in flight (mlp_small, 128 rows: 512 KiB
+// in the down projection).  Groups with workgroups of their own need fewer ranges to fill the chip and spread that
+// read-back; in exchange rtw workgroups (of one XCD) fetch the same weight frags, which occupies rtw times the
+// requests in flight chip-wide while they stream from HBM.  Measured at 128 rows: phases with 2 and 4 MB of weights
+// take 35-40 % less time with four groups, 8 MB 14 % less with two groups (more with four when the weights are in the
+// memory-side cache, less when they come from HBM), 15 MB 14 % more with two groups.
+int stream_row_groups(int rt, int tiles, int KB) {
+  const double weight_mb = (double)tiles * KB * FRAG_BYTES / 1.0e6;
+  int rtw = rt;
+  while (rtw > 1 && (weight_mb * (rtw - 1) > 13.5 || tiles * rtw > 2048)) rtw /= 2;
+  return rtw;
+}
+
+// ... of the last product, whose contraction is not split: groups only while there are fewer workgroups than CUs
+int stream_row_groups_whole(int rt, int tiles) {
+  int rtw = 1;
+  while (2 * rtw <= rt && 2 * rtw * tiles <= 256) rtw *= 2;
+  return rtw;
+}
+
 int stream_splits(int tiles, int KB, int rt) {
   int s = (256 + tiles - 1) / tiles;      // aim at one workgroup per CU
   int smax = KB / SW;                     // at least one contraction block per wave
@@ -407,8 +472,8 @@ int stream_splits(int tiles, int KB, int rt) {
 }
 
 template <int PH>
-static void launch_stream(int rt, const StreamArgs& a, hipStream_t st) {
-  const dim3 grid(a.tiles * a.S), block(SW * 64);
+static void launch_stream(int rt, const StreamArgs& a, hipStream_t st) {   // rt: row tiles per workgroup
+  const dim3 grid(PH == PH_D2 ? a.tiles * a.S : (a.tiles * a.S + 7) / 8 * 8 * a.rtw), block(SW * 64);
   if (rt == 1) hipLaunchKernelGGL((k_stream<PH, 1>), grid, block, 0, st, a);
   else if (rt == 2) hipLaunchKernelGGL((k_stream<PH, 2>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((k_stream<PH, 4>), grid, block, 0, st, a);
@@ -440,46 +505,49 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   StreamArgs a;
   // D1
   a = StreamArgs{ws + p.off_wU, nullptr, X, ws + p.off_T, part, cnt, (int)M, (int)(p.d / 16), (int)(2 * p.r / 32), 1,
-                 (int)p.d, (int)p.r, 0, 0, fT};
-  a.S = stream_splits(a.tiles, a.KB, rt);
-  if (a.tiles > 2048) return (int)hipErrorInvalidValue;
+                 (int)p.d, (int)p.r, 0, 0, fT, 1};
+  a.rtw = stream_row_groups(rt, a.tiles, a.KB);
+  a.S = stream_splits(a.tiles * a.rtw, a.KB, rt / a.rtw);
+  if (a.tiles * a.rtw > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 0, 0, st);
   if (t16) {
     a.tiles *= 2;
     a.S = stream_splits16(a.tiles, a.KB / 2, mt16);
     launch_stream16<PH_D1>(mt16, a, st);
   } else {
-    launch_stream<PH_D1>(rt, a, st);
+    launch_stream<PH_D1>(rt / a.rtw, a, st);
   }
   prof_mark(c, ps, 0, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D2 (never split over workgroups: its contraction is only r long)
   a = StreamArgs{ws + p.off_wVg, ws + p.off_wVu, ws + p.off_T, ws + p.off_H, part, cnt, (int)M, (int)(p.r / 16),
-                 (int)(p.ffn / 32), 1, 0, (int)p.r, 0, fT, fH};
+                 (int)(p.ffn / 32), 1, 0, (int)p.r, 0, fT, fH, 1};
   prof_mark(c, ps, 1, 0, st);
   launch_stream<PH_D2>(rt, a, st);
   prof_mark(c, ps, 1, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D4
   a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048 * TICKET_STRIDE, (int)M, (int)(p.ffn / 16),
-                 (int)(p.rd / 32), 1, 0, (int)p.r, 1, fH, fTd};
-  a.S = stream_splits(a.tiles, a.KB, rt);
-  if (a.tiles > 2048) return (int)hipErrorInvalidValue;
+                 (int)(p.rd / 32), 1, 0, (int)p.r, 1, fH, fTd, 1};
+  a.rtw = stream_row_groups(rt, a.tiles, a.KB);
+  a.S = stream_splits(a.tiles * a.rtw, a.KB, rt / a.rtw);
+  if (a.tiles * a.rtw > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 2, 0, st);
   if (t16) {
     a.tiles *= 2;
     a.S = stream_splits16(a.tiles, a.KB / 2, mt16);
     launch_stream16<PH_D4>(mt16, a, st);
   } else {
-    launch_stream<PH_D4>(rt, a, st);
+    launch_stream<PH_D4>(rt / a.rtw, a, st);
   }
   prof_mark(c, ps, 2, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D5
   a = StreamArgs{ws + p.off_wVd, nullptr, ws + p.off_Td, Y, part, cnt, (int)M, (int)(p.rd / 16), (int)(p.d / 32), 1,
-                 (int)p.d, (int)p.r, 0, fTd, 0};
+                 (int)p.d, (int)p.r, 0, fTd, 0, 1};
+  a.rtw = stream_row_groups_whole(rt, a.tiles);
   prof_mark(c, ps, 3, 0, st);
-  launch_stream<PH_D5>(rt, a, st);
+  launch_stream<PH_D5>(rt / a.rtw, a, st);
   prof_mark(c, ps, 3, 1, st);
   return (int)hipGetLastError();
 }

@@ -142,14 +142,22 @@ def test_describe_names_the_plan_of_every_baseline_config():
     # decode shape: one row tile, both split phases fill the chip
     s = B.svdmlp_describe(pre, 16)
     assert s.startswith("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=64 ranges=4] k_stream_d2[tiles=448]")
-    assert "k_stream_d4[tile=16 tiles=32 ranges=8] k_stream_d5[tiles=128]" in s
+    assert "k_stream_d4[tile=16 tiles=32 ranges=8] k_stream_d5[tiles=128 row_groups=1]" in s
     assert B.svdmlp_describe(pre, 32) == s
-    assert B.svdmlp_describe(pre, 33) == s.replace("row_tiles=1", "row_tiles=2")
-    assert "row_tiles=2" in B.svdmlp_describe(pre, 64) and "row_tiles=4" in B.svdmlp_describe(pre, 128)
+    # two row tiles: the last product (128 tiles) gives each its own workgroups
+    assert B.svdmlp_describe(pre, 33) == s.replace("row_tiles=1", "row_tiles=2").replace("d5[tiles=128 row_groups=1]", "d5[tiles=128 row_groups=2]")
+    assert "row_tiles=2" in B.svdmlp_describe(pre, 64)
+    # four row tiles: 8 MB of [Ug|Uu] are worth fetching twice to shorten the partial sums' read-back, 15 MB of Ud are not
+    s = B.svdmlp_describe(pre, 128)
+    assert s.startswith("path=3 bf16-streaming: row_tiles=4 k_stream_d1[tiles=32 row_groups=2 ranges=4] k_stream_d2[tiles=448]")
+    assert "k_stream_d4[tiles=16 row_groups=1 ranges=16] k_stream_d5[tiles=128 row_groups=2]" in s
     assert B.svdmlp_describe(pre, 129).startswith("path=5")
-    # config 2 (M = 128) streams; forced onto the tiled path it has one row tile
+    # config 2 (M = 128) streams, small factors: row-tile groups in every phase that has too few tiles;
+    # forced onto the tiled path it has one row tile
     small = desc(max_M=128, d=2048, ffn=8192, r=256, r_down=256)
-    assert B.svdmlp_describe(small, 128).startswith("path=3 bf16-streaming: row_tiles=4")
+    s = B.svdmlp_describe(small, 128)
+    assert s.startswith("path=3 bf16-streaming: row_tiles=4 k_stream_d1[tiles=16 row_groups=4 ranges=4] k_stream_d2[tiles=256]")
+    assert "k_stream_d4[tiles=8 row_groups=4 ranges=8] k_stream_d5[tiles=64 row_groups=4]" in s
     small.flags |= B.FLAG_FORCE_TILED
     # fewer tiles than half the CUs: every tile of k_gate_up as two 128-row halves
     assert "k_gate_up[tile=256x256 tiles=32 workgroups=32 full=0 halves=64" in B.svdmlp_describe(small, 128)
