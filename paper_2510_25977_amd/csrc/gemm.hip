@@ -8,9 +8,9 @@
 //   k_out       Y    = Td Vd                       256 rows x 256 columns per workgroup
 //
 // Why not keep H in registers: a workgroup that owns every rank column of its rows (so that H never has to be
-// stored) has room for only 128 rows, and then each byte brought into the CU feeds too few MFMAs.  A CU keeps a
-// bounded number of cache-line requests in flight (about 8 KiB), so what it can pull in per clock is that over the
-// average L2 latency: the operand bytes per MFMA decide the speed.  A 256 x 256 tile needs 16 KiB of operands per
+// stored) has room for only 128 rows, and then each byte brought into the CU feeds too few MFMAs.  A CU pulls
+// operands in at a bounded rate (measured: 44 B/clk from L2 at best, about 20 B/clk at these kernels' L2 miss rates,
+// where eight waves of MFMAs on a 256 x 256 tile take 32 B/clk): the operand bytes per MFMA decide the speed.  A 256 x 256 tile needs 16 KiB of operands per
 // 64 MFMAs, a quarter of what the 128-row fused tile needs per MFMA.  The price is one write and one read of H.
 //
 // Both kernels are one machine: eight waves, two per SIMD, 128 accumulator registers per lane; wave w owns rows

@@ -256,8 +256,8 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
 // ------------------------------------------------------------------------------------------------
 // D1 and D4: the same products on 16 x 16 x 32 MFMAs, one 16-column output tile per workgroup group.
 // These two phases split their contraction over workgroups, and what the split costs (the partial tile written
-// through, and above all the read-back of all S partial tiles by one workgroup, whose CU keeps only about 8 KiB of
-// requests in flight) goes with the tile size: a 16 x 16 fp32 tile is 1 KiB instead of 4 KiB, and twice as many
+// through, and above all the read-back of all S partial tiles by one workgroup, past its L2 and through one CU's
+// bounded fetch rate) goes with the tile size: a 16 x 16 fp32 tile is 1 KiB instead of 4 KiB, and twice as many
 // tiles need half as many ranges.  The weight frags are the same ones (32 rows x 16 k, lane-major): a 16-row
 // operand of contraction block pair (2 kb2, 2 kb2 + 1) is lanes 16 hn .. + 15 and 32 + 16 hn .. + 15 of those two
 // frags, i.e. four 256-byte runs per load; every cache line of a frag is still read by exactly one workgroup.
@@ -440,7 +440,7 @@ bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd
 
 // Row-tile groups of the two split phases (k_stream; `rt` row tiles in the batch, `tiles` 32-column tiles, KB
 // contraction blocks).  With all row tiles in one workgroup the weights are fetched once, but the workgroup that adds
-// the partial tiles reads ranges x rt of them through one CU's few requests in flight (mlp_small, 128 rows: 512 KiB
+// the partial tiles reads ranges x rt of them through one CU's bounded fetch rate (mlp_small, 128 rows: 512 KiB
 // in the down projection).  Groups with workgroups of their own need fewer ranges to fill the chip and spread that
 // read-back; in exchange rtw workgroups (of one XCD) fetch the same weight frags, which occupies rtw times the
 // requests in flight chip-wide while they stream from HBM.  Measured at 128 rows: phases with 2 and 4 MB of weights
