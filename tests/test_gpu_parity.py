@@ -354,6 +354,62 @@ def test_workload_prefill_extents_other_row_counts_sampled_rows(M):
     assert relfro(Y, ref) <= WORKLOAD_FRO_TOL, relfro(Y, ref)
 
 
+def test_prefill_extents_row_count_whose_activation_passes_4_gib():
+    """Maximum-size edge: 150093 rows at d=4096 ffn=14336 r=512.  The gated activation in the workspace is 4.3 GB and X
+    and Y are 1.2 GB each, so every byte offset that is formed from a row index must be a 64-bit one (and the first stage
+    must leave the kernel whose row offsets are 32-bit).  Rows of X are drawn from 8192 seeded rows through a fixed
+    scrambling of the row index, so a row fetched from a wrong place does not match; the oracle evaluates rows on both
+    sides of the 2^31 and 2^32 byte marks of the activation, and the ragged last rows."""
+    M = 150093
+    gi = synth.make_workload("prefill", M=8192, r=512)
+    d = dev()
+    src = torch.arange(M, dtype=torch.int64)
+    src = (src * 7919 + src // 8192 * 131) % 8192
+    Xs = gi.X.to(d)
+    X = Xs[src.to(d)].contiguous()
+    f = {k: v.to(d) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=M, **f)
+    Y = mlp(X)
+    torch.cuda.synchronize()
+    assert mlp.last_path == 5
+    per_row = 14336 * 2
+    rows = sorted({0, 1, 255, 256, 8191, 8192, 65535, 65536, (1 << 31) // per_row - 1, (1 << 31) // per_row, (1 << 31) // per_row + 300,
+                   (1 << 32) // per_row - 1, (1 << 32) // per_row, (1 << 32) // per_row + 1, 150015, 150016, M - 2, M - 1})
+    Yh = Y[torch.tensor(rows, device=d)].cpu().to(torch.float64).numpy()
+    mlp.close()
+    del Y, X
+    a = {k: synth.to_f64(v) for k, v in gi.factors().items()}
+    ref = oracle.gated(synth.to_f64(gi.X)[src[rows].numpy()], **a)
+    assert relmax(Yh, ref) <= BF16_TOL, relmax(Yh, ref)
+    assert relfro(Yh, ref) <= WORKLOAD_FRO_TOL, relfro(Yh, ref)
+
+
+def test_linear_layer_with_an_x_beyond_4_gib_takes_the_first_stage_with_64_bit_row_offsets():
+    """Maximum-size edge of the single factored layer: 270001 rows of d = 8192 (X is 4.4 GB).  The eight-wave first stage
+    forms its row offsets in 32 bits, so the planner must hand this to the other first-stage kernel; the oracle evaluates
+    rows on both sides of the 2^32 byte mark of X and the ragged last rows."""
+    M, d_, n, r = 270001, 8192, 1024, 512
+    li = synth.make_linear_gaussian(4096, d_, n, r, stream=47)
+    dv = dev()
+    src = torch.arange(M, dtype=torch.int64)
+    src = (src * 7919 + src // 4096 * 131) % 4096
+    X = li.X.to(dv)[src.to(dv)].contiguous()
+    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
+    names = kernel_names(mlp, X)
+    assert names[0] == "k_s1", names
+    O = mlp(X)
+    torch.cuda.synchronize()
+    assert mlp.last_path == 6
+    per_row = d_ * 2
+    rows = sorted({0, 1, 255, 256, 4095, 4096, (1 << 31) // per_row - 1, (1 << 31) // per_row, (1 << 32) // per_row - 1,
+                   (1 << 32) // per_row, (1 << 32) // per_row + 129, 269999, M - 1})
+    Oh = O[torch.tensor(rows, device=dv)].cpu().to(torch.float64).numpy()
+    mlp.close()
+    del O, X
+    ref = oracle.linear(synth.to_f64(li.X)[src[rows].numpy()], synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
+
+
 def test_workload_prefill_fused_variant_sampled_rows():
     """The same workload with the gated activation kept in registers (one fused kernel, path 2)."""
     gi = synth.make_workload("prefill", r=512)
