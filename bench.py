@@ -134,6 +134,13 @@ def bench_xuv(dev, M, steps, warmup, dense=True, shape=(8192, 4096, 16384)):
         out["naive_recompute"] = dict(ms_per_step=rms, blocks=nblk, B_N=B_N, flops=nblk * 2 * M * r * d + 2 * M * r * n,
                                       provider="this library's kernels, T recomputed for every block of B_N output columns "
                                                "(paper Alg. 1); timing only, every block multiplies by the same V block")
+        # Block-size comparison (the paper's Table 3 varies B_M on Trainium): the same layer with both products on
+        # 128 x 128 tiles; operand bytes a CU must pull in per MFMA halve from the 128- to the 256-row tile.
+        small = B.SvdMlp(max_M=M, Ug=U, Vg=V, kind=B.SVDMLP_LINEAR, keep_factors=False, flags=B.FLAG_TILE_128)
+        sms, _ = time_steps(lambda: small(X, O), max(5, steps // 3), max(3, warmup // 2))
+        small.close()
+        out["tile_rows"] = {"128": dict(ms_per_step=sms, operand_bytes_per_mfma=512),
+                            "256 (planner's choice at this M)": dict(ms_per_step=ms, operand_bytes_per_mfma=256)}
     mlp.close()
     return out
 
@@ -313,6 +320,7 @@ def main():
             out["unfused_baseline"]["speedup_of_this_library"] = x["unfused"]["ms_per_step"] / x["ms"]
             out["naive_recompute_baseline"] = x["naive_recompute"]
             out["naive_recompute_baseline"]["speedup_of_this_library"] = x["naive_recompute"]["ms_per_step"] / x["ms"]
+            out["tile_rows"] = x["tile_rows"]
         print(json.dumps(out))
         return
 

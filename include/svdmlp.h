@@ -70,8 +70,10 @@ enum {
   SVDMLP_FLAG_STREAM_ONE_KERNEL = 1u << 3,/* weight-streaming path as one kernel that works through a queue of tiles
                                            instead of four launches (used when M <= 32 and the extents fit its
                                            per-wave register budget); slower than the four launches as measured */
-  SVDMLP_FLAG_TILED_FUSED = 1u << 4     /* MFMA-tiled path: keep the gated activation in registers (one fused kernel)
+  SVDMLP_FLAG_TILED_FUSED = 1u << 4,    /* MFMA-tiled path: keep the gated activation in registers (one fused kernel)
                                            instead of staging it through the workspace */
+  SVDMLP_FLAG_TILE_128 = 1u << 5        /* kind LINEAR: both products on 128 x 128 tiles whatever the planner would pick
+                                           (the small-block point of a block-size comparison, paper Table 3) */
 };
 
 typedef struct {

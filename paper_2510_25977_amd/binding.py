@@ -22,7 +22,7 @@ SVDMLP_BF16, SVDMLP_F32 = 0, 1
 SVDMLP_GATED, SVDMLP_LINEAR = 0, 1
 SVDMLP_OK = 0
 SVDMLP_INVALID_ARGUMENT, SVDMLP_UNSUPPORTED, SVDMLP_WORKSPACE_TOO_SMALL, SVDMLP_HIP_ERROR, SVDMLP_NO_DEVICE = -1, -2, -3, -4, -5
-FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK, FLAG_STREAM_ONE_KERNEL, FLAG_TILED_FUSED = 1, 2, 4, 8, 16
+FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK, FLAG_STREAM_ONE_KERNEL, FLAG_TILED_FUSED, FLAG_TILE_128 = 1, 2, 4, 8, 16, 32
 
 EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_status_string",
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",

@@ -192,7 +192,7 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
   };
   const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
   auto first_stage = [&](int64_t ncols) {
-    const int S = in_splits(M, p.d, ncols);
+    const int S = linear_on_small_tiles(p) ? 0 : in_splits(M, p.d, ncols);
     if (S >= 1) {
       put(" k_in[tile=256x256 tiles=%d ranges=%d]", MT256 * (int)(ncols / 256), S);
       if (S > 1) put(" k_reduce");
@@ -207,7 +207,7 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
   } else if (p.kind == SVDMLP_LINEAR) {
     put("path=6 bf16-linear:");
     first_stage(p.r);
-    if (p.ffn % 256 == 0) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.ffn / 256));
+    if (p.ffn % 256 == 0 && !linear_on_small_tiles(p)) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.ffn / 256));
     else put(" k_s5[tile=128x128 tiles=%d]", MT128 * (int)(p.ffn / 128));
   } else {
     bool stream_path = M <= STREAM_MAX_M;

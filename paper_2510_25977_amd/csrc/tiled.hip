@@ -668,7 +668,7 @@ int launch_reduce(const Ctx* c, const float* part, char* out, int splits, int MT
 static int first_stage(const Ctx* c, const void* X, int64_t M, int64_t r_strip, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
-  if (in_supported(M, p.d, 2 * r_strip)) return launch_in(c, X, M, 2 * r_strip, r_strip, st);
+  if (!linear_on_small_tiles(p) && in_supported(M, p.d, 2 * r_strip)) return launch_in(c, X, M, 2 * r_strip, r_strip, st);
   const int MT128 = (int)((M + 127) / 128), PT = (int)(2 * r_strip / 128);
   const int S = s1_splits(MT128, PT, p.d);
   hipLaunchKernelGGL(k_s1, dim3(MT128 * PT * S), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
@@ -720,7 +720,9 @@ int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   char* ws = c->ws;
   const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
   const int PT = (int)(p.r / 128);
-  const char* const names[2] = {in_supported(M, p.d, p.r) ? "k_in" : "k_s1", p.ffn % 256 == 0 ? "k_out" : "k_s5"};
+  const bool small = linear_on_small_tiles(p);
+  const bool out256 = !small && p.ffn % 256 == 0;
+  const char* const names[2] = {!small && in_supported(M, p.d, p.r) ? "k_in" : "k_s1", out256 ? "k_out" : "k_s5"};
   const int ps = prof_open_forward(c, 2, names);
   int e;
   prof_mark(c, ps, 0, 0, st);
@@ -728,7 +730,7 @@ int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   prof_mark(c, ps, 0, 1, st);
   if (e) return e;
   prof_mark(c, ps, 1, 0, st);
-  if (p.ffn % 256 == 0) {
+  if (out256) {
     e = launch_out_generic(c, ws + p.off_T, ws + p.off_wVd, M, Y, MT256, p.ffn, p.r, st);
   } else {
     const int CT = (int)(p.ffn / 128);

@@ -174,6 +174,9 @@ def test_describe_names_the_plan_of_every_baseline_config():
     lin = desc(kind=B.SVDMLP_LINEAR, max_M=32768, d=8192, ffn=16384, r=4096, r_down=0)
     assert "k_in[tile=256x256 tiles=64 ranges=4] k_reduce k_out" in B.svdmlp_describe(lin, 1024)
     assert "k_in[tile=256x256 tiles=256 ranges=1] k_out[tile=256x256 tiles=1024]" in B.svdmlp_describe(lin, 4096)
+    # the small-block point of the block-size comparison: both products on 128 x 128 tiles on request
+    lin.flags |= B.FLAG_TILE_128
+    assert "k_s1[tile=128x128 tiles=1024 ranges=1] k_s5[tile=128x128 tiles=4096]" in B.svdmlp_describe(lin, 4096)
     f32 = desc(dtype=B.SVDMLP_F32, max_M=10, d=96, ffn=200, r=24, r_down=40)
     assert B.svdmlp_describe(f32, 10).startswith("path=1")
     # errors

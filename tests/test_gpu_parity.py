@@ -168,6 +168,26 @@ def kernel_names(mlp, X):
     return list(k)
 
 
+def test_bf16_linear_on_128_tiles_on_request():
+    """SVDMLP_FLAG_TILE_128: the same layer as above on k_s1 + k_s5 (the small-block point of the block-size
+    comparison); same parity bar, and bitwise reproducible."""
+    M, d, n, r = 3000, 4096, 4096, 4096
+    li = synth.make_linear_gaussian(M, d, n, r, stream=43)
+    dv = dev()
+    mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR, flags=B.FLAG_TILE_128)
+    X = li.X.to(dv)
+    assert kernel_names(mlp, X) == ["k_s1", "k_s5"]
+    O = mlp(X)
+    O2 = mlp(X)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2)
+    rows = list(range(0, M, 61)) + [M - 1]
+    Oh = O[rows].cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.linear(synth.to_f64(li.X)[rows], synth.to_f64(li.U), synth.to_f64(li.V))
+    assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
+
+
 def test_bf16_first_stage_cuts_a_long_contraction_when_tiles_are_few():
     """32 tiles (256 x 256) of T and d = 16384: the eight-wave first-stage kernel runs over eight ranges of d and
     k_reduce adds them (linear layer and gated MLP); ragged M; the oracle evaluates a sample of rows."""
