@@ -150,6 +150,14 @@ int svdmlp_profile_begin(svdmlp_ctx *ctx, int max_forwards);
 int svdmlp_profile_end(svdmlp_ctx *ctx, float *avg_ms, int *n_kernels, int *n_forwards);
 const char *svdmlp_profile_kernel_name(const svdmlp_ctx *ctx, int k);
 
+/* Host only: the rank that the paper's rule (Sec. 4.1, Eq. 5) gives a k x n weight matrix for a target compression
+ * ratio (the fraction of the k n parameters removed, 0 <= ratio < 1), snapped to a multiple of `block`:
+ *     r = floor( k n (1 - ratio) / ((k + n) block) + alpha ) * block,   at least one block
+ * (alpha = 0.5 rounds to the nearest block; the paper uses blocks that are a multiple of its tile size, here a
+ * multiple of 128 costs nothing, see the rank rounding above).  Returns -1 for non-positive extents or block, a ratio
+ * outside [0, 1) or alpha outside [0, 1]. */
+int64_t svdmlp_rank_for_ratio(int64_t k, int64_t n, double ratio, int64_t block, double alpha);
+
 /* ABI version of this header (bumped on any incompatible change). */
 int svdmlp_abi_version(void);
 

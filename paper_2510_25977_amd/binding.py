@@ -26,7 +26,7 @@ FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK, FLAG_STREAM_ONE_KERNE
 
 EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_status_string",
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
-           "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe"]
+           "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_last_path.argtypes = [ctypes.c_void_p]
         L.svdmlp_last_path.restype = ctypes.c_int
         L.svdmlp_abi_version.restype = ctypes.c_int
+        L.svdmlp_rank_for_ratio.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_double, ctypes.c_int64, ctypes.c_double]
+        L.svdmlp_rank_for_ratio.restype = ctypes.c_int64
         L.svdmlp_profile_begin.argtypes = [ctypes.c_void_p, ctypes.c_int]
         L.svdmlp_profile_begin.restype = ctypes.c_int
         L.svdmlp_profile_end.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int),
@@ -91,6 +93,13 @@ def status_string(status: int) -> str:
 
 def svdmlp_workspace_bytes(desc: svdmlp_desc) -> int:
     return int(lib().svdmlp_workspace_bytes(ctypes.byref(desc)))
+
+
+def svdmlp_rank_for_ratio(k: int, n: int, ratio: float, block: int = 128, alpha: float = 0.5) -> int:
+    r = lib().svdmlp_rank_for_ratio(int(k), int(n), float(ratio), int(block), float(alpha))
+    if r < 0:
+        raise SvdMlpError(SVDMLP_INVALID_ARGUMENT, "svdmlp_rank_for_ratio")
+    return int(r)
 
 
 def svdmlp_describe(desc: svdmlp_desc, M: int) -> str:

@@ -2,6 +2,7 @@
 // Host code only; every arithmetic step of the forward runs in the kernels of the other files.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -155,6 +156,14 @@ using namespace svdmlp;
 extern "C" {
 
 int svdmlp_abi_version(void) { return 1; }
+
+// Paper Eq. 5 (Sec. 4.1): block-aligned rank for a target compression ratio.
+int64_t svdmlp_rank_for_ratio(int64_t k, int64_t n, double ratio, int64_t block, double alpha) {
+  if (k <= 0 || n <= 0 || block <= 0 || !(ratio >= 0.0 && ratio < 1.0) || !(alpha >= 0.0 && alpha <= 1.0)) return -1;
+  const double blocks = std::floor((double)k * (double)n * (1.0 - ratio) / ((double)(k + n) * (double)block) + alpha);
+  const int64_t nb = blocks < 1.0 ? 1 : (int64_t)blocks;
+  return nb * block;
+}
 
 const char* svdmlp_status_string(int status) {
   switch (status) {

@@ -237,3 +237,21 @@ int main(void) {
                     "-L", str(libdir), "-lsvdmlp", f"-Wl,-rpath,{libdir}"], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(" ", 2)
     assert int(out[0]) == 1 and int(out[1]) > 0 and out[2].startswith("path=5 bf16-tiled-staged:")
+
+
+def test_rank_for_ratio_follows_the_rank_rule():
+    """svdmlp_rank_for_ratio (paper Eq. 5): hand-evaluated cases, the never-zero rule, argument checks, and agreement
+    with the Python cost model over a grid of layer shapes and ratios."""
+    from paper_2510_25977_amd import costmodel as cm
+    # 2048*8192*0.8/(10240*128) = 10.24 -> floor(10.74) = 10 blocks; 4096*14336*0.95/(18432*128) = 23.64 -> 24 blocks
+    assert B.svdmlp_rank_for_ratio(2048, 8192, 0.2, 128, 0.5) == 1280
+    assert B.svdmlp_rank_for_ratio(4096, 14336, 0.05, 128, 0.5) == 3072
+    assert B.svdmlp_rank_for_ratio(4096, 14336, 0.05, 128, 0.0) == 23 * 128      # alpha = 0: round down
+    assert B.svdmlp_rank_for_ratio(64, 64, 0.99, 128, 0.5) == 128                # at least one block
+    for k, n in [(2048, 8192), (4096, 14336), (5120, 27648), (7168, 18432), (48, 80)]:
+        for ratio in (0.0, 0.1, 0.2, 0.35, 0.5, 0.8, 0.95):
+            for block in (8, 128, 256):
+                assert B.svdmlp_rank_for_ratio(k, n, ratio, block, 0.5) == cm.block_aligned_rank(k, n, ratio, block)
+    for bad in [(0, 8, 0.1, 128, 0.5), (8, -1, 0.1, 128, 0.5), (8, 8, 1.0, 128, 0.5), (8, 8, -0.1, 128, 0.5), (8, 8, 0.1, 0, 0.5),
+                (8, 8, 0.1, 128, 1.5), (8, 8, float("nan"), 128, 0.5)]:
+        assert B.lib().svdmlp_rank_for_ratio(*bad) == -1
