@@ -703,3 +703,30 @@ def test_one_kernel_decode_successive_forwards_with_different_inputs():
     torch.cuda.synchronize()
     fresh.close()
     assert torch.equal(Y, outs[1]) and torch.equal(Y, outs[5])
+
+
+def test_contexts_on_two_streams_run_concurrently_without_interference():
+    """Two contexts (a streaming-path one and a tiled-path one), each with its own workspace, enqueue forwards on two
+    streams at the same time; every output equals, bit for bit, what the same context gives when it runs alone."""
+    dv = dev()
+    ga = synth.make_gated(24, 512, 1408, 192, 256, stream=71)
+    gb = synth.make_gated(700, 512, 1024, 192, 256, stream=72)
+    A = B.SvdMlp(max_M=24, **{k: v.to(dv) for k, v in ga.factors().items()})
+    Bc = B.SvdMlp(max_M=700, **{k: v.to(dv) for k, v in gb.factors().items()})
+    Xa, Xb = ga.X.to(dv), gb.X.to(dv)
+    Ya0, Yb0 = A(Xa).clone(), Bc(Xb).clone()
+    torch.cuda.synchronize()
+    assert A.last_path == 3 and Bc.last_path == 5
+    sa, sb = torch.cuda.Stream(device=dv), torch.cuda.Stream(device=dv)
+    Ya = [torch.empty_like(Ya0) for _ in range(8)]
+    Yb = [torch.empty_like(Yb0) for _ in range(8)]
+    torch.cuda.synchronize()
+    for i in range(8):
+        A.forward(Xa, Ya[i], stream=sa)
+        Bc.forward(Xb, Yb[i], stream=sb)
+    sa.synchronize()
+    sb.synchronize()
+    for i in range(8):
+        assert torch.equal(Ya[i], Ya0) and torch.equal(Yb[i], Yb0), i
+    A.close()
+    Bc.close()
