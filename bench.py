@@ -37,7 +37,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per forward of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
 # scaled by a plain copy of known size (profiles/prefill_r512_pmc_traffic_mfma.txt); key = (kernel, M, d, ffn, r)
 MEASURED_TRAFFIC = {
-    ("k_gate_up", 4096, 4096, 14336, 512): {"read_MB": 184.9, "written_MB": 117.4, "algorithmic_read_MB": 37.7,
+    ("k_gate_up", 4096, 4096, 14336, 512): {"read_MB": 181.3, "written_MB": 117.5, "algorithmic_read_MB": 37.7,
                                             "algorithmic_written_MB": 117.4,
                                             "source": "profiles/prefill_r512_pmc_traffic_mfma.txt"},
     ("k_stream_d2", 16, 4096, 14336, 512): {"read_MB": 29.95, "written_MB": 0.92, "algorithmic_read_MB": 29.38,

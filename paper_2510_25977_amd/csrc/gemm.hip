@@ -29,6 +29,7 @@
 // phase 2s+1; its copies were waited for before the barrier that opens phase 2s, and its slot is
 // written again by copies issued in phase 2s+4 or later.
 #include "common.h"
+#include <type_traits>
 
 namespace svdmlp {
 
@@ -249,19 +250,29 @@ __device__ __forceinline__ unsigned mul_pair(unsigned sp, float p0, float p1) {
 // ------------------------------------------------------------------------------------------------
 // Tiles of one workgroup of k_gate_up.  ntiles = G q + rem tiles go to G workgroups.  If at most half of the
 // workgroups would get a tile in the last round, the rem leftover tiles are cut into upper and lower halves
-// (128 rows each) and given to 2 rem workgroups of a second launch (HALF): the last round then costs about half a
-// tile's time instead of a whole one.  Full launch: workgroup b takes tiles b, b + G, ... below `ntiles`.
-// Half launch: workgroup b takes one half of one of the tiles first .. first + rem - 1.
-template <bool HALF>
+// (128 rows each) and given to 2 rem workgroups: the last round then costs about half a tile's time instead of a
+// whole one.  MODE 0 (full tiles only): workgroup b takes tiles b, b + G, ... below `ntiles`.  MODE 1 (halves only):
+// workgroup b takes one half of one of the tiles first .. first + rem - 1.  MODE 2 (both in one launch, so that the
+// copy stream runs on from the last full tile into the half and no second launch ramps up): the full tiles below
+// `first`, then, for the first 2 rem workgroups, a half as in MODE 1.
+enum { GU_FULL = 0, GU_HALF = 1, GU_MIXED = 2 };
+template <int MODE>
 struct GuSched {
   int b, G, ntiles, first, rem;
   __device__ __forceinline__ void init(int b_, int G_, int ntiles_, int first_, int rem_) {
     b = b_; G = G_; ntiles = ntiles_; first = first_; rem = rem_;
   }
-  __device__ __forceinline__ int count() const { return HALF ? 1 : (b < ntiles ? (ntiles - 1 - b) / G + 1 : 0); }
+  // full tiles of this workgroup (MODE 2: those below `first`)
+  __device__ __forceinline__ int nfull() const {
+    const int n = MODE == GU_MIXED ? first : ntiles;
+    return MODE == GU_HALF ? 0 : (b < n ? (n - 1 - b) / G + 1 : 0);
+  }
+  __device__ __forceinline__ int count() const {
+    return MODE == GU_HALF ? 1 : MODE == GU_FULL ? nfull() : nfull() + (b < 2 * rem ? 1 : 0);
+  }
   // k-th tile of this workgroup: id, and hh = -1 for a full tile, 0 / 1 for the upper / lower half
   __device__ __forceinline__ void tile(int k, int& id, int& hh) const {
-    if (!HALF) {
+    if (MODE == GU_FULL || (MODE == GU_MIXED && k < nfull())) {
       id = b + k * G;
       hh = -1;
     } else if (rem % 8 == 0) {  // both halves of a tile on one XCD, the one its id maps to
@@ -296,11 +307,11 @@ __device__ __forceinline__ GuTile gu_tile(int id, int hh, int w, const char* T, 
 }
 
 // producer of k_gate_up: walks gate units, up units, then the next tile of this workgroup
-template <bool HALF>
+template <int MODE>
 struct GuProd {
   GProd prod;
   GuTile pt;
-  GuSched<HALF> sched;
+  GuSched<MODE> sched;
   const char* T;
   const char* wVg;
   const char* wVu;
@@ -330,7 +341,7 @@ struct GuProd {
   }
 };
 
-template <bool HALF>
+template <int MODE>
 __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ T, const char* __restrict__ wVg,
                                                        const char* __restrict__ wVu, char* __restrict__ H, int KB, int KBf,
                                                        int MT, int NT, int mx, int ngm, int ntiles, int first, int rem) {
@@ -342,7 +353,7 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
   const long long strip = (long long)KB * FRAG_BYTES;
 
   // producer: position in the stream
-  GuProd<HALF> gp;
+  GuProd<MODE> gp;
   GProd& prod = gp.prod;
   gp.sched.init(blockIdx.x, gridDim.x, ntiles, first, rem);
   const int my_tiles = gp.sched.count();
@@ -379,34 +390,20 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
 
   f32x16 acc[2][4];
   u32x4 S[16];  // SiLU(G) as bf16 pairs, frag by frag, while the up tile is accumulated
-  for (int k = 0; k < my_tiles; ++k) {
-    int id, hh, mt, nt;
-    gp.sched.tile(k, id, hh);
-    g_tile_of(id, MT, NT, mx, ngm, mt, nt);
-    // One tile: gate phase, SiLU, up phase, H out.  HALF: 128 rows; wave (wm, wn) then owns rows 64 wm.. of the half.
+  // One tile: gate phase, SiLU, up phase, H out.  HALF: 128 rows; wave (wm, wn) then owns rows 64 wm.. of the half.
+  auto one_tile = [&](auto half_c, int mt, int nt, int hh) __attribute__((always_inline)) {
+    constexpr bool HALF = decltype(half_c)::value;
     char* hbase = H + ((((long long)mt * KBf + 2 * (8 * nt + 2 * wn)) * 8) + (HALF ? 4 * hh + 2 * wm : 4 * wm)) * FRAG_BYTES;
     constexpr int NB = HALF ? 2 : 4;
-    // ---- gate phase ----
-    for (int i = 0; i < half; ++i) {
+    // One step: memory phase (copies of a later step, LDS reads, the SiLU when it is due), compute phase.  FIRST: the
+    // accumulators start from zero with this step.  The first step of each phase is written out apart from the loop
+    // over the others (no run-time choice between the two kinds of compute phase inside a loop).
+    auto step = [&](auto first_c, auto silu_c) __attribute__((always_inline)) {
+      constexpr bool FIRST = decltype(first_c)::value, SILU = decltype(silu_c)::value;
       gp.produce();
       if (HALF) cons.fetch_half();
       else cons.fetch();
-      g_certify(gp.prod, cons);
-      if (HALF) {
-        if (i == 0) cons.compute_half<true>(acc);
-        else cons.compute_half<false>(acc);
-      } else {
-        if (i == 0) cons.compute<true>(acc);
-        else cons.compute<false>(acc);
-      }
-      lds_barrier();
-    }
-    // ---- up phase ----
-    for (int i = 0; i < half; ++i) {
-      gp.produce();
-      if (HALF) cons.fetch_half();
-      else cons.fetch();
-      if (i == 0) {  // SiLU(G), rounded to bf16 pairs; runs under the other wave's compute phase
+      if (SILU) {  // SiLU(G), rounded to bf16 pairs; runs under the other wave's compute phase
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -421,15 +418,18 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
             }
       }
       g_certify(gp.prod, cons);
-      if (HALF) {
-        if (i == 0) cons.compute_half<true>(acc);
-        else cons.compute_half<false>(acc);
-      } else {
-        if (i == 0) cons.compute<true>(acc);
-        else cons.compute<false>(acc);
-      }
+      if (HALF) cons.template compute_half<FIRST>(acc);
+      else cons.template compute<FIRST>(acc);
       lds_barrier();
-    }
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    // ---- gate phase ----
+    step(T_{}, F_{});
+    for (int i = 1; i < half; ++i) step(F_{}, F_{});
+    // ---- up phase ----
+    step(T_{}, T_{});
+    for (int i = 1; i < half; ++i) step(F_{}, F_{});
     // H = SiLU(G) .* P rounded to bf16: registers 8t..8t+7 of tile (a, b) are the frag of ffn contraction block
     // 2 (ffn tile) + t, row tile b.  The stores are left in flight; the next tile's first phases run under them.
 #pragma unroll
@@ -443,6 +443,19 @@ __global__ __launch_bounds__(G_THREADS) void k_gate_up(const char* __restrict__ 
           for (int e = 0; e < 4; ++e) v[e] = mul_pair(v[e], acc[a][b][8 * t2 + 2 * e], acc[a][b][8 * t2 + 2 * e + 1]);
           store16_sv_nt(hbase + ((long long)(2 * a + t2) * 8 + b) * FRAG_BYTES, gp.prod.lane16, v);
         }
+  };
+  for (int k = 0; k < my_tiles; ++k) {
+    int id, hh, mt, nt;
+    gp.sched.tile(k, id, hh);
+    g_tile_of(id, MT, NT, mx, ngm, mt, nt);
+    if constexpr (MODE == GU_FULL) {
+      one_tile(std::false_type{}, mt, nt, hh);
+    } else if constexpr (MODE == GU_HALF) {
+      one_tile(std::true_type{}, mt, nt, hh);
+    } else {
+      if (hh < 0) one_tile(std::false_type{}, mt, nt, hh);
+      else one_tile(std::true_type{}, mt, nt, hh);
+    }
   }
   if (w < 4) lds_barrier();  // matches the extra barrier of waves 4..7
 }
@@ -759,15 +772,15 @@ int launch_gate_up(const Ctx* c, int MT256, hipStream_t st) {
   char* ws = c->ws;
   const int NT = (int)(p.ffn / 256);
   const GuPlan g = gate_up_plan(MT256, p.ffn, p.r, c->n_cus);
-  int e = 0;
-  if (g.nfull > 0) {
-    hipLaunchKernelGGL(k_gate_up<false>, dim3(g.G), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
+  if (!g.halves)
+    hipLaunchKernelGGL(k_gate_up<GU_FULL>, dim3(g.G), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
                        ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.nfull, 0, 0);
-    e = (int)hipGetLastError();
-  }
-  if (e || !g.halves) return e;
-  hipLaunchKernelGGL(k_gate_up<true>, dim3(2 * g.rem), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
-                     ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.ntiles, g.nfull, g.rem);
+  else if (g.nfull == 0)
+    hipLaunchKernelGGL(k_gate_up<GU_HALF>, dim3(2 * g.rem), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
+                       ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.ntiles, g.nfull, g.rem);
+  else   // whole rounds of full tiles, then the leftover tiles as halves, in one launch (2 rem <= G)
+    hipLaunchKernelGGL(k_gate_up<GU_MIXED>, dim3(g.G), dim3(G_THREADS), 0, st, ws + p.off_T, ws + p.off_wVg, ws + p.off_wVu,
+                       ws + p.off_Hfull, (int)(p.r / 16), (int)(p.ffn / 16), MT256, NT, g.mx, g.ngm, g.ntiles, g.nfull, g.rem);
   return (int)hipGetLastError();
 }
 
