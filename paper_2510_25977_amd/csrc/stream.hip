@@ -267,10 +267,10 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int PH, int MT>   // MT = 16-row tiles of the batch (M <= 16 MT)
+template <int PH, int MT>   // MT = 16-row tiles of the batch (M <= 16 MT <= 32)
 __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   static_assert(PH == PH_D1 || PH == PH_D4, "only the phases that split their contraction over workgroups");
-  static_assert(MT == 1 || MT == 2 || MT == 4 || MT == 8, "up to four 32-row activation tiles");
+  static_assert(MT == 1 || MT == 2, "one 32-row activation tile");
   __shared__ f32x4 red[SW][MT][64];
   __shared__ int s_last;
   const int lane = threadIdx.x % 64, w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
@@ -431,11 +431,12 @@ int stream_splits16(int tiles, int KB2, int mt) {
   return s;
 }
 // 16-row tiles k_stream16 pads a batch to
-int stream_tiles16(int64_t M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8; }
+int stream_tiles16(int64_t M) { return M <= 16 ? 1 : 2; }
 // whether the two split phases of a forward of M rows run on 16-column tiles
 bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd) {
-  // beyond 64 rows the activation frags, re-read for every 16-column weight tile, cost more than the smaller partials save
-  return M <= 64 && d % 32 == 0 && ffn % 32 == 0 && 2 * r / 16 <= 2048 && rd / 16 <= 2048;
+  // beyond 32 rows the activation frags, re-read for every 16-column weight tile, cost more than the smaller partials
+  // save (the 32-column tiles with row-tile groups of their own measure faster there)
+  return M <= 32 && d % 32 == 0 && ffn % 32 == 0 && 2 * r / 16 <= 2048 && rd / 16 <= 2048;
 }
 
 // Row-tile groups of the two split phases (k_stream; `rt` row tiles in the batch, `tiles` 32-column tiles, KB
@@ -443,13 +444,14 @@ bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd
 // the partial tiles reads ranges x rt of them through one CU's bounded fetch rate (mlp_small, 128 rows: 512 KiB
 // in the down projection).  Groups with workgroups of their own need fewer ranges to fill the chip and spread that
 // read-back; in exchange rtw workgroups (of one XCD) fetch the same weight frags, which occupies rtw times the
-// requests in flight chip-wide while they stream from HBM.  Measured at 128 rows: phases with 2 and 4 MB of weights
-// take 35-40 % less time with four groups, 8 MB 14 % less with two groups (more with four when the weights are in the
-// memory-side cache, less when they come from HBM), 15 MB 14 % more with two groups.
+// requests in flight chip-wide while they stream from HBM.  Measured: at 128 rows phases with 2 and 4 MB of weights
+// take 35-40 % less time with four groups, 8 MB 25 % less with four groups, 15 MB 10 % less with two (and no less with
+// four when the weights come from HBM); at 64 rows two groups on these 32-column tiles beat the 16-column tiles of
+// k_stream16 (whose workgroups re-read twice the activation bytes) by 2.3 us (D1, 8 MB) and 2.5 us (D4, 15 MB).
 int stream_row_groups(int rt, int tiles, int KB) {
   const double weight_mb = (double)tiles * KB * FRAG_BYTES / 1.0e6;
   int rtw = rt;
-  while (rtw > 1 && (weight_mb * (rtw - 1) > 13.5 || tiles * rtw > 2048)) rtw /= 2;
+  while (rtw > 1 && (weight_mb * (rtw - 1) > 30.0 || tiles * rtw > 2048)) rtw /= 2;
   return rtw;
 }
 
@@ -483,9 +485,7 @@ template <int PH>
 static void launch_stream16(int mt, const StreamArgs& a, hipStream_t st) {
   const dim3 grid(a.tiles * a.S), block(SW * 64);
   if (mt == 1) hipLaunchKernelGGL((k_stream16<PH, 1>), grid, block, 0, st, a);
-  else if (mt == 2) hipLaunchKernelGGL((k_stream16<PH, 2>), grid, block, 0, st, a);
-  else if (mt == 4) hipLaunchKernelGGL((k_stream16<PH, 4>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((k_stream16<PH, 8>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((k_stream16<PH, 2>), grid, block, 0, st, a);
 }
 
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {

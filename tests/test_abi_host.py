@@ -144,13 +144,15 @@ def test_describe_names_the_plan_of_every_baseline_config():
     assert s.startswith("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=64 ranges=4] k_stream_d2[tiles=448]")
     assert "k_stream_d4[tile=16 tiles=32 ranges=8] k_stream_d5[tiles=128 row_groups=1]" in s
     assert B.svdmlp_describe(pre, 32) == s
-    # two row tiles: the last product (128 tiles) gives each its own workgroups
-    assert B.svdmlp_describe(pre, 33) == s.replace("row_tiles=1", "row_tiles=2").replace("d5[tiles=128 row_groups=1]", "d5[tiles=128 row_groups=2]")
-    assert "row_tiles=2" in B.svdmlp_describe(pre, 64)
-    # four row tiles: 8 MB of [Ug|Uu] are worth fetching twice to shorten the partial sums' read-back, 15 MB of Ud are not
+    # two row tiles: 32-column tiles, each row tile with workgroups of its own in the two cut phases and in the last one
+    s = B.svdmlp_describe(pre, 33)
+    assert s.startswith("path=3 bf16-streaming: row_tiles=2 k_stream_d1[tiles=32 row_groups=2 ranges=4] k_stream_d2[tiles=448]")
+    assert "k_stream_d4[tiles=16 row_groups=2 ranges=8] k_stream_d5[tiles=128 row_groups=2]" in s
+    assert B.svdmlp_describe(pre, 64) == s
+    # four row tiles: 8 MB of [Ug|Uu] are worth fetching four times to shorten the partial sums' read-back, 15 MB of Ud twice
     s = B.svdmlp_describe(pre, 128)
-    assert s.startswith("path=3 bf16-streaming: row_tiles=4 k_stream_d1[tiles=32 row_groups=2 ranges=4] k_stream_d2[tiles=448]")
-    assert "k_stream_d4[tiles=16 row_groups=1 ranges=16] k_stream_d5[tiles=128 row_groups=2]" in s
+    assert s.startswith("path=3 bf16-streaming: row_tiles=4 k_stream_d1[tiles=32 row_groups=4 ranges=2] k_stream_d2[tiles=448]")
+    assert "k_stream_d4[tiles=16 row_groups=2 ranges=8] k_stream_d5[tiles=128 row_groups=2]" in s
     assert B.svdmlp_describe(pre, 129).startswith("path=5")
     # config 2 (M = 128) streams, small factors: row-tile groups in every phase that has too few tiles;
     # forced onto the tiled path it has one row tile
