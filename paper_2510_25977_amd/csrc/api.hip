@@ -97,7 +97,11 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   // of 64, at least 128; the down rank to a multiple of 256 for the staged variant (256-wide rank tiles), else to
   // what the fused one takes (a workgroup owns 4, 8 or 16 32-wide rank tiles, or groups of 16).
   const int64_t r = de->r <= 128 ? 128 : (de->r + 63) / 64 * 64;
-  const bool want_fused = (de->flags & SVDMLP_FLAG_TILED_FUSED) != 0;
+  // The fused variant is also the automatic choice when both ranks fit one 128-wide tile: the staged variant would run
+  // the down rank padded to 256, and with so little arithmetic per element of H its round trip through HBM is what
+  // bounds it (measured at d = 4096, ffn = 14336, r = r_down = 128: fused 9-16 % faster from 512 rows on, 3 % slower
+  // at 256 rows; from r = 192 on the staged variant is level or faster).
+  const bool want_fused = (de->flags & SVDMLP_FLAG_TILED_FUSED) != 0 || (de->r <= 128 && p->rd <= 128);
   int64_t rd = p->rd;
   if (want_fused) rd = rd <= 128 ? 128 : rd <= 256 ? 256 : (rd + 511) / 512 * 512;
   else rd = (rd + 255) / 256 * 256;

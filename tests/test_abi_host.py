@@ -170,8 +170,13 @@ def test_describe_names_the_plan_of_every_baseline_config():
     # fused variant on request, and for extents the staged one does not take
     pre.flags |= B.FLAG_TILED_FUSED
     assert B.svdmlp_describe(pre, 4096).startswith("path=2 bf16-tiled-fused:")
-    odd = desc(max_M=512, d=256, ffn=384, r=128, r_down=128)   # ffn and r_down run rounded up to 512 and 256
+    odd = desc(max_M=512, d=256, ffn=384, r=192, r_down=128)   # ffn and r_down run rounded up to 512 and 256
     assert B.svdmlp_describe(odd, 512).startswith("path=5")
+    # both ranks within one 128-wide tile: the fused variant by itself (the staged one would pad r_down to 256 and is
+    # bound by the round trip of the activation at so little arithmetic per element)
+    tiny = desc(max_M=4096, d=4096, ffn=14336, r=128, r_down=128)
+    assert B.svdmlp_describe(tiny, 4096).startswith("path=2 bf16-tiled-fused:")
+    assert "k_stream_d4[tile=16 tiles=8 " in B.svdmlp_describe(tiny, 16)      # the streaming path runs r_down = 128 unpadded
     # single factored layer at the paper's kernel-evaluation shape: the first stage cuts d when tiles are few
     lin = desc(kind=B.SVDMLP_LINEAR, max_M=32768, d=8192, ffn=16384, r=4096, r_down=0)
     assert "k_in[tile=256x256 tiles=64 ranges=4] k_reduce k_out" in B.svdmlp_describe(lin, 1024)

@@ -730,3 +730,16 @@ def test_contexts_on_two_streams_run_concurrently_without_interference():
         assert torch.equal(Ya[i], Ya0) and torch.equal(Yb[i], Yb0), i
     A.close()
     Bc.close()
+
+
+def test_small_ranks_take_the_fused_variant_by_themselves():
+    """r and r_down within one 128-wide tile: the planner picks the variant that keeps the gated activation in registers
+    (path 2) without the flag, and the streaming path runs the down rank unpadded; same parity bar."""
+    gi = synth.make_gated(700, 512, 1024, 100, 128, stream=73)
+    Y, ref, path = run_gated(gi)
+    assert path == 2
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+    assert relfro(Y, ref) <= 1.5e-2
+    Ys, refs, paths = run_gated(synth.make_gated(20, 512, 1024, 100, 128, stream=73))
+    assert paths == 3
+    assert relmax(Ys, refs) <= BF16_TOL, relmax(Ys, refs)
