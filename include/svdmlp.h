@@ -132,7 +132,8 @@ int svdmlp_describe(const svdmlp_desc *desc, int64_t M, char *buf, size_t buf_by
 int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
 
 /* Which path the last svdmlp_forward on this context took: 0 none yet, 1 fp32 debug,
- * 2 bf16 MFMA-tiled (prefill) with the gated activation kept in registers (SVDMLP_FLAG_TILED_FUSED),
+ * 2 bf16 MFMA-tiled (prefill) with the gated activation kept in registers (SVDMLP_FLAG_TILED_FUSED, or chosen by the
+ * library when r and r_down are both at most 128),
  * 3 bf16 weight-streaming (decode; the default for M <= 128) as four launches, 4 bf16 weight-streaming as one persistent kernel (SVDMLP_FLAG_STREAM_ONE_KERNEL), 5 bf16
  * MFMA-tiled with the gated activation staged through the workspace (the default for M > 128), 6 bf16 single
  * factored layer (SVDMLP_LINEAR). */
