@@ -743,3 +743,18 @@ def test_small_ranks_take_the_fused_variant_by_themselves():
     Ys, refs, paths = run_gated(synth.make_gated(20, 512, 1024, 100, 128, stream=73))
     assert paths == 3
     assert relmax(Ys, refs) <= BF16_TOL, relmax(Ys, refs)
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -10, 64.0])
+@pytest.mark.parametrize("M", [20, 300])
+def test_gate_in_its_linear_and_in_its_saturated_regime(M, scale):
+    """Inputs scaled by a power of two (exact in bf16): tiny gate pre-activations, where SiLU(g) ~ g / 2 and the output
+    is quadratic in the scale, and large ones, where SiLU(g) is g or 0 to rounding and exp2 of the negated gate
+    overflows or underflows inside the kernels.  Streaming and tiled path, same parity bar."""
+    gi = synth.make_gated(M, 512, 1408, 192, 256, stream=74)
+    gi.X = (gi.X.to(torch.float32) * scale).to(torch.bfloat16)
+    Y, ref, path = run_gated(gi)
+    assert path == (3 if M <= 128 else 5)
+    assert np.isfinite(Y).all()
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+    assert relfro(Y, ref) <= 1.5e-2
