@@ -81,3 +81,45 @@ def sqrt_sigma_factors(W, r: int):
     root = np.sqrt(s[:r])
     return u[:, :r] * root[None, :], root[:, None] * vt[:r, :], s
 
+
+
+# ----------------------------------------------------------------------------------------------
+# The MI355X counterpart of the paper's block-size model (Sec. 4.2.2, Eq. 10-11).  On Trainium the block height B_M
+# sets the arithmetic intensity against HBM and the SBUF footprint caps it; on a CDNA4 compute unit the tile shape sets
+# the operand bytes that must reach the CU per MFMA and the register file caps the tile.
+# ----------------------------------------------------------------------------------------------
+MFMA_ROWS, MFMA_COLS, MFMA_K = 32, 32, 16          # v_mfma_f32_32x32x16_bf16
+MFMA_CLK_PER_SIMD = 32                             # one such MFMA occupies a SIMD's matrix core for 32 clocks
+SIMDS_PER_CU = 4
+REGISTER_FILE_BYTES_PER_CU = 512 * 1024
+
+
+def tile_operand_bytes_per_mfma(tile_rows: int, tile_cols: int, s: int = 2) -> float:
+    """Operand bytes a workgroup must bring into its CU per MFMA for a tile_rows x tile_cols output tile: one
+    contraction block (16) needs (tile_rows + tile_cols) * 16 elements and feeds tile_rows/32 * tile_cols/32 MFMAs.
+    256 x 256: 256 B, 128 x 256: 384 B, 128 x 128: 512 B."""
+    return (tile_rows + tile_cols) * MFMA_K * s / ((tile_rows // MFMA_ROWS) * (tile_cols // MFMA_COLS))
+
+
+def tile_operand_rate_at_mfma_peak(tile_rows: int, tile_cols: int, s: int = 2) -> float:
+    """Bytes per clock a CU would have to fetch to keep its four matrix cores busy on such a tile
+    (256 x 256: 32 B/clk, 128 x 128: 64 B/clk)."""
+    return tile_operand_bytes_per_mfma(tile_rows, tile_cols, s) * SIMDS_PER_CU / MFMA_CLK_PER_SIMD
+
+
+def tile_mfma_fraction(tile_rows: int, tile_cols: int, fetch_bytes_per_clk: float, s: int = 2) -> float:
+    """Fraction of the MFMA rate a fetch-bound kernel reaches on such a tile when its CU pulls operands in at the
+    given rate (the counterpart of reading Eq. 10 against the machine balance): min(1, rate / rate needed)."""
+    return min(1.0, fetch_bytes_per_clk / tile_operand_rate_at_mfma_peak(tile_rows, tile_cols, s))
+
+
+def tile_accumulator_bytes(tile_rows: int, tile_cols: int) -> int:
+    """fp32 accumulators of the tile, spread over the CU's register file (the counterpart of Eq. 11's footprint)."""
+    return tile_rows * tile_cols * 4
+
+
+def tile_fits_register_file(tile_rows: int, tile_cols: int) -> bool:
+    """The accumulators of a tile may take at most half of the CU's register file: the eight waves that share the tile
+    need the other half for operand fragments, the squashed gate tile (16 bits per accumulator) and addresses.
+    256 x 256 fp32 (256 KiB) is the largest square tile that fits; 256 x 512 would fill the file with accumulators."""
+    return 2 * tile_accumulator_bytes(tile_rows, tile_cols) <= REGISTER_FILE_BYTES_PER_CU

@@ -70,3 +70,23 @@ def test_sqrt_sigma_factors_truncation_error_and_balance():
     U2, V2, _ = cm.sqrt_sigma_factors(W, r_rule)
     assert cm.compression_ratio(48, 80, r_rule) <= 0.55 and U2.shape[1] == r_rule
 
+
+
+def test_tile_model_of_the_compute_unit():
+    """The tile-shape model behind the kernels' block sizes (counterpart of the paper's Eq. 10-11 on a CDNA4 CU),
+    checked against the figures the design quotes and against rocprofv3 measurements of the default workload
+    (profiles/prefill_r512_pmc_traffic_mfma.txt): MFMA-busy fraction 0.31 for the 128 x 128 first stage and 0.53-0.54
+    for the 256 x 256 gate/up kernel at the operand rates measured there."""
+    assert cm.tile_operand_bytes_per_mfma(256, 256) == 256
+    assert cm.tile_operand_bytes_per_mfma(128, 256) == 384
+    assert cm.tile_operand_bytes_per_mfma(128, 128) == 512
+    assert cm.tile_operand_rate_at_mfma_peak(256, 256) == 32
+    assert cm.tile_operand_rate_at_mfma_peak(128, 128) == 64
+    # measured: k_s1 pulls ~20 B/clk per CU (4.325e6 requests x 128 B over 256 CUs x 1.06e5 clk) and is 0.308 MFMA-busy
+    assert abs(cm.tile_mfma_fraction(128, 128, 20.0) - 0.31) < 0.01
+    # measured: k_gate_up pulls 17-18 B/clk and is 0.53-0.54 MFMA-busy
+    assert 0.52 < cm.tile_mfma_fraction(256, 256, 17.5) < 0.56
+    assert cm.tile_mfma_fraction(256, 256, 44.0) == 1.0          # the copy rate from L2 alone would not bound it
+    # register file: 256 x 256 is the largest tile with two waves per SIMD; the paper's SBUF limit in this chip's terms
+    assert cm.tile_fits_register_file(256, 256) and not cm.tile_fits_register_file(256, 512)
+    assert cm.tile_accumulator_bytes(256, 256) == 256 * 1024
