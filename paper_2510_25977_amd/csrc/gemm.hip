@@ -733,6 +733,11 @@ int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps) {
   // more ranges mean more fp32 partial tiles to write and add; with very few tiles they still pay
   const int64_t cap = mt256 * qt <= 4 ? 32 : 16;
   if (s > cap) s = cap;
+  // One 256-wide rank tile (down rank up to 256): the kernel reads the whole activation for half the arithmetic and is
+  // bound by HBM bytes, a good part of them its own partial tiles.  Eight ranges are then enough as long as they
+  // still give 128 workgroups, which together can pull in what HBM delivers (r = r_down = 256, M = 4096: the forward
+  // 172 -> 163 us with 8 instead of 16 ranges; with fewer than 128 workgroups it loses).
+  if (qt == 1 && s > 8 && mt256 * 8 >= 128) s = 8;
   if (s < 1) s = 1;
   return (int)s;
 }
