@@ -156,10 +156,10 @@ def copy_calibration(dev, reps=5):
     return dict(bytes_read=n, bytes_written=n, launches=reps, kernel="torch Tensor.copy_ (uint8, 256 MiB)")
 
 
-def bench_decode_rotating(dev, M, steps, warmup, nsets=12, flags=0):
+def bench_decode_rotating(dev, M, steps, warmup, nsets=12, flags=0, r=None):
     """Decode shape measured cold to the 256 MB memory-side cache: rotate through `nsets` independent
     factor sets (one context each, > 2x the cache in total) so every forward streams its weights from HBM."""
-    gi = synth.make_workload("decode", M=M)
+    gi = synth.make_workload("decode", M=M, r=r)
     dims = gi.dims
     X = gi.X.to(dev)
     Y = torch.empty_like(X)
@@ -332,7 +332,7 @@ def main():
 
     dflags = B.FLAG_STREAM_ONE_KERNEL if args.one_kernel_decode else 0
     if args.workload == "decode":
-        dec = bench_decode_rotating(dev, M, args.steps, args.warmup, flags=dflags)
+        dec = bench_decode_rotating(dev, M, args.steps, args.warmup, flags=dflags, r=args.r)
         ms, wall_ms, kernels, path = dec["ms_per_step"], dec["ms_per_step"], dec["warm_kernels_ms"], (4 if dflags else 3)
     else:
         ms, wall_ms, kernels, path, ms_ev = bench_forward(gi, dev, args.steps, args.warmup,
