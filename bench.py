@@ -302,6 +302,7 @@ def main():
         k = x["kernels"]
         kfl = {"k_s1": 2 * x["M"] * x["d"] * x["r"], "k_in": 2 * x["M"] * x["d"] * x["r"], "k_out": 2 * x["M"] * x["r"] * x["n"],
                "k_s5": 2 * x["M"] * x["r"] * x["n"]}
+        kfl.update({"k_stream_d1": kfl["k_s1"], "k_stream_d5": kfl["k_out"]})
         kname = max((n_ for n_ in k if n_ in kfl), key=k.get)
         out = {"metric": METRIC, "value": x["flops"] / x["ms"] / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
                "warmup": args.warmup, "ms_per_step": x["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -313,6 +314,13 @@ def main():
                "roofline": {"bound": "mfma", "kernel": kname, "achieved": kfl[kname] / k[kname] / 1e9, "peak": PEAK_BF16_TFLOPS,
                             "unit": "TFLOP/s", "frac": kfl[kname] / k[kname] / 1e9 / PEAK_BF16_TFLOPS, "traffic": None,
                             "per_kernel_TFLOPs": {n_: kfl[n_] / v / 1e9 for n_, v in k.items() if v and n_ in kfl}}}
+        if x["path"] == 7:   # up to 128 rows: weight-streaming kernels, bound by the bytes of the factors
+            kb = {"k_stream_d1": 2 * x["d"] * x["r"], "k_stream_d5": 2 * x["r"] * x["n"]}
+            nbytes = 2 * x["r"] * (x["d"] + x["n"]) + 2 * x["M"] * (x["d"] + x["n"])
+            out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": kb[kname] / k[kname] / 1e6, "peak": PEAK_HBM_GBS,
+                               "unit": "GB/s", "frac": kb[kname] / k[kname] / 1e6 / PEAK_HBM_GBS, "traffic": None,
+                               "whole_forward_GBps": nbytes / x["ms"] / 1e6,
+                               "note": "single factor set (warm in the memory-side cache if it fits); per-kernel time from HIP events"}
         if "dense" in x:
             out["dense_baseline"] = x["dense"]
             out["dense_baseline"]["speedup_of_factored"] = x["dense"]["ms_per_step"] / x["ms"]

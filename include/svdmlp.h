@@ -64,7 +64,7 @@ enum {
 
 /* Bits of svdmlp_desc.flags (testing and benchmarking aids; 0 = automatic choice). */
 enum {
-  SVDMLP_FLAG_FORCE_TILED = 1u << 0,    /* bf16: always take the MFMA-tiled (prefill) path */
+  SVDMLP_FLAG_FORCE_TILED = 1u << 0,    /* bf16: always take the MFMA-tiled (prefill) path (both kinds) */
   SVDMLP_FLAG_FORCE_STREAM = 1u << 1,   /* bf16: always take the weight-streaming (decode) path; needs M <= 128 */
   SVDMLP_FLAG_SKIP_ARCH_CHECK = 1u << 2,/* do not require gfx950 (host-only unit tests of argument handling) */
   SVDMLP_FLAG_STREAM_ONE_KERNEL = 1u << 3,/* weight-streaming path as one kernel that works through a queue of tiles
@@ -136,7 +136,7 @@ int svdmlp_last_hip_error(const svdmlp_ctx *ctx);
  * library when r and r_down are both at most 128),
  * 3 bf16 weight-streaming (decode; the default for M <= 128) as four launches, 4 bf16 weight-streaming as one persistent kernel (SVDMLP_FLAG_STREAM_ONE_KERNEL), 5 bf16
  * MFMA-tiled with the gated activation staged through the workspace (the default for M > 128), 6 bf16 single
- * factored layer (SVDMLP_LINEAR). */
+ * factored layer (SVDMLP_LINEAR) MFMA-tiled, 7 bf16 single factored layer weight-streaming (the default for M <= 128). */
 int svdmlp_last_path(const svdmlp_ctx *ctx);
 
 /* Per-kernel timing for benchmarks.  svdmlp_profile_begin creates a pool of HIP events for up to

@@ -84,6 +84,8 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
       if (si > 1 && si * mt * 256 > prow) prow = si * mt * 256;
     }
     p->off_Tdp = take((size_t)prow * r * 4);
+    p->off_part = take((size_t)8 << 20);              // streaming path: split-K partial tiles
+    p->off_cnt = take(CNT_BYTES);                     // ... and its tickets
     p->total_bytes = off;
     return SVDMLP_OK;
   }
@@ -217,6 +219,19 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
   };
   if (p.dtype == SVDMLP_F32) {
     put("path=1 fp32-debug:%s", p.kind == SVDMLP_GATED ? " k_f32_gemm x5 (SiLU-gate epilogue in the third)" : " k_f32_gemm x2");
+  } else if (p.kind == SVDMLP_LINEAR && ((linear_stream_pays(M, p.d, p.r, p.ffn) && !(p.flags & (SVDMLP_FLAG_FORCE_TILED | SVDMLP_FLAG_TILE_128))) ||
+                                         (p.flags & SVDMLP_FLAG_FORCE_STREAM))) {
+    if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+    const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;
+    const int t1 = (int)(p.r / 32), t5 = (int)(p.ffn / 32);
+    if (M <= 32 && p.d % 32 == 0 && p.r / 16 <= 2048)
+      put("path=7 bf16-linear-streaming: row_tiles=%d k_stream_d1[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt,
+          2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t5, stream_row_groups_whole(rt, t5));
+    else {
+      const int g1 = stream_row_groups(rt, t1, (int)(p.d / 16));
+      put("path=7 bf16-linear-streaming: row_tiles=%d k_stream_d1[tiles=%d row_groups=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt,
+          t1, g1, stream_splits(t1 * g1, (int)(p.d / 16), rt / g1), t5, stream_row_groups_whole(rt, t5));
+    }
   } else if (p.kind == SVDMLP_LINEAR) {
     put("path=6 bf16-linear:");
     first_stage(p.r);
@@ -321,8 +336,13 @@ int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip
     c->last_path = 1;
     e = f32_forward(c, X, M, Y, st);
   } else if (c->plan.kind == SVDMLP_LINEAR) {
-    c->last_path = 6;
-    e = bf16_linear_forward(c, X, M, Y, st);
+    bool stream_path = linear_stream_pays(M, c->plan.d, c->plan.r, c->plan.ffn) && !(c->plan.flags & (SVDMLP_FLAG_FORCE_TILED | SVDMLP_FLAG_TILE_128));
+    if (c->plan.flags & SVDMLP_FLAG_FORCE_STREAM) {
+      if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+      stream_path = true;
+    }
+    c->last_path = stream_path ? 7 : 6;
+    e = stream_path ? bf16_linear_stream_forward(c, X, M, Y, st) : bf16_linear_forward(c, X, M, Y, st);
   } else {
     bool stream_path = M <= STREAM_MAX_M;
     if (c->plan.flags & SVDMLP_FLAG_FORCE_TILED) stream_path = false;

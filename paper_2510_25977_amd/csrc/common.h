@@ -199,6 +199,8 @@ int stream_splits16(int tiles, int KB2, int mt);
 int stream_tiles16(int64_t M);
 bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd);   // rows the weight-streaming path takes (four 32-row tiles)
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
+int bf16_linear_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
+bool linear_stream_pays(int64_t M, int64_t d, int64_t r, int64_t n);
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 bool bf16_decode_supported(const Ctx* c, int64_t M);
 

@@ -55,7 +55,8 @@ int bf16_repack_all(const Ctx* c, hipStream_t st) {
     // U^T: rows p in [0, r), contraction over d, meets row-major X -> natural order; V^T: rows n in [0, ffn),
     // contraction over r, meets T produced by an MFMA -> chain order
     if ((e = repack(de.Ug, p.d, p.r_in, p.d, p.r, ws + p.off_wU, ORDER_NATURAL, TILE_MAJOR, 0, (int)(p.r / 32), st))) return e;
-    return repack(de.Vg, p.r_in, p.ffn, p.r, p.ffn, ws + p.off_wVd, ORDER_CHAIN, TILE_MAJOR, 0, (int)(p.ffn / 32), st);
+    if ((e = repack(de.Vg, p.r_in, p.ffn, p.r, p.ffn, ws + p.off_wVd, ORDER_CHAIN, TILE_MAJOR, 0, (int)(p.ffn / 32), st))) return e;
+    return (int)hipMemsetAsync(ws + p.off_cnt, 0, CNT_BYTES, st);   // tickets of the streaming path start at zero
   }
   // [Ug | Uu]^T: rows p in [0, 2r), contraction over d, meets X read from row-major memory -> natural order
   const int pt = (int)(2 * p.r / 32);

@@ -553,4 +553,54 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   return (int)hipGetLastError();
 }
 
+// Whether the single factored layer of M <= 128 rows streams: every workgroup of a phase re-reads the activation of
+// its rows from L2, (r / 32) d + (n / 32) r elements per row over the two phases; beyond about 0.5 GB of that the
+// MFMA-tiled kernels are faster (measured: d = 8192, r = 4096, n = 16384 at 96 / 128 rows 85 / 91 us against 79 us
+// tiled, at 64 rows 57 against 78 us; every smaller layer tried streams 1.3 - 3x faster up to 128 rows).
+bool linear_stream_pays(int64_t M, int64_t d, int64_t r, int64_t n) {
+  const int64_t rows = M <= 32 ? 32 : M <= 64 ? 64 : 128;
+  return M <= STREAM_MAX_M && (double)((r / 32) * d + (n / 32) * r) * (double)rows * 2.0 <= 512.0e6;
+}
+
+// Single factored layer O = (X U) V for up to 128 rows (paper Sec. 4.2.1 at decode sizes): the first and the last
+// phase of the path above back to back.  T = X U is phase D1 with one strip of r columns, O = T V is phase D5 with
+// the row length of O; U and V frags are the ones the tiled kernels of this kind read.
+int bf16_linear_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
+  const Plan& p = c->plan;
+  char* ws = c->ws;
+  int* cnt = reinterpret_cast<int*>(ws + p.off_cnt + CNT_ONE_KERNEL_BYTES);
+  float* part = reinterpret_cast<float*>(ws + p.off_part);
+  if (M > STREAM_MAX_M) return (int)hipErrorInvalidValue;
+  const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;
+  const bool t16 = M <= 32 && p.d % 32 == 0 && p.r / 16 <= 2048;
+  const int mt16 = stream_tiles16(M);
+  static const char* const names[2] = {"k_stream_d1", "k_stream_d5"};
+  const int ps = prof_open_forward(c, 2, names);
+  const int fT = (int)(p.r / 16);   // frags of T per 32-row tile
+  int e;
+  StreamArgs a;
+  a = StreamArgs{ws + p.off_wU, nullptr, X, ws + p.off_T, part, cnt, (int)M, (int)(p.d / 16), (int)(p.r / 32), 1,
+                 (int)p.d, (int)p.r, 0, 0, fT, 1};
+  a.rtw = stream_row_groups(rt, a.tiles, a.KB);
+  a.S = stream_splits(a.tiles * a.rtw, a.KB, rt / a.rtw);
+  if (a.tiles * a.rtw > 2048) return (int)hipErrorInvalidValue;
+  prof_mark(c, ps, 0, 0, st);
+  if (t16) {
+    a.tiles *= 2;
+    a.S = stream_splits16(a.tiles, a.KB / 2, mt16);
+    launch_stream16<PH_D1>(mt16, a, st);
+  } else {
+    launch_stream<PH_D1>(rt / a.rtw, a, st);
+  }
+  prof_mark(c, ps, 0, 1, st);
+  if ((e = (int)hipGetLastError())) return e;
+  a = StreamArgs{ws + p.off_wVd, nullptr, ws + p.off_T, Y, part, cnt, (int)M, (int)(p.r / 16), (int)(p.ffn / 32), 1,
+                 (int)p.ffn, (int)p.r, 0, fT, 0, 1};
+  a.rtw = stream_row_groups_whole(rt, a.tiles);
+  prof_mark(c, ps, 1, 0, st);
+  launch_stream<PH_D5>(rt / a.rtw, a, st);
+  prof_mark(c, ps, 1, 1, st);
+  return (int)hipGetLastError();
+}
+
 }  // namespace svdmlp

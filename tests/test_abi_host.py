@@ -71,9 +71,11 @@ def test_workspace_bytes_formula(lib):
     assert B.svdmlp_workspace_bytes(d32) >= 4 * 10 * (48 + 200 + 40)
     dl = desc(dtype=B.SVDMLP_F32, kind=B.SVDMLP_LINEAR, max_M=32, d=256, ffn=1024, r=16, r_down=0)
     assert 0 < B.svdmlp_workspace_bytes(dl) <= 4 * 32 * 16 + 256
-    # bf16 LINEAR: re-tiled U and V + the rank-r strip of 256-row-padded M
+    # bf16 LINEAR: re-tiled U and V + the rank-r strip of 256-row-padded M, the partial tiles of the first stage when it
+    # cuts d (none at these extents), and the streaming path's 8 MiB of partial tiles and its ticket lines
     db = desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=1024, r=256, r_down=0)
-    assert B.svdmlp_workspace_bytes(db) == 2 * (256 * 512 + 1024 * 256 + 512 * 256)
+    tickets = 32768 + 3 * 256 * 128 + 2 * 2048 * 128
+    assert B.svdmlp_workspace_bytes(db) == 2 * (256 * 512 + 1024 * 256 + 512 * 256) + (8 << 20) + tickets
 
 
 @pytest.mark.parametrize("kw,status", [
@@ -181,6 +183,11 @@ def test_describe_names_the_plan_of_every_baseline_config():
     lin = desc(kind=B.SVDMLP_LINEAR, max_M=32768, d=8192, ffn=16384, r=4096, r_down=0)
     assert "k_in[tile=256x256 tiles=64 ranges=4] k_reduce k_out" in B.svdmlp_describe(lin, 1024)
     assert "k_in[tile=256x256 tiles=256 ranges=1] k_out[tile=256x256 tiles=1024]" in B.svdmlp_describe(lin, 4096)
+    # up to 128 rows the layer streams its weights (phases D1 and D5 of the streaming path), unless re-reading the
+    # activation for every weight tile would cost more than the tiles (this shape beyond 64 rows)
+    assert B.svdmlp_describe(lin, 16).startswith("path=7 bf16-linear-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=256 ranges=1] k_stream_d5[tiles=512")
+    assert B.svdmlp_describe(lin, 64).startswith("path=7") and B.svdmlp_describe(lin, 65).startswith("path=6")
+    assert B.svdmlp_describe(desc(kind=B.SVDMLP_LINEAR, max_M=128, d=4096, ffn=4096, r=1024, r_down=0), 128).startswith("path=7")
     # the small-block point of the block-size comparison: both products on 128 x 128 tiles on request
     lin.flags |= B.FLAG_TILE_128
     assert "k_s1[tile=128x128 tiles=1024 ranges=1] k_s5[tile=128x128 tiles=4096]" in B.svdmlp_describe(lin, 4096)

@@ -123,7 +123,7 @@ def test_bf16_linear_small(M, d, n, r):
     mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
     O = mlp(li.X.to(dv))
     torch.cuda.synchronize()
-    assert mlp.last_path == 6 and tuple(O.shape) == (M, n)
+    assert mlp.last_path == (7 if M <= 128 else 6) and tuple(O.shape) == (M, n)
     Oh = O.cpu().to(torch.float64).numpy()
     mlp.close()
     ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
@@ -599,7 +599,7 @@ def test_bf16_linear_random_supported_extents(M, d, n, r):
     mlp = B.SvdMlp(max_M=M, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
     O = mlp(li.X.to(dv))
     torch.cuda.synchronize()
-    assert mlp.last_path == 6
+    assert mlp.last_path == (7 if M <= 128 else 6)
     Oh = O.cpu().to(torch.float64).numpy()
     mlp.close()
     ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
@@ -758,3 +758,63 @@ def test_gate_in_its_linear_and_in_its_saturated_regime(M, scale):
     assert np.isfinite(Y).all()
     assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
     assert relfro(Y, ref) <= 1.5e-2
+
+
+@pytest.mark.parametrize("M", [1, 16, 32, 33, 64, 100, 128])
+@pytest.mark.parametrize("d,n,r", [(256, 512, 128), (512, 1408 - 128, 200), (1024, 4096, 512)])
+def test_bf16_linear_streaming_small_batches(M, d, n, r):
+    """O = (X U) V for up to 128 rows on the weight-streaming kernels (path 7) against the oracle's plain chain, and
+    against the MFMA-tiled path of the same context family (forced), which rounds at the same two places."""
+    li = synth.make_linear_gaussian(M, d, n, r, stream=81)
+    dv = dev()
+    U, V, X = li.U.to(dv), li.V.to(dv), li.X.to(dv)
+    mlp = B.SvdMlp(max_M=128, Ug=U, Vg=V, kind=B.SVDMLP_LINEAR)
+    O = mlp(X)
+    O2 = mlp(X)
+    torch.cuda.synchronize()
+    assert mlp.last_path == 7 and tuple(O.shape) == (M, n)
+    assert torch.equal(O, O2)                                  # fixed-order sums: bit-reproducible
+    mlp.close()
+    ref = oracle.linear(synth.to_f64(li.X), synth.to_f64(li.U), synth.to_f64(li.V))
+    Oh = O.cpu().to(torch.float64).numpy()
+    assert relmax(Oh, ref) <= BF16_TOL, (relmax(Oh, ref), relfro(Oh, ref))
+    assert relfro(Oh, ref) <= 1.5e-2
+    tiled = B.SvdMlp(max_M=128, Ug=U, Vg=V, kind=B.SVDMLP_LINEAR, flags=B.FLAG_FORCE_TILED)
+    Ot = tiled(X)
+    torch.cuda.synchronize()
+    assert tiled.last_path == 6
+    tiled.close()
+    assert relmax(Ot.cpu().to(torch.float64).numpy(), ref) <= BF16_TOL
+
+
+def test_bf16_linear_streaming_can_be_captured_and_matches_describe():
+    """Path 7 under stream capture (replayed three times with eager work in between), and the kernels svdmlp_describe
+    names are the ones that run."""
+    li = synth.make_linear_gaussian(20, 512, 1024, 256, stream=82)
+    dv = dev()
+    mlp = B.SvdMlp(max_M=64, Ug=li.U.to(dv), Vg=li.V.to(dv), kind=B.SVDMLP_LINEAR)
+    X = li.X.to(dv)
+    assert kernel_names(mlp, X) == ["k_stream_d1", "k_stream_d5"]
+    assert B.svdmlp_describe(mlp.desc, 20).startswith("path=7 bf16-linear-streaming: row_tiles=1 k_stream_d1[tile=16")
+    eager = mlp(X).clone()
+    torch.cuda.synchronize()
+    O = torch.empty_like(eager)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        mlp(X, O)
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        mlp(X, O)
+    for i in range(3):
+        O.fill_(3.0)
+        other = mlp((X * 0.5).contiguous())      # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, eager), i
+        assert not torch.equal(other, eager)
+    del g
+    mlp.close()
