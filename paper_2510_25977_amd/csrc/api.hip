@@ -235,7 +235,7 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
   } else if (p.kind == SVDMLP_LINEAR) {
     put("path=6 bf16-linear:");
     first_stage(p.r);
-    if (p.ffn % 256 == 0 && !linear_on_small_tiles(p)) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.ffn / 256));
+    if (linear_out_uses_256(M, p.ffn) && !linear_on_small_tiles(p)) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.ffn / 256));
     else put(" k_s5[tile=128x128 tiles=%d]", MT128 * (int)(p.ffn / 128));
   } else {
     bool stream_path = M <= STREAM_MAX_M;

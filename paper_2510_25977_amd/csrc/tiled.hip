@@ -721,7 +721,7 @@ int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
   const int PT = (int)(p.r / 128);
   const bool small = linear_on_small_tiles(p);
-  const bool out256 = !small && p.ffn % 256 == 0;
+  const bool out256 = !small && linear_out_uses_256(M, p.ffn);
   const char* const names[2] = {!small && in_supported(M, p.d, p.r) ? "k_in" : "k_s1", out256 ? "k_out" : "k_s5"};
   const int ps = prof_open_forward(c, 2, names);
   int e;
