@@ -171,13 +171,12 @@ GuPlan gate_up_plan(int MT256, int64_t ffn, int64_t r, int ncu);
 int launch_gate_up(const Ctx* c, int MT256, hipStream_t st);
 int launch_down1(const Ctx* c, int MT256, int splits, hipStream_t st);
 int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st);
-// whether the last product of the gated forward runs on k_out (256 x 256 tiles) rather than k_s5 (128 x 128): the wide
-// tile needs d % 256 == 0 and enough rows to give it tiles (up to 1024 rows the small one measures faster)
-inline bool out_uses_256(int64_t M, int64_t d) { return d % 256 == 0 && M > 1024; }
-// ... of the single factored layer (row length n): the wide tile once it has more than 64 tiles, a quarter of the CUs
-// (measured at n = 4096, 14336, 16384: below that the 128 x 128 kernel's four times as many workgroups are 10-30 %
-// faster, at 112-128 tiles the two are level, beyond the wide tile wins)
-inline bool linear_out_uses_256(int64_t M, int64_t n) { return n % 256 == 0 && ((M + 255) / 256) * (n / 256) > 64; }
+// Whether a last product with rows of length n (Y = Td Vd of the gated forward, O = T V of the single layer) runs on
+// k_out (256 x 256 tiles) rather than k_s5 (128 x 128): the wide tile needs n % 256 == 0 and more than 64 tiles, a
+// quarter of the CUs (measured at n = 2048 .. 16384: below that the small kernel's four times as many workgroups
+// are up to 30 % faster, at 112-128 tiles the two are level, beyond the wide tile wins).
+inline bool out_uses_256(int64_t M, int64_t n) { return n % 256 == 0 && ((M + 255) / 256) * (n / 256) > 64; }
+inline bool linear_out_uses_256(int64_t M, int64_t n) { return out_uses_256(M, n); }
 // kind LINEAR with SVDMLP_FLAG_TILE_128: k_s1 and k_s5 whatever the row count
 inline bool linear_on_small_tiles(const Plan& p) { return p.kind == SVDMLP_LINEAR && (p.flags & SVDMLP_FLAG_TILE_128) != 0; }
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
