@@ -734,10 +734,14 @@ int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps) {
   const int64_t cap = mt256 * qt <= 4 ? 32 : 16;
   if (s > cap) s = cap;
   // One 256-wide rank tile (down rank up to 256): the kernel reads the whole activation for half the arithmetic and is
-  // bound by HBM bytes, a good part of them its own partial tiles.  Eight ranges are then enough as long as they
-  // still give 128 workgroups, which together can pull in what HBM delivers (r = r_down = 256, M = 4096: the forward
+  // bound by HBM bytes, a good part of them its own partial tiles.  Then as few ranges as still give 128 workgroups
+  // (which together can pull in what HBM delivers), but not fewer than eight (r = r_down = 256, M = 4096: the forward
   // 172 -> 163 us with 8 instead of 16 ranges; with fewer than 128 workgroups it loses).
-  if (qt == 1 && s > 8 && mt256 * 8 >= 128) s = 8;
+  if (qt == 1) {
+    int64_t need = (128 + mt256 - 1) / mt256;
+    if (need < 8) need = 8;
+    if (s > need) s = need;
+  }
   if (s < 1) s = 1;
   return (int)s;
 }
