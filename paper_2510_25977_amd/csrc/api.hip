@@ -228,7 +228,7 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
       put("path=7 bf16-linear-streaming: row_tiles=%d k_stream_d1[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt,
           2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t5, stream_row_groups_whole(rt, t5));
     else {
-      const int g1 = stream_row_groups(rt, t1, (int)(p.d / 16));
+      const int g1 = stream_row_groups(rt, t1, (int)(p.d / 16), true);
       put("path=7 bf16-linear-streaming: row_tiles=%d k_stream_d1[tiles=%d row_groups=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt,
           t1, g1, stream_splits(t1 * g1, (int)(p.d / 16), rt / g1), t5, stream_row_groups_whole(rt, t5));
     }
@@ -252,7 +252,7 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
             " k_stream_d4[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt, 2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t2,
             2 * t4, stream_splits16(2 * t4, (int)(p.ffn / 32), stream_tiles16(M)), t5, stream_row_groups_whole(rt, t5));
       else {
-        const int g1 = stream_row_groups(rt, t1, (int)(p.d / 16)), g4 = stream_row_groups(rt, t4, (int)(p.ffn / 16));
+        const int g1 = stream_row_groups(rt, t1, (int)(p.d / 16), true), g4 = stream_row_groups(rt, t4, (int)(p.ffn / 16), false);
         put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tiles=%d row_groups=%d ranges=%d] k_stream_d2[tiles=%d]"
             " k_stream_d4[tiles=%d row_groups=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt, t1, g1,
             stream_splits(t1 * g1, (int)(p.d / 16), rt / g1), t2, t4, g4, stream_splits(t4 * g4, (int)(p.ffn / 16), rt / g4), t5,

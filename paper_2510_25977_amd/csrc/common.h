@@ -196,7 +196,7 @@ constexpr size_t CNT_BYTES = CNT_ONE_KERNEL_BYTES + 2 * 2048 * TICKET_STRIDE * 4
 constexpr int STREAM_MAX_M = 128;
 // workgroup-level contraction ranges of a streaming-path phase with `tiles` output tiles, KB contraction blocks, rt row tiles
 int stream_splits(int tiles, int KB, int rt);
-int stream_row_groups(int rt, int tiles, int KB);
+int stream_row_groups(int rt, int tiles, int KB, bool first);   // first: phase D1 (else D4)
 int stream_row_groups_whole(int rt, int tiles);
 int stream_splits16(int tiles, int KB2, int mt);
 int stream_tiles16(int64_t M);

@@ -449,10 +449,15 @@ bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd
 // take 35-40 % less time with four groups, 8 MB 25 % less with four groups, 15 MB 10 % less with two (and no less with
 // four when the weights come from HBM); at 64 rows two groups on these 32-column tiles beat the 16-column tiles of
 // k_stream16 (whose workgroups re-read twice the activation bytes) by 2.3 us (D1, 8 MB) and 2.5 us (D4, 15 MB).
-int stream_row_groups(int rt, int tiles, int KB) {
+int stream_row_groups(int rt, int tiles, int KB, bool first) {
   const double weight_mb = (double)tiles * KB * FRAG_BYTES / 1.0e6;
   int rtw = rt;
-  while (rtw > 1 && (weight_mb * (rtw - 1) > 30.0 || tiles * rtw > 2048)) rtw /= 2;
+  // the first phase (activation = the rows of X) takes more copies of a fetch than the down projection, whose
+  // workgroups also stream the ffn-wide activation: cold, every row tile on its own still pays with 17 MB of [Ug|Uu]
+  // (r = 1024, 128 rows: the forward 67.8 -> 65.4 us), two groups lose a little with 34 MB (r = 2048), and the down
+  // projection loses with four groups at 15 MB and 29 MB
+  const double lim = first && weight_mb <= 20.0 ? 1.0e9 : 30.0;
+  while (rtw > 1 && (weight_mb * (rtw - 1) > lim || tiles * rtw > 2048)) rtw /= 2;
   return rtw;
 }
 
@@ -507,7 +512,7 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   // D1
   a = StreamArgs{ws + p.off_wU, nullptr, X, ws + p.off_T, part, cnt, (int)M, (int)(p.d / 16), (int)(2 * p.r / 32), 1,
                  (int)p.d, (int)p.r, 0, 0, fT, 1};
-  a.rtw = stream_row_groups(rt, a.tiles, a.KB);
+  a.rtw = stream_row_groups(rt, a.tiles, a.KB, true);
   a.S = stream_splits(a.tiles * a.rtw, a.KB, rt / a.rtw);
   if (a.tiles * a.rtw > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 0, 0, st);
@@ -530,7 +535,7 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   // D4
   a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048 * TICKET_STRIDE, (int)M, (int)(p.ffn / 16),
                  (int)(p.rd / 32), 1, 0, (int)p.r, 1, fH, fTd, 1};
-  a.rtw = stream_row_groups(rt, a.tiles, a.KB);
+  a.rtw = stream_row_groups(rt, a.tiles, a.KB, false);
   a.S = stream_splits(a.tiles * a.rtw, a.KB, rt / a.rtw);
   if (a.tiles * a.rtw > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 2, 0, st);
@@ -581,7 +586,7 @@ int bf16_linear_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, 
   StreamArgs a;
   a = StreamArgs{ws + p.off_wU, nullptr, X, ws + p.off_T, part, cnt, (int)M, (int)(p.d / 16), (int)(p.r / 32), 1,
                  (int)p.d, (int)p.r, 0, 0, fT, 1};
-  a.rtw = stream_row_groups(rt, a.tiles, a.KB);
+  a.rtw = stream_row_groups(rt, a.tiles, a.KB, true);
   a.S = stream_splits(a.tiles * a.rtw, a.KB, rt / a.rtw);
   if (a.tiles * a.rtw > 2048) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 0, 0, st);
