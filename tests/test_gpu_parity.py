@@ -348,30 +348,71 @@ def test_workload_decode(M, one_kernel):
 SAMPLE_ROWS = [0, 1, 31, 32, 127, 128, 1000, 2047]
 
 
+def assert_every_row_tile(Y, ref, rows_per_tile=256):
+    """The stated bars over the whole output, and the Frobenius bar again for every row tile on its own (a tile that
+    the launch mapping skipped or computed from another tile's operands cannot hide in the average)."""
+    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
+    assert relfro(Y, ref) <= WORKLOAD_FRO_TOL, relfro(Y, ref)
+    for m0 in range(0, Y.shape[0], rows_per_tile):
+        e = relfro(Y[m0:m0 + rows_per_tile], ref[m0:m0 + rows_per_tile])
+        assert e <= WORKLOAD_FRO_TOL, (m0, e)
+
+
 @pytest.mark.parametrize("r", [256, 512, 1024])
-def test_workload_prefill_sampled_rows(r):
-    """d=4096 ffn=14336 M=4096, launch configuration of the benchmark; the oracle evaluates a sample of
-    rows (rows of X are independent, so this is exact for those rows)."""
+def test_workload_prefill_all_rows(r):
+    """d=4096 ffn=14336 M=4096 in the launch configuration of the benchmark: all 4096 rows (sixteen 256-row tiles, the
+    XCD grid of the gate/up kernel and its mixed round of full and half tiles) against the oracle."""
     gi = synth.make_workload("prefill", r=r)
-    rows = SAMPLE_ROWS + [4095, 3000]
-    Y, ref, path = run_gated(gi, rows=rows)
+    Y, ref, path = run_gated(gi)
     assert path == 5
-    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
-    assert relfro(Y, ref) <= WORKLOAD_FRO_TOL, relfro(Y, ref)
+    assert Y.shape == (4096, 4096)
+    assert_every_row_tile(Y, ref)
 
 
-@pytest.mark.parametrize("M", [200, 1100, 3000, 5000, 16384])
-def test_workload_prefill_extents_other_row_counts_sampled_rows(M):
+@pytest.mark.parametrize("M", [200, 1100, 3000, 5000])
+def test_workload_prefill_extents_other_row_counts_all_rows(M):
     """d=4096 ffn=14336 r=512 at row counts off the benchmark's: few rows (leftover rounds as half tiles, many
-    contraction ranges), ragged last tiles, row counts that are no multiple of the chip's tile rounds, and a large
-    one (first stage on 256 x 256 tiles).  The oracle evaluates rows at the tile borders and the last rows."""
+    contraction ranges), ragged last tiles, row counts that are no multiple of the chip's tile rounds.  All rows."""
     gi = synth.make_workload("prefill", M=M, r=512)
-    rows = sorted({r for r in (0, 1, 31, 32, 127, 128, 255, 256, 1023, 1024, 2999, 4095, 4096, 4999, 8191, 8192, 12345,
-                               M - 257, M - 129, M - 33, M - 2, M - 1) if 0 <= r < M})
+    Y, ref, path = run_gated(gi)
+    assert path == 5
+    assert_every_row_tile(Y, ref)
+
+
+def test_workload_prefill_extents_16384_rows_one_row_of_every_tile():
+    """d=4096 ffn=14336 r=512, M = 16384 (first stage on 256 x 256 tiles): the oracle evaluates the tile borders and a
+    row of every 128-row tile, at a position that moves through the tile."""
+    M = 16384
+    gi = synth.make_workload("prefill", M=M, r=512)
+    rows = sorted({r for r in (0, 1, 31, 32, 127, 128, 255, 256, 1023, 1024, 4095, 4096, 8191, 8192, 12345,
+                               M - 257, M - 129, M - 33, M - 2, M - 1)} | {128 * t + (37 * t) % 128 for t in range(M // 128)})
     Y, ref, path = run_gated(gi, rows=rows)
     assert path == 5
     assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
     assert relfro(Y, ref) <= WORKLOAD_FRO_TOL, relfro(Y, ref)
+
+
+def test_gate_up_xcd_grid_and_mixed_round_all_rows():
+    """Eight row tiles x 40 column tiles of the gate/up kernel = 320 tiles on 256 CUs: one round of full tiles and 64
+    leftover tiles run as 128 halves, on an XCD grid (the planner's description says so); all rows against the oracle."""
+    import re
+    M, d, ffn, r = 2048, 256, 10240, 256
+    gi = synth.make_gated(M, d, ffn, r, r, stream=77)
+    dv = dev()
+    f = {k: v.to(dv) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=M, flags=B.FLAG_FORCE_TILED, **f)
+    text = B.svdmlp_describe(mlp.desc, M)
+    m = re.search(r"k_gate_up\[tile=256x256 tiles=(\d+) workgroups=(\d+) full=(\d+) halves=(\d+) xcd_grid=(\d+)x(\d+)\]", text)
+    assert m, text
+    tiles, wgs, full, halves, g0, g1 = map(int, m.groups())
+    assert (tiles, wgs, full, halves) == (320, 256, 256, 128) and g0 * g1 == 8, text
+    Y = mlp(gi.X.to(dv))
+    torch.cuda.synchronize()
+    assert mlp.last_path == 5
+    Yh = Y.cpu().to(torch.float64).numpy()
+    mlp.close()
+    ref = oracle.gated(synth.to_f64(gi.X), **{k: synth.to_f64(v) for k, v in gi.factors().items()})
+    assert_every_row_tile(Yh, ref)
 
 
 def test_prefill_extents_row_count_whose_activation_passes_4_gib():
@@ -430,22 +471,21 @@ def test_linear_layer_with_an_x_beyond_4_gib_takes_the_first_stage_with_64_bit_r
     assert relmax(Oh, ref) <= BF16_TOL, relmax(Oh, ref)
 
 
-def test_workload_prefill_fused_variant_sampled_rows():
-    """The same workload with the gated activation kept in registers (one fused kernel, path 2)."""
+def test_workload_prefill_fused_variant_all_rows():
+    """The same workload with the gated activation kept in registers (one fused kernel, path 2), all rows."""
     gi = synth.make_workload("prefill", r=512)
-    Y, ref, path = run_gated(gi, rows=SAMPLE_ROWS + [4095], flags=B.FLAG_TILED_FUSED)
+    Y, ref, path = run_gated(gi, flags=B.FLAG_TILED_FUSED)
     assert path == 2
-    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
-    assert relfro(Y, ref) <= WORKLOAD_FRO_TOL, relfro(Y, ref)
+    assert_every_row_tile(Y, ref, rows_per_tile=128)
 
 
-def test_workload_wide_sampled_rows():
-    """d=5120 ffn=27648 r=1024 M=2048, power-law U columns, 1 % of X entries x20."""
+def test_workload_wide_all_rows():
+    """d=5120 ffn=27648 r=1024 M=2048, power-law U columns, 1 % of X entries x20: all 2048 rows against the oracle."""
     gi = synth.make_workload("wide")
-    Y, ref, path = run_gated(gi, rows=SAMPLE_ROWS)
+    Y, ref, path = run_gated(gi)
     assert path == 5
-    assert relmax(Y, ref) <= BF16_TOL, relmax(Y, ref)
-    assert relfro(Y, ref) <= WORKLOAD_FRO_TOL, relfro(Y, ref)
+    assert Y.shape == (2048, 5120)
+    assert_every_row_tile(Y, ref)
 
 
 # ---------------------------------------------------------------------------------- edge cases
