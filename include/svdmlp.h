@@ -59,7 +59,8 @@ enum {
   SVDMLP_UNSUPPORTED = -2,        /* dtype / kind / extent combination the kernels do not cover */
   SVDMLP_WORKSPACE_TOO_SMALL = -3,
   SVDMLP_HIP_ERROR = -4,          /* a HIP runtime call failed; see svdmlp_last_hip_error */
-  SVDMLP_NO_DEVICE = -5           /* no HIP device, or the current device is not gfx950 */
+  SVDMLP_NO_DEVICE = -5,          /* no HIP device, or the current device is not gfx950 */
+  SVDMLP_SCRATCH_TOO_SMALL = -6   /* svdmlp_forward_static_scratch: the extents need more than the static array holds */
 };
 
 /* Bits of svdmlp_desc.flags (testing and benchmarking aids; 0 = automatic choice). */
@@ -112,6 +113,24 @@ int svdmlp_create(const svdmlp_desc *desc, svdmlp_ctx **out);
  * successive calls must be ordered on one stream or by events.  The call only launches kernels (no memset, no
  * copy), so it may be recorded into a HIP graph by stream capture (not while a per-kernel profile is open). */
 int svdmlp_forward(svdmlp_ctx *ctx, const void *X, int64_t M, void *Y, void *hip_stream);
+
+/* svdmlp_forward for callers that cannot allocate device memory for intermediates and cannot hand the library a
+ * buffer for them per call: code recorded under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation once they run.  Same arguments, result and rules as svdmlp_forward, restricted to BF16 GATED contexts and
+ * 1 <= M <= 128 (the weight-streaming path; anything else returns SVDMLP_UNSUPPORTED), but every per-forward buffer
+ * (rank-r strips, the ffn-wide activation of the call's rows, split-K partial tiles, arrival tickets) lives in a
+ * static device array inside the library, svdmlp_static_scratch_bytes() = 16 MiB per GPU, instead of the context's
+ * workspace; the workspace is only read (the re-tiled factors).  The call allocates nothing, makes no memset and no
+ * copy, and only launches kernels (one more than svdmlp_forward: it clears the tickets).  The array's device address
+ * was looked up by svdmlp_create; the current device must be the one the context was created on
+ * (SVDMLP_INVALID_ARGUMENT otherwise).  Extents whose buffers do not fit, 8.5 MiB + 128-row-padded T, H and Td, i.e.
+ * roughly rows * (2 r + ffn + r_down) * 2 bytes > 7.5 MiB with rows = 32, 64 or 128, return SVDMLP_SCRATCH_TOO_SMALL
+ * and launch nothing.  Every GPU holds one such array until the process ends, shared by all contexts and callers on
+ * it: two of these calls that overlap in time on one GPU (different streams, different contexts) race; order them. */
+int svdmlp_forward_static_scratch(svdmlp_ctx *ctx, const void *X, int64_t M, void *Y, void *hip_stream);
+
+/* Size in bytes of that static array (host only). */
+size_t svdmlp_static_scratch_bytes(void);
 
 /* Release the context's host memory.  Does not free or touch device memory; the caller must make
  * sure no forward is still running.  svdmlp_destroy(NULL) returns SVDMLP_OK. */

@@ -22,11 +22,13 @@ SVDMLP_BF16, SVDMLP_F32 = 0, 1
 SVDMLP_GATED, SVDMLP_LINEAR = 0, 1
 SVDMLP_OK = 0
 SVDMLP_INVALID_ARGUMENT, SVDMLP_UNSUPPORTED, SVDMLP_WORKSPACE_TOO_SMALL, SVDMLP_HIP_ERROR, SVDMLP_NO_DEVICE = -1, -2, -3, -4, -5
+SVDMLP_SCRATCH_TOO_SMALL = -6
 FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK, FLAG_STREAM_ONE_KERNEL, FLAG_TILED_FUSED, FLAG_TILE_128 = 1, 2, 4, 8, 16, 32
 
 EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_status_string",
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
-           "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio"]
+           "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio",
+           "svdmlp_forward_static_scratch", "svdmlp_static_scratch_bytes"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -63,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_create.restype = ctypes.c_int
         L.svdmlp_forward.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
         L.svdmlp_forward.restype = ctypes.c_int
+        L.svdmlp_forward_static_scratch.argtypes = L.svdmlp_forward.argtypes
+        L.svdmlp_forward_static_scratch.restype = ctypes.c_int
+        L.svdmlp_static_scratch_bytes.argtypes = []
+        L.svdmlp_static_scratch_bytes.restype = ctypes.c_size_t
         L.svdmlp_destroy.argtypes = [ctypes.c_void_p]
         L.svdmlp_destroy.restype = ctypes.c_int
         L.svdmlp_status_string.argtypes = [ctypes.c_int]
@@ -122,6 +128,17 @@ def svdmlp_forward(ctx, X_ptr: int, M: int, Y_ptr: int, stream_ptr: int = 0) -> 
     st = lib().svdmlp_forward(ctx, ctypes.c_void_p(X_ptr), int(M), ctypes.c_void_p(Y_ptr), ctypes.c_void_p(stream_ptr))
     if st != SVDMLP_OK:
         raise SvdMlpError(st, "svdmlp_forward")
+
+
+def svdmlp_forward_static_scratch(ctx, X_ptr: int, M: int, Y_ptr: int, stream_ptr: int = 0) -> None:
+    st = lib().svdmlp_forward_static_scratch(ctx, ctypes.c_void_p(X_ptr), int(M), ctypes.c_void_p(Y_ptr),
+                                             ctypes.c_void_p(stream_ptr))
+    if st != SVDMLP_OK:
+        raise SvdMlpError(st, "svdmlp_forward_static_scratch")
+
+
+def svdmlp_static_scratch_bytes() -> int:
+    return int(lib().svdmlp_static_scratch_bytes())
 
 
 def svdmlp_destroy(ctx) -> None:

@@ -179,6 +179,7 @@ const char* svdmlp_status_string(int status) {
     case SVDMLP_WORKSPACE_TOO_SMALL: return "workspace too small";
     case SVDMLP_HIP_ERROR: return "HIP runtime error";
     case SVDMLP_NO_DEVICE: return "no gfx950 device";
+    case SVDMLP_SCRATCH_TOO_SMALL: return "extents beyond the library's static scratch array";
     default: return "unknown status";
   }
 }
@@ -296,8 +297,8 @@ int svdmlp_create(const svdmlp_desc* desc, svdmlp_ctx** out) {
     if (desc->workspace_bytes < p.total_bytes) return SVDMLP_WORKSPACE_TOO_SMALL;
   }
   int n_cus = 0;
+  int dev = -1;
   if (!(desc->flags & SVDMLP_FLAG_SKIP_ARCH_CHECK)) {
-    int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return SVDMLP_NO_DEVICE; }
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return SVDMLP_NO_DEVICE; }
@@ -312,6 +313,12 @@ int svdmlp_create(const svdmlp_desc* desc, svdmlp_ctx** out) {
   c->last_hip_error = 0;
   c->last_path = 0;
   c->n_cus = n_cus;
+  c->device = dev;
+  if (desc->dtype == SVDMLP_BF16 && gated && !(desc->flags & SVDMLP_FLAG_SKIP_ARCH_CHECK)) {
+    // this device's copy of the static scratch array, looked up here so that no forward ever has to
+    const int e = static_scratch_resolve(dev, &c->static_scratch);
+    if (e != 0) { (void)hipGetLastError(); delete c; return SVDMLP_HIP_ERROR; }
+  }
   if (desc->dtype == SVDMLP_BF16 && !(desc->flags & SVDMLP_FLAG_SKIP_ARCH_CHECK)) {
     // One-time re-tiling of the invariant factors into matrix-core fragments.
     int e = (int)hipDeviceSynchronize();
@@ -363,6 +370,29 @@ int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip
   }
   return SVDMLP_OK;
 }
+
+int svdmlp_forward_static_scratch(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip_stream) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c || M < 0) return SVDMLP_INVALID_ARGUMENT;
+  if (M == 0) return SVDMLP_OK;
+  if (!X || !Y || X == Y || M > c->plan.max_M) return SVDMLP_INVALID_ARGUMENT;
+  if (!aligned16(X) || !aligned16(Y)) return SVDMLP_INVALID_ARGUMENT;
+  if (c->plan.dtype != SVDMLP_BF16 || c->plan.kind != SVDMLP_GATED || M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+  if (stream_static_scratch_need(c->plan, M) > STATIC_SCRATCH_BYTES) return SVDMLP_SCRATCH_TOO_SMALL;
+  if (c->desc.flags & SVDMLP_FLAG_SKIP_ARCH_CHECK) return SVDMLP_NO_DEVICE;  // host-only context: nothing to run on
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != c->device) { (void)hipGetLastError(); return SVDMLP_INVALID_ARGUMENT; }
+  c->last_path = 3;
+  const int e = bf16_stream_forward_static(c, X, M, Y, static_cast<hipStream_t>(hip_stream));
+  if (e != 0) {
+    c->last_hip_error = e;
+    (void)hipGetLastError();
+    return SVDMLP_HIP_ERROR;
+  }
+  return SVDMLP_OK;
+}
+
+size_t svdmlp_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
 
 static void prof_release(Ctx* c) {
   Prof& p = c->prof;

@@ -202,6 +202,11 @@ int stream_splits16(int tiles, int KB2, int mt);
 int stream_tiles16(int64_t M);
 bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd);   // rows the weight-streaming path takes (four 32-row tiles)
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
+// ... with T, H, Td, the partial tiles and the tickets in the library's static device array (stream.hip)
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+int static_scratch_resolve(int device, char** out);            // hipError_t as int; once per device, at create
+size_t stream_static_scratch_need(const Plan& p, int64_t M);  // bytes of the array a forward of M rows takes
+int bf16_stream_forward_static(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int bf16_linear_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 bool linear_stream_pays(int64_t M, int64_t d, int64_t r, int64_t n);
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
@@ -225,6 +230,8 @@ struct Ctx {
   int last_hip_error;
   int last_path;
   int n_cus = 0;                                 // compute units of the device the context was created on
+  int device = -1;                               // ... and its ordinal
+  char* static_scratch = nullptr;                // that device's copy of the library's static scratch array
   mutable Prof prof;
 };
 

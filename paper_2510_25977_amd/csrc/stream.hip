@@ -15,6 +15,7 @@
 // bit-reproducible.  Products are computed transposed (lane = activation row), so each output tile is
 // already the chain-order frag the next product consumes.
 #include "common.h"
+#include <mutex>
 #include <type_traits>
 
 namespace svdmlp {
@@ -494,11 +495,31 @@ static void launch_stream16(int mt, const StreamArgs& a, hipStream_t st) {
   else hipLaunchKernelGGL((k_stream16<PH, 2>), grid, block, 0, st, a);
 }
 
+// The per-forward buffers of the path: the rank-r strips T, the ffn-wide activation H of its (at most 128) rows, the
+// down strip Td, the partial tiles of the two phases that split their contraction over workgroups, and their tickets.
+struct StreamBufs {
+  char* T;
+  char* H;
+  char* Td;
+  float* part;
+  int* cnt;
+};
+
+static int stream_forward_on(const Ctx* c, const StreamBufs& b, const void* X, int64_t M, void* Y, hipStream_t st);
+
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
-  int* cnt = reinterpret_cast<int*>(ws + p.off_cnt + CNT_ONE_KERNEL_BYTES);
-  float* part = reinterpret_cast<float*>(ws + p.off_part);
+  const StreamBufs b = {ws + p.off_T, ws + p.off_H, ws + p.off_Td, reinterpret_cast<float*>(ws + p.off_part),
+                        reinterpret_cast<int*>(ws + p.off_cnt + CNT_ONE_KERNEL_BYTES)};
+  return stream_forward_on(c, b, X, M, Y, st);
+}
+
+static int stream_forward_on(const Ctx* c, const StreamBufs& b, const void* X, int64_t M, void* Y, hipStream_t st) {
+  const Plan& p = c->plan;
+  char* ws = c->ws;
+  int* cnt = b.cnt;
+  float* part = b.part;
   if (M > STREAM_MAX_M) return (int)hipErrorInvalidValue;
   const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;   // 32-row tiles the batch is padded to
   const bool t16 = stream_uses_tile16(M, p.d, p.ffn, p.r, p.rd);
@@ -510,7 +531,7 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
 
   StreamArgs a;
   // D1
-  a = StreamArgs{ws + p.off_wU, nullptr, X, ws + p.off_T, part, cnt, (int)M, (int)(p.d / 16), (int)(2 * p.r / 32), 1,
+  a = StreamArgs{ws + p.off_wU, nullptr, X, b.T, part, cnt, (int)M, (int)(p.d / 16), (int)(2 * p.r / 32), 1,
                  (int)p.d, (int)p.r, 0, 0, fT, 1};
   a.rtw = stream_row_groups(rt, a.tiles, a.KB, true);
   a.S = stream_splits(a.tiles * a.rtw, a.KB, rt / a.rtw);
@@ -526,14 +547,14 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   prof_mark(c, ps, 0, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D2 (never split over workgroups: its contraction is only r long)
-  a = StreamArgs{ws + p.off_wVg, ws + p.off_wVu, ws + p.off_T, ws + p.off_H, part, cnt, (int)M, (int)(p.r / 16),
+  a = StreamArgs{ws + p.off_wVg, ws + p.off_wVu, b.T, b.H, part, cnt, (int)M, (int)(p.r / 16),
                  (int)(p.ffn / 32), 1, 0, (int)p.r, 0, fT, fH, 1};
   prof_mark(c, ps, 1, 0, st);
   launch_stream<PH_D2>(rt, a, st);
   prof_mark(c, ps, 1, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D4
-  a = StreamArgs{ws + p.off_wUd, nullptr, ws + p.off_H, ws + p.off_Td, part, cnt + 2048 * TICKET_STRIDE, (int)M, (int)(p.ffn / 16),
+  a = StreamArgs{ws + p.off_wUd, nullptr, b.H, b.Td, part, cnt + 2048 * TICKET_STRIDE, (int)M, (int)(p.ffn / 16),
                  (int)(p.rd / 32), 1, 0, (int)p.r, 1, fH, fTd, 1};
   a.rtw = stream_row_groups(rt, a.tiles, a.KB, false);
   a.S = stream_splits(a.tiles * a.rtw, a.KB, rt / a.rtw);
@@ -549,13 +570,81 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   prof_mark(c, ps, 2, 1, st);
   if ((e = (int)hipGetLastError())) return e;
   // D5
-  a = StreamArgs{ws + p.off_wVd, nullptr, ws + p.off_Td, Y, part, cnt, (int)M, (int)(p.rd / 16), (int)(p.d / 32), 1,
+  a = StreamArgs{ws + p.off_wVd, nullptr, b.Td, Y, part, cnt, (int)M, (int)(p.rd / 16), (int)(p.d / 32), 1,
                  (int)p.d, (int)p.r, 0, fTd, 0, 1};
   a.rtw = stream_row_groups_whole(rt, a.tiles);
   prof_mark(c, ps, 3, 0, st);
   launch_stream<PH_D5>(rt / a.rtw, a, st);
   prof_mark(c, ps, 3, 1, st);
   return (int)hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same forward with its per-forward buffers in a static device array instead of the caller's workspace, for
+// callers that may not allocate device memory and hold no workspace of their own for intermediates (code under graph
+// capture, tight serving loops).  Layout of the array: partial tiles (8 MiB, the capacity stream_splits assumes), the
+// ticket lines of D1 and D4, then T, H and Td of the call, each 256-byte aligned.  Every GPU the library's code is
+// loaded on holds its own copy of the array until the process ends; all calls on one GPU share it, so calls that
+// overlap on one GPU race (as forwards on one context do).
+// ------------------------------------------------------------------------------------------------
+constexpr size_t SCRATCH_PART_BYTES = (size_t)8 << 20;
+constexpr size_t SCRATCH_TICKET_BYTES = (size_t)2 * 2048 * TICKET_STRIDE * 4;
+constexpr size_t SCRATCH_ACT_OFF = SCRATCH_PART_BYTES + SCRATCH_TICKET_BYTES;
+static_assert(STATIC_SCRATCH_BYTES > SCRATCH_ACT_OFF, "room for the activations");
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+// Device address of this GPU's copy of the array.  The array's name is only a host-side handle; the address comes
+// from the runtime, once per device, with that device current (svdmlp_create calls this, so the lookup, which may load
+// the code object, never happens inside a forward).
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static char* g_scratch_ptr[MAX_DEVICES] = {};
+
+int static_scratch_resolve(int device, char** out) {
+  if (device < 0 || device >= MAX_DEVICES) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    char* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!ptr) return (int)hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return 0;
+}
+
+__global__ __launch_bounds__(256) void k_clear_tickets(int* cnt, int lines) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < lines) cnt[(size_t)i * TICKET_STRIDE] = 0;
+}
+
+size_t stream_static_scratch_need(const Plan& p, int64_t M) {
+  const size_t rows = M <= 32 ? 32 : M <= 64 ? 64 : 128;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  return SCRATCH_ACT_OFF + up(rows * 2 * p.r * 2) + up(rows * p.ffn * 2) + up(rows * p.rd * 2);
+}
+
+int bf16_stream_forward_static(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st) {
+  const Plan& p = c->plan;
+  char* base = c->static_scratch;   // resolved at create for this context's device
+  if (!base || stream_static_scratch_need(p, M) > STATIC_SCRATCH_BYTES) return (int)hipErrorInvalidValue;
+  const size_t rows = M <= 32 ? 32 : M <= 64 ? 64 : 128;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  StreamBufs b;
+  b.part = reinterpret_cast<float*>(base);
+  b.cnt = reinterpret_cast<int*>(base + SCRATCH_PART_BYTES);
+  b.T = base + SCRATCH_ACT_OFF;
+  b.H = b.T + up(rows * 2 * p.r * 2);
+  b.Td = b.H + up(rows * p.ffn * 2);
+  // The tickets must start at zero.  Every forward leaves them at zero, but the array is shared by every caller on
+  // this GPU and outlives them, so they are cleared here, with a kernel (a memset node does not belong in a graph
+  // that a caller may be capturing).  The other buffers are written before they are read.
+  const int lines = 2 * 2048;
+  hipLaunchKernelGGL(k_clear_tickets, dim3((lines + 255) / 256), dim3(256), 0, st, b.cnt, lines);
+  const int e = (int)hipGetLastError();
+  if (e) return e;
+  return stream_forward_on(c, b, X, M, Y, st);
 }
 
 // Whether the single factored layer of M <= 128 rows streams: every workgroup of a phase re-reads the activation of

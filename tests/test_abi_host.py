@@ -54,7 +54,7 @@ def create_status(d):
 
 
 def test_status_strings(lib):
-    for code in (0, -1, -2, -3, -4, -5, 17):
+    for code in (0, -1, -2, -3, -4, -5, -6, 17):
         s = lib.svdmlp_status_string(code)
         assert s and len(s) > 1
     assert b"workspace" in lib.svdmlp_status_string(B.SVDMLP_WORKSPACE_TOO_SMALL)
@@ -123,6 +123,40 @@ def test_host_only_context_lifecycle(lib):
     assert lib.svdmlp_profile_kernel_name(out, 0) is None
     assert lib.svdmlp_destroy(out) == 0
     assert lib.svdmlp_destroy(None) == 0
+
+
+def test_static_scratch_forward_checks_its_arguments_without_a_device(lib):
+    """The allocation-free variant validates like svdmlp_forward, takes only what streams (bf16, gated, up to 128 rows)
+    and refuses extents whose per-forward buffers pass the static array, all before touching a device."""
+    assert lib.svdmlp_static_scratch_bytes() == 16 << 20
+    fwd = lib.svdmlp_forward_static_scratch
+    X, Y = ctypes.c_void_p(0x2000), ctypes.c_void_p(0x3000)
+    out = ctypes.c_void_p()
+    d = desc(max_M=300)
+    assert lib.svdmlp_create(ctypes.byref(d), ctypes.byref(out)) == 0
+    assert fwd(out, X, 0, Y, None) == 0
+    assert fwd(out, X, -1, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert fwd(out, X, 301, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert fwd(out, None, 4, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert fwd(out, X, 4, X, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert fwd(out, ctypes.c_void_p(0x2002), 4, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert fwd(None, X, 4, Y, None) == B.SVDMLP_INVALID_ARGUMENT
+    assert fwd(out, X, 129, Y, None) == B.SVDMLP_UNSUPPORTED          # beyond the weight-streaming path
+    assert fwd(out, X, 128, Y, None) == B.SVDMLP_NO_DEVICE            # would run: host-only context
+    lib.svdmlp_destroy(out)
+    for kw in (dict(dtype=B.SVDMLP_F32), dict(kind=B.SVDMLP_LINEAR)):
+        d = desc(**kw)
+        assert lib.svdmlp_create(ctypes.byref(d), ctypes.byref(out)) == 0
+        assert fwd(out, X, 4, Y, None) == B.SVDMLP_UNSUPPORTED
+        lib.svdmlp_destroy(out)
+    # 128 rows x ffn = 30720: the activation alone is 7.9 MB, the array has 7.5 MiB for T, H and Td
+    d = desc(max_M=128, ffn=30720)
+    assert lib.svdmlp_create(ctypes.byref(d), ctypes.byref(out)) == 0
+    assert fwd(out, X, 128, Y, None) == B.SVDMLP_SCRATCH_TOO_SMALL
+    assert fwd(out, X, 65, Y, None) == B.SVDMLP_SCRATCH_TOO_SMALL     # 65 rows run as 128
+    assert fwd(out, X, 64, Y, None) == B.SVDMLP_NO_DEVICE             # fits
+    assert b"static scratch" in lib.svdmlp_status_string(B.SVDMLP_SCRATCH_TOO_SMALL)
+    lib.svdmlp_destroy(out)
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
