@@ -1,22 +1,31 @@
 #!/usr/bin/env python3
 """Benchmark of the fused SVD-factored gated MLP forward on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload prefill|wide|mlp_small|decode|xuv] [--r R] [--M M]
-                    [--fused] [--one-kernel-decode] [--sweep] [--shape d,r,n] [--no-cpu-baseline] [--no-dense] [--no-decode]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--repeats R] [--workload prefill|wide|mlp_small|decode|xuv]
+                    [--r R] [--M M] [--fused] [--one-kernel-decode] [--sweep] [--shape d,r,n] [--roofs]
+                    [--no-cpu-baseline] [--no-dense] [--no-decode] [--no-configs] [--no-roofs]
 
 A step is one pass of the whole hot path (svdmlp_forward: rank-r strips, gate/up second stage with
 the SiLU gate, down projection) over one batch of seeded synthetic input already resident in HBM.
 Prints ONE JSON line.  `value` is TFLOP/s of the prefill workload (algorithmic FLOPs 6 M r (d + ffn)
-divided by the step time); the same line also carries the decode-shape GB/s, a dense bf16 MLP on the
-same GPU (third-party GEMMs through torch), the roofline of the dominant kernel and the CPU oracle
-timed on the host cores.  Defaults: 50 warm-up and 200 timed steps (the clocks need a few tens of
-forwards to settle; short runs read about 15 % slower).
+divided by the step time); the same line also carries the other configurations (`configs`: the prefill
+rank sweep, the wide layer, the 128-row layer and the decode shapes, each with its rate and fraction of
+its roof), a dense bf16 MLP on the same GPU (third-party GEMMs through torch), the roofline of the
+dominant kernel against the published and the measured peak, and the CPU oracle timed on the host cores.
+
+Timing protocol: W untimed warm-up steps, then R (default 10) batches of exactly K steps, each batch
+between two HIP events on the launch stream with a device synchronisation on both sides;
+`ms_per_step` is the MEDIAN batch (per step), `ms_per_step_min` the fastest, `ms_per_step_first_batch`
+the first one (what a single short batch straight after the warm-up reads while the clocks are still
+settling: about 15 % slower at K = 20).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -34,31 +43,46 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
-# HBM-side bytes per forward of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
-# scaled by a plain copy of known size (profiles/prefill_r512_pmc_traffic_mfma.txt); key = (kernel, M, d, ffn, r)
-MEASURED_TRAFFIC = {
-    ("k_gate_up", 4096, 4096, 14336, 512): {"read_MB": 181.3, "written_MB": 117.5, "algorithmic_read_MB": 37.7,
-                                            "algorithmic_written_MB": 117.4,
-                                            "source": "profiles/prefill_r512_pmc_traffic_mfma.txt"},
-    ("k_stream_d2", 16, 4096, 14336, 512): {"read_MB": 29.95, "written_MB": 0.92, "algorithmic_read_MB": 29.38,
-                                            "algorithmic_written_MB": 0.46,
-                                            "source": "profiles/decode_m16_kernel_trace_pmc.txt"},
-}
+def measured_traffic(kernel, profile):
+    """HBM-side bytes per launch of `kernel` from the rocprofv3 --pmc summary `profile` under profiles/ (FETCH_SIZE /
+    WRITE_SIZE scaled by a copy of known size; the file says how): the line "  <kernel> ... read X MB  written Y MB"."""
+    path = os.path.join(ROOT, "profiles", profile)
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"^\s*" + re.escape(kernel) + r"\S*\s.*?read\s+([0-9.]+) MB\s+written\s+([0-9.]+) MB", text, re.M)
+    if not m:
+        return None
+    return {"read_MB": float(m.group(1)), "written_MB": float(m.group(2)), "source": "profiles/" + profile}
 
 
-def time_steps(fn, steps, warmup):
+def time_batches(fn, steps, warmup, repeats=10):
+    """W untimed warm-up steps, then `repeats` batches of exactly `steps` steps, each between two events on the current
+    stream, with a synchronisation before and after.  Returns per-step milliseconds: median, min, first, all."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        fn()
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    return e0.elapsed_time(e1) / steps, wall_ms / steps
+    per = []
+    wall = []
+    for _ in range(max(1, repeats)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall.append((time.perf_counter() - t0) * 1e3 / steps)
+        per.append(e0.elapsed_time(e1) / steps)
+    return {"median": statistics.median(per), "min": min(per), "first": per[0], "all": per,
+            "wall_median": statistics.median(wall), "repeats": len(per)}
+
+
+def time_steps(fn, steps, warmup, repeats=3):
+    t = time_batches(fn, steps, warmup, repeats)
+    return t["median"], t["wall_median"]
 
 
 def make_ctx(gi, dev, max_M, flags=0):
@@ -66,24 +90,24 @@ def make_ctx(gi, dev, max_M, flags=0):
     return B.SvdMlp(max_M=max_M, flags=flags, keep_factors=False, **f)
 
 
-def bench_forward(gi, dev, steps, warmup, profile=True, flags=0):
-    """Time `steps` forwards of one context, twice: first bare (this is the reported throughput), then again with
-    the library recording a HIP event before and after every kernel on the launch stream, which gives the
-    per-kernel averages (the event packets between the kernels cost a few microseconds per launch, so the second
-    pass is slower; both step times are reported)."""
+def bench_forward(gi, dev, steps, warmup, profile=True, flags=0, repeats=10):
+    """Time the forward of one context (time_batches); then once more with the library recording a HIP event before
+    and after every kernel on the launch stream, which gives the per-kernel averages (the event packets between the
+    kernels cost a few microseconds per launch, so that pass is slower; both step times are reported)."""
     dims = gi.dims
     mlp = make_ctx(gi, dev, dims["M"], flags=flags)
     X = gi.X.to(dev)
     Y = torch.empty_like(X)
-    ms, wall_ms = time_steps(lambda: mlp(X, Y), steps, warmup)
+    t = time_batches(lambda: mlp(X, Y), steps, warmup, repeats)
     kernels, ms_ev = {}, None
     if profile:
-        B.svdmlp_profile_begin(mlp.ctx, steps)
-        ms_ev, _ = time_steps(lambda: mlp(X, Y), steps, 0)
+        n_ev = max(steps, 20)
+        B.svdmlp_profile_begin(mlp.ctx, n_ev)
+        ms_ev = time_batches(lambda: mlp(X, Y), n_ev, 0, 1)["median"]
         kernels, nf = B.svdmlp_profile_end(mlp.ctx)
     path = mlp.last_path
     mlp.close()
-    return ms, wall_ms, kernels, path, ms_ev
+    return t, kernels, path, ms_ev
 
 
 def bench_xuv(dev, M, steps, warmup, dense=True, shape=(8192, 4096, 16384)):
@@ -98,7 +122,7 @@ def bench_xuv(dev, M, steps, warmup, dense=True, shape=(8192, 4096, 16384)):
     O = torch.empty((M, n), dtype=torch.bfloat16, device=dev)
     ms, wall_ms = time_steps(lambda: mlp(X, O), steps, warmup)
     B.svdmlp_profile_begin(mlp.ctx, steps)
-    ms_ev, _ = time_steps(lambda: mlp(X, O), steps, 0)
+    ms_ev, _ = time_steps(lambda: mlp(X, O), steps, 0, repeats=1)
     kernels, _ = B.svdmlp_profile_end(mlp.ctx)
     path = mlp.last_path
     U, V = mlp.tensors[0], mlp.tensors[1]
@@ -156,38 +180,83 @@ def copy_calibration(dev, reps=5):
     return dict(bytes_read=n, bytes_written=n, launches=reps, kernel="torch Tensor.copy_ (uint8, 256 MiB)")
 
 
-def bench_decode_rotating(dev, M, steps, warmup, nsets=12, flags=0, r=None):
-    """Decode shape measured cold to the 256 MB memory-side cache: rotate through `nsets` independent
-    factor sets (one context each, > 2x the cache in total) so every forward streams its weights from HBM."""
-    gi = synth.make_workload("decode", M=M, r=r)
-    dims = gi.dims
-    X = gi.X.to(dev)
-    Y = torch.empty_like(X)
-    ctxs = []
+def rotating_contexts(gi, dev, max_M, nsets, flags=0):
+    """`nsets` contexts over the same factor values at different addresses (one re-tiled copy each)."""
     f = {k: v.to(dev) for k, v in gi.factors().items()}
-    for i in range(nsets):
-        # the same values in every set; only the addresses (hence the cache lines) differ
-        ctxs.append(B.SvdMlp(max_M=max(16, M), keep_factors=False, flags=flags, **f))
+    ctxs = [B.SvdMlp(max_M=max_M, keep_factors=False, flags=flags, **f) for _ in range(nsets)]
     del f
+    return ctxs
+
+
+def bench_rotating(ctxs, gi, dev, M, steps, warmup, repeats, warm_too=True):
+    """A weight-bandwidth-bound shape measured cold to the 256 MB memory-side cache: the forwards rotate through
+    independent factor sets (one context each, more than 2x the cache in total), so every forward streams its
+    weights from HBM.  The single-set time (warm in that cache) and its per-kernel split are reported beside it."""
+    dims = gi.dims
+    X = gi.X[:M].contiguous().to(dev)
+    Y = torch.empty_like(X)
     n = [0]
+    nsets = len(ctxs)
 
     def step():
         ctxs[n[0] % nsets](X, Y)
         n[0] += 1
 
-    ms, _ = time_steps(step, steps, warmup)
-    # single set, warm in the memory-side cache; then once more for its per-kernel split (the events cost a few
-    # microseconds per launch, so that pass is not the one timed)
-    ms_warm, _ = time_steps(lambda: ctxs[0](X, Y), steps, warmup)
-    B.svdmlp_profile_begin(ctxs[0].ctx, steps)
-    time_steps(lambda: ctxs[0](X, Y), steps, 0)
-    kernels, _ = B.svdmlp_profile_end(ctxs[0].ctx)
+    t = time_batches(step, steps, warmup, repeats)
+    nbytes = cm.gated_mlp_bytes(M, dims["d"], dims["ffn"], dims["r"])
+    out = dict(M=M, ms_per_step=t["median"], ms_per_step_min=t["min"], steps_per_batch=steps, repeats=t["repeats"],
+               GBps=nbytes / t["median"] / 1e6, frac_of_hbm_peak=nbytes / t["median"] / 1e6 / PEAK_HBM_GBS, bytes=nbytes,
+               factor_sets=nsets)
+    if warm_too:
+        tw = time_batches(lambda: ctxs[0](X, Y), steps, warmup, max(3, repeats // 2))
+        # once more for the per-kernel split (the events cost a few microseconds per launch: not the pass that is timed)
+        B.svdmlp_profile_begin(ctxs[0].ctx, steps)
+        time_batches(lambda: ctxs[0](X, Y), steps, 0, 1)
+        kernels, _ = B.svdmlp_profile_end(ctxs[0].ctx)
+        out.update(warm_single_set_ms=tw["median"], warm_GBps=nbytes / tw["median"] / 1e6, warm_kernels_ms=kernels)
+    return out
+
+
+def bench_decode_rotating(dev, M, steps, warmup, nsets=12, flags=0, r=None, repeats=10):
+    gi = synth.make_workload("decode", M=M, r=r)
+    ctxs = rotating_contexts(gi, dev, max(16, M), nsets, flags)
+    out = bench_rotating(ctxs, gi, dev, M, steps, warmup, repeats)
     for c in ctxs:
         c.close()
-    nbytes = cm.gated_mlp_bytes(M, dims["d"], dims["ffn"], dims["r"])
-    return dict(M=M, ms_per_step=ms, GBps=nbytes / ms / 1e6, frac_of_hbm_peak=nbytes / ms / 1e6 / PEAK_HBM_GBS,
-                bytes=nbytes, factor_sets=nsets, warm_single_set_ms=ms_warm, warm_GBps=nbytes / ms_warm / 1e6,
-                warm_kernels_ms=kernels)
+    return out
+
+
+def measure_roofs(dev, quick=True):
+    """What this machine delivers with kernels that do one thing only (svdmlp_roof_* of the library): a streaming
+    read of a buffer larger than the memory-side cache (HBM), the same over a buffer that fits it, a register-resident
+    MFMA issue loop, and a chain of four dependent launches of an empty kernel of the decode path's launch shape."""
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    s = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    out = {"compute_units": cus}
+    big = torch.full(((1536 << 20),), 1, dtype=torch.uint8, device=dev)
+    for name, nbytes in (("hbm_read", big.numel()), ("memory_side_cache_read", 96 << 20)):
+        t = time_batches(lambda: B.svdmlp_roof_read(big.data_ptr(), nbytes, sink.data_ptr(), cus * 8, s),
+                         4 if nbytes > (1 << 30) else 40, 2, 5)
+        out[name] = {"bytes": nbytes, "ms": t["median"], "GBps": nbytes / t["median"] / 1e6, "GBps_best": nbytes / t["min"] / 1e6}
+    del big
+    iters = 8000
+    t = time_batches(lambda: B.svdmlp_roof_mfma(iters, sink.data_ptr(), cus, s), 3, 2, 5)
+    fl = cus * 8 * 4 * iters * 32768
+    out["mfma_bf16"] = {"flop": fl, "ms": t["median"], "TFLOPs": fl / t["median"] / 1e9, "TFLOPs_best": fl / t["min"] / 1e9,
+                        "note": "v_mfma_f32_32x32x16_bf16, constant register operands, two waves per SIMD"}
+
+    def chain():
+        for _ in range(4):
+            B.svdmlp_roof_empty(256, 512, s)
+
+    t = time_batches(chain, 200, 20, 5)
+    out["four_dependent_empty_launches_us"] = {"median": t["median"] * 1e3, "min": t["min"] * 1e3,
+                                               "shape": "256 workgroups x 512 threads, back to back in a loop of such chains"}
+    t = time_batches(lambda: B.svdmlp_roof_empty(256, 512, s), 400, 20, 5)
+    out["one_empty_launch_us"] = {"median": t["median"] * 1e3, "min": t["min"] * 1e3}
+    assert int(sink.abs().sum().item()) == 0   # the sinks are never written
+    return out
 
 
 def bench_dense(dev, M, d, ffn, steps, warmup):
@@ -221,33 +290,99 @@ def bench_unfused(gi, dev, steps, warmup):
     return dict(ms_per_step=ms, provider="six torch.matmul calls + silu * mul (third-party kernels)")
 
 
-def cpu_baseline(gi, target_seconds=12.0):
-    """The fp64 oracle as it stands, timed on the host cores on a bounded sample of rows of the same workload."""
+def _oracle_rows(oracle, X, a, rows):
+    t0 = time.perf_counter()
+    oracle.gated(X[:rows], **a)
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(gi, target_seconds=10.0):
+    """The fp64 oracle as it stands, timed on the host cores on a bounded sample of rows of the same workload: with all
+    the threads its OpenMP row loop takes, and with one thread (omp_set_num_threads of the OpenMP runtime the oracle is
+    linked against; the oracle itself is not touched)."""
+    import ctypes
     import oracle
     a = {k: synth.to_f64(v) for k, v in gi.factors().items()}
     X = synth.to_f64(gi.X)
     dims = gi.dims
     fl_row = cm.gated_mlp_flops(1, dims["d"], dims["ffn"], dims["r"])
     cores = oracle.threads()
-    probe = min(X.shape[0], max(cores, 8))
-    t0 = time.perf_counter()
-    oracle.gated(X[:probe], **a)
-    dt = time.perf_counter() - t0
-    rows = int(min(X.shape[0], max(probe, target_seconds / max(dt / probe, 1e-9))))
-    rows = max(cores, rows // cores * cores) if rows >= cores else rows
-    rows = min(rows, X.shape[0])
-    t0 = time.perf_counter()
-    oracle.gated(X[:rows], **a)
-    dt = time.perf_counter() - t0
-    return dict(value=fl_row * rows / dt / 1e12, unit="TFLOP/s", cores=cores, kind="oracle",
-                sample=f"first {rows} of {X.shape[0]} rows of the same workload, fp64, {dt:.1f} s", seconds=dt)
+
+    def sample(threads, budget):
+        probe = min(X.shape[0], max(threads, 8))
+        dt = _oracle_rows(oracle, X, a, probe)
+        rows = int(min(X.shape[0], max(probe, budget / max(dt / probe, 1e-9))))
+        rows = max(threads, rows // threads * threads) if rows >= threads else rows
+        rows = min(rows, X.shape[0])
+        dt = _oracle_rows(oracle, X, a, rows)
+        return rows, dt
+
+    rows, dt = sample(cores, target_seconds)
+    out = dict(value=fl_row * rows / dt / 1e12, unit="TFLOP/s", cores=cores, kind="oracle",
+               sample=f"first {rows} of {X.shape[0]} rows of the same workload, fp64, {dt:.1f} s", seconds=dt)
+    try:
+        omp = ctypes.CDLL("libgomp.so.1")
+        omp.omp_set_num_threads(1)
+        try:
+            if oracle.threads() == 1:
+                rows1, dt1 = sample(1, target_seconds * 0.6)
+                out["one_thread"] = dict(value=fl_row * rows1 / dt1 / 1e12, unit="TFLOP/s", cores=1,
+                                         sample=f"first {rows1} rows, fp64, {dt1:.1f} s", seconds=dt1)
+        finally:
+            omp.omp_set_num_threads(cores)
+    except OSError:
+        pass
+    return out
+
+
+def bench_configs(dev, steps, warmup, repeats, skip=()):
+    """The other configurations of the metric, each timed like the headline: the prefill shape at r = 256 and 1024,
+    the wide layer, the 128-row layer (cold to the memory-side cache) and the decode shape at M = 1, 4, 16 (cold)."""
+    rows = []
+    for name, kw in (("prefill", dict(r=256)), ("prefill", dict(r=1024)), ("wide", {})):
+        gi = synth.make_workload(name, **kw)
+        dm = gi.dims
+        t, kernels, path, _ = bench_forward(gi, dev, steps, warmup, profile=True, repeats=repeats)
+        fl = cm.gated_mlp_flops(dm["M"], dm["d"], dm["ffn"], dm["r"])
+        rows.append({"workload": f"{name}: d={dm['d']} ffn={dm['ffn']} r={dm['r']} M={dm['M']}", "bound": "mfma",
+                     "ms_per_step": t["median"], "ms_per_step_min": t["min"], "TFLOPs": fl / t["median"] / 1e9,
+                     "frac_of_bf16_mfma_peak": fl / t["median"] / 1e9 / PEAK_BF16_TFLOPS, "kernels_ms": kernels, "path": path})
+        del gi
+        torch.cuda.empty_cache()
+    # 128-row layer: 15.7 MB of factors per set; 40 sets pass twice the memory-side cache
+    gi = synth.make_workload("mlp_small")
+    dm = gi.dims
+    ctxs = rotating_contexts(gi, dev, dm["M"], 40)
+    b = bench_rotating(ctxs, gi, dev, dm["M"], max(steps, 100), warmup, repeats)
+    for c in ctxs:
+        c.close()
+    b.update(workload=f"mlp_small: d={dm['d']} ffn={dm['ffn']} r={dm['r']} M={dm['M']}", bound="hbm",
+             TFLOPs=cm.gated_mlp_flops(dm["M"], dm["d"], dm["ffn"], dm["r"]) / b["ms_per_step"] / 1e9)
+    rows.append(b)
+    del ctxs
+    torch.cuda.empty_cache()
+    if "decode" not in skip:
+        gi = synth.make_workload("decode", M=16)
+        dm = gi.dims
+        ctxs = rotating_contexts(gi, dev, 16, 12)
+        for M in (1, 4, 16):
+            b = bench_rotating(ctxs, gi, dev, M, max(steps, 200), warmup, repeats, warm_too=(M == 16))
+            b.update(workload=f"decode: d={dm['d']} ffn={dm['ffn']} r={dm['r']} M={M}", bound="hbm")
+            rows.append(b)
+        for c in ctxs:
+            c.close()
+    return rows
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--repeats", type=int, default=10, help="timed batches of --steps steps; the median batch is reported")
+    ap.add_argument("--roofs", action="store_true", help="only the roof microbenchmarks (one JSON line)")
+    ap.add_argument("--no-roofs", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other configurations (`configs` of the line)")
     ap.add_argument("--workload", default="prefill", choices=["prefill", "wide", "mlp_small", "decode", "xuv"])
     ap.add_argument("--r", type=int, default=None)
     ap.add_argument("--M", type=int, default=None)
@@ -332,6 +467,12 @@ def main():
         print(json.dumps(out))
         return
 
+    if args.roofs:
+        print(json.dumps({"metric": "roof microbenchmarks", "peak_bf16_TFLOPs": PEAK_BF16_TFLOPS, "peak_hbm_GBps": PEAK_HBM_GBS,
+                          "measured": measure_roofs(dev)}))
+        return
+    roofs = None if args.no_roofs else measure_roofs(dev)
+
     gi = synth.make_workload(args.workload, M=args.M, r=args.r)
     dims = gi.dims
     M, d, ffn, r = dims["M"], dims["d"], dims["ffn"], dims["r"]
@@ -339,13 +480,17 @@ def main():
     nbytes = cm.gated_mlp_bytes(M, d, ffn, r)
 
     dflags = B.FLAG_STREAM_ONE_KERNEL if args.one_kernel_decode else 0
+    ms_ev = None
     if args.workload == "decode":
-        dec = bench_decode_rotating(dev, M, args.steps, args.warmup, flags=dflags, r=args.r)
-        ms, wall_ms, kernels, path = dec["ms_per_step"], dec["ms_per_step"], dec["warm_kernels_ms"], (4 if dflags else 3)
+        dec = bench_decode_rotating(dev, M, max(args.steps, 200), args.warmup, flags=dflags, r=args.r, repeats=args.repeats)
+        t = {"median": dec["ms_per_step"], "min": dec["ms_per_step_min"], "first": None, "wall_median": dec["ms_per_step"],
+             "repeats": dec["repeats"]}
+        kernels, path = dec["warm_kernels_ms"], (4 if dflags else 3)
     else:
-        ms, wall_ms, kernels, path, ms_ev = bench_forward(gi, dev, args.steps, args.warmup,
-                                                          flags=B.FLAG_TILED_FUSED if args.fused else 0)
+        t, kernels, path, ms_ev = bench_forward(gi, dev, args.steps, args.warmup, flags=B.FLAG_TILED_FUSED if args.fused else 0,
+                                                repeats=args.repeats)
         dec = None
+    ms = t["median"]
 
     out = {
         "metric": METRIC,
@@ -357,15 +502,24 @@ def main():
         "config": {"workload": f"{args.workload}: gated SVD-MLP d={d} ffn={ffn} r={r} M={M}", "M": M, "d": d, "ffn": ffn,
                    "r": r, "path": {2: "mfma-tiled, fused", 3: "weight-streaming, 4 launches", 4: "weight-streaming, 1 launch",
                             5: "mfma-tiled, staged"}.get(path, str(path))},
+        "timing": {"protocol": "warm-up, then `repeats` batches of `steps` forwards, each between two HIP events on the launch "
+                               "stream with a synchronisation on both sides; ms_per_step = median batch / steps",
+                   "repeats": t["repeats"], "ms_per_step_min": t["min"], "ms_per_step_first_batch": t["first"],
+                   "value_at_min": (flops / t["min"] / 1e9 if args.workload != "decode" else nbytes / t["min"] / 1e6),
+                   "value_first_batch": (flops / t["first"] / 1e9 if t["first"] else None)},
         "flops_per_step": flops, "algorithmic_bytes_per_step": nbytes,
         "frac_of_bf16_mfma_peak": flops / ms / 1e9 / PEAK_BF16_TFLOPS,
-        "wall_ms_per_step": wall_ms,
+        "wall_ms_per_step": t["wall_median"],
         "kernels_ms": kernels,
     }
+    if roofs is not None:
+        out["measured_roofs"] = roofs
+        if args.workload != "decode":
+            out["frac_of_measured_mfma_peak"] = flops / ms / 1e9 / roofs["mfma_bf16"]["TFLOPs"]
     if args.workload != "decode":
         out["ms_per_step_with_kernel_events"] = ms_ev
 
-    # roofline of the dominant kernel (HIP-event average over the timed region)
+    # roofline of the dominant kernel (HIP-event average over a timed region of the same forwards)
     if path in (3, 4):   # weight-streaming path: HBM-bound
         rd = dims.get("r_down", r)
         kbytes = {"k_decode": nbytes,                                           # the whole forward is one launch
@@ -377,12 +531,18 @@ def main():
         kname = "k_stream_d2" if args.workload == "decode" and "k_stream_d2" in cand else max(cand, key=cand.get)
         k_ms = kernels.get(kname, 0.0)
         k_bytes = kbytes[kname]
+        traffic = measured_traffic(kname, "decode_m16_kernel_trace_pmc.txt") if (M, d, ffn, r) == (16, 4096, 14336, 512) else None
+        if traffic:
+            traffic["algorithmic_MB"] = k_bytes / 1e6
         out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": k_bytes / k_ms / 1e6 if k_ms else None,
                            "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": k_bytes / k_ms / 1e6 / PEAK_HBM_GBS if k_ms else None,
-                           "traffic": MEASURED_TRAFFIC.get((kname, M, d, ffn, r)),
+                           "traffic": traffic,
                            "whole_forward_GBps": nbytes / ms / 1e6,
                            "note": "per-kernel time from HIP events" + (" of the warm single-set run" if args.workload == "decode" else "")}
+        if roofs is not None and k_ms:
+            out["roofline"]["measured_peak"] = roofs["hbm_read"]["GBps"]
+            out["roofline"]["frac_of_measured_peak"] = k_bytes / k_ms / 1e6 / roofs["hbm_read"]["GBps"]
     else:
         rd = dims.get("r_down", r)
         kflops = {"k_s1": 2 * M * d * 2 * r, "k_in": 2 * M * d * 2 * r,   # X [Ug|Uu]
@@ -390,20 +550,50 @@ def main():
                   "k_gate_up": 4 * M * ffn * r,             # gate + up second stage
                   "k_down1": 2 * M * ffn * rd,              # down first stage
                   "k_s5": 2 * M * rd * d, "k_out": 2 * M * rd * d}
+        # bytes each kernel has to move at least: its factor panels and rank-r strips once, X in, Y out; the ffn-wide
+        # activation H and the split-K partial sums are the implementation's own traffic and count as nothing
+        kalg = {"k_s1": 2 * (M * d + 2 * d * r), "k_in": 2 * (M * d + 2 * d * r),
+                "k_gate_up": 2 * (M * 2 * r + 2 * r * ffn), "k_fused": 2 * (M * 2 * r + 2 * r * ffn + ffn * rd),
+                "k_down1": 2 * (ffn * rd), "k_s5": 2 * (M * rd + rd * d + M * d), "k_out": 2 * (M * rd + rd * d + M * d)}
         cand = {k: v for k, v in kernels.items() if k in kflops}
         kname = max(cand, key=cand.get) if cand else "k_gate_up"   # the dominant kernel: the longest one
         k_ms = kernels.get(kname, 0.0)
         k_flops = kflops[kname]
+        traffic = None
+        if args.workload == "prefill" and M == 4096 and not args.fused:
+            traffic = measured_traffic(kname, f"prefill_r{r}_pmc_traffic_mfma.txt")
+        if traffic:
+            traffic["algorithmic_MB"] = kalg[kname] / 1e6
+            traffic["times_algorithmic"] = (traffic["read_MB"] + traffic["written_MB"]) / (kalg[kname] / 1e6)
         out["roofline"] = {"bound": "mfma", "kernel": kname, "achieved": k_flops / k_ms / 1e9 if k_ms else None,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": k_flops / k_ms / 1e9 / PEAK_BF16_TFLOPS if k_ms else None,
-                           "traffic": MEASURED_TRAFFIC.get((kname, M, d, ffn, r)),
+                           "traffic": traffic,
                            "per_kernel_TFLOPs": {k: kflops[k] / v / 1e9 for k, v in cand.items() if v}}
+        if roofs is not None and k_ms:
+            out["roofline"]["measured_peak"] = roofs["mfma_bf16"]["TFLOPs"]
+            out["roofline"]["frac_of_measured_peak"] = k_flops / k_ms / 1e9 / roofs["mfma_bf16"]["TFLOPs"]
 
     if dec is not None:
         out["decode"] = dec
-    elif not args.no_decode:
-        out["decode"] = bench_decode_rotating(dev, 16, max(args.steps, 48), args.warmup, flags=dflags)
+    elif not args.no_decode and args.no_configs:
+        out["decode"] = bench_decode_rotating(dev, 16, max(args.steps, 200), args.warmup, flags=dflags, repeats=args.repeats)
+    if not args.no_configs and args.workload == "prefill" and args.r in (None, 512) and args.M in (None, 4096) and not args.fused:
+        del gi
+        torch.cuda.empty_cache()
+        out["configs"] = bench_configs(dev, args.steps, args.warmup, max(3, args.repeats // 2),
+                                       skip=("decode",) if args.no_decode else ())
+        for row in out["configs"]:
+            if row["workload"].startswith("decode") and row["M"] == 16:
+                out["decode"] = row
+        gi = synth.make_workload(args.workload, M=args.M, r=args.r)
+    if "decode" in out and roofs is not None:
+        out["decode"]["measured_hbm_peak_GBps"] = roofs["hbm_read"]["GBps"]
+        out["decode"]["frac_of_measured_hbm_peak"] = out["decode"]["GBps"] / roofs["hbm_read"]["GBps"]
+        # the floor of a forward that is four dependent launches: the launches themselves plus its bytes at the measured rate
+        floor_us = roofs["four_dependent_empty_launches_us"]["median"] + out["decode"]["bytes"] / roofs["hbm_read"]["GBps"] / 1e3
+        out["decode"]["floor_four_launches_plus_bytes_us"] = floor_us
+        out["decode"]["frac_of_hbm_peak_at_that_floor"] = out["decode"]["bytes"] / floor_us / 1e3 / PEAK_HBM_GBS
     if not args.no_dense and args.workload != "decode":
         out["dense_baseline"] = bench_dense(dev, M, d, ffn, max(5, args.steps // 3), max(3, args.warmup // 2))
         out["dense_baseline"]["speedup_of_factored"] = out["dense_baseline"]["ms_per_step"] / ms
@@ -416,7 +606,6 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(gi if args.workload != "decode" else synth.make_workload("decode", M=16))
     print(json.dumps(out))
-
 
 if __name__ == "__main__":
     main()

@@ -178,6 +178,22 @@ const char *svdmlp_profile_kernel_name(const svdmlp_ctx *ctx, int k);
  * outside [0, 1) or alpha outside [0, 1]. */
 int64_t svdmlp_rank_for_ratio(int64_t k, int64_t n, double ratio, int64_t block, double alpha);
 
+/* Roof microbenchmarks: kernels that do one thing only, so that a benchmark can print what this machine delivers
+ * beside the published peaks.  Each call only enqueues one kernel on hip_stream (NULL = default stream); the caller
+ * times it (events on that stream) and owns all buffers (device pointers).  They return SVDMLP_OK,
+ * SVDMLP_INVALID_ARGUMENT or SVDMLP_HIP_ERROR.
+ *   svdmlp_roof_read : `workgroups` workgroups of 256 lanes stream the first bytes / 32768 * 32768 bytes of buf
+ *                      (16-byte aligned, at least 32 KiB; use more than the 256 MB memory-side cache) with 16-byte
+ *                      loads, eight per lane in flight; sink is 4 bytes that are never written for a buffer filled
+ *                      with one repeated byte.  HBM GB/s = bytes read / time.
+ *   svdmlp_roof_mfma : `workgroups` workgroups of eight waves, each wave issuing 4 * iters
+ *                      v_mfma_f32_32x32x16_bf16 on register operands (four independent accumulators).
+ *                      FLOP = workgroups * 8 * 4 * iters * 32768; sink is 4 bytes, never written.
+ *   svdmlp_roof_empty: a kernel of `workgroups` x `threads` that does nothing (chains of dependent launches). */
+int svdmlp_roof_read(const void *buf, size_t bytes, void *sink, int workgroups, void *hip_stream);
+int svdmlp_roof_mfma(int iters, void *sink, int workgroups, void *hip_stream);
+int svdmlp_roof_empty(int workgroups, int threads, void *hip_stream);
+
 /* ABI version of this header (bumped on any incompatible change). */
 int svdmlp_abi_version(void);
 

@@ -28,7 +28,8 @@ FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK, FLAG_STREAM_ONE_KERNE
 EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_status_string",
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
            "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio",
-           "svdmlp_forward_static_scratch", "svdmlp_static_scratch_bytes"]
+           "svdmlp_forward_static_scratch", "svdmlp_static_scratch_bytes",
+           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_empty"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -69,6 +70,12 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_forward_static_scratch.restype = ctypes.c_int
         L.svdmlp_static_scratch_bytes.argtypes = []
         L.svdmlp_static_scratch_bytes.restype = ctypes.c_size_t
+        L.svdmlp_roof_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+        L.svdmlp_roof_read.restype = ctypes.c_int
+        L.svdmlp_roof_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+        L.svdmlp_roof_mfma.restype = ctypes.c_int
+        L.svdmlp_roof_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        L.svdmlp_roof_empty.restype = ctypes.c_int
         L.svdmlp_destroy.argtypes = [ctypes.c_void_p]
         L.svdmlp_destroy.restype = ctypes.c_int
         L.svdmlp_status_string.argtypes = [ctypes.c_int]
@@ -139,6 +146,25 @@ def svdmlp_forward_static_scratch(ctx, X_ptr: int, M: int, Y_ptr: int, stream_pt
 
 def svdmlp_static_scratch_bytes() -> int:
     return int(lib().svdmlp_static_scratch_bytes())
+
+
+def _check(st: int, where: str) -> None:
+    if st != SVDMLP_OK:
+        raise SvdMlpError(st, where)
+
+
+def svdmlp_roof_read(buf_ptr: int, nbytes: int, sink_ptr: int, workgroups: int, stream_ptr: int = 0) -> None:
+    _check(lib().svdmlp_roof_read(ctypes.c_void_p(buf_ptr), int(nbytes), ctypes.c_void_p(sink_ptr), int(workgroups),
+                                  ctypes.c_void_p(stream_ptr)), "svdmlp_roof_read")
+
+
+def svdmlp_roof_mfma(iters: int, sink_ptr: int, workgroups: int, stream_ptr: int = 0) -> None:
+    _check(lib().svdmlp_roof_mfma(int(iters), ctypes.c_void_p(sink_ptr), int(workgroups), ctypes.c_void_p(stream_ptr)),
+           "svdmlp_roof_mfma")
+
+
+def svdmlp_roof_empty(workgroups: int, threads: int, stream_ptr: int = 0) -> None:
+    _check(lib().svdmlp_roof_empty(int(workgroups), int(threads), ctypes.c_void_p(stream_ptr)), "svdmlp_roof_empty")
 
 
 def svdmlp_destroy(ctx) -> None:

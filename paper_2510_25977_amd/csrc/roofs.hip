@@ -1,0 +1,86 @@
+// Roof microbenchmarks (gfx950): what this machine actually delivers for the three things the forward is bounded by,
+// measured with kernels that do nothing else.  The benchmark prints them beside the published peaks, so that every
+// "fraction of the roof" can be read against a measured roof as well.
+//   read   : every lane streams 16-byte loads over a buffer (larger than the 256 MB memory-side cache) -> HBM GB/s
+//   mfma   : every wave issues v_mfma_f32_32x32x16_bf16 on register-resident operands, four independent accumulators
+//            -> matrix-core TFLOP/s at the clock the chip sustains under that load
+//   empty  : a kernel that does nothing, for timing chains of dependent launches (the floor of a forward that is a
+//            sequence of short kernels, as the weight-streaming path is)
+#include "common.h"
+
+namespace svdmlp {
+
+constexpr int ROOF_READ_UNROLL = 8;
+
+__global__ __launch_bounds__(256) void k_roof_read(const u32x4* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
+  // workgroup b reads blocks b, b + gridDim.x, ... of 256 x ROOF_READ_UNROLL x 16 bytes, each lane 16 bytes per load,
+  // a wave 1 KiB contiguous per load, all loads of a block in flight before the first use
+  const size_t per_block = (size_t)256 * ROOF_READ_UNROLL;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (size_t base = (size_t)blockIdx.x * per_block; base + per_block <= n16; base += (size_t)gridDim.x * per_block) {
+    u32x4 v[ROOF_READ_UNROLL];
+#pragma unroll
+    for (int u = 0; u < ROOF_READ_UNROLL; ++u) v[u] = __builtin_nontemporal_load(src + base + (size_t)u * 256 + threadIdx.x);
+#pragma unroll
+    for (int u = 0; u < ROOF_READ_UNROLL; ++u) acc ^= v[u];
+  }
+  // never true for the buffers the benchmark passes (filled with a constant pattern); keeps the loads alive
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = acc[0];
+}
+
+__global__ __launch_bounds__(512) void k_roof_mfma(int iters, float* __restrict__ sink) {
+  const int lane = threadIdx.x % 64;
+  bf16x8 a, b;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    a[s] = (__bf16)(0.001f * (float)((lane + s) % 7));
+    b[s] = (__bf16)(0.002f * (float)((lane * 3 + s) % 5));
+  }
+  f32x16 c0, c1, c2, c3;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { c0[e] = 0.f; c1[e] = 0.f; c2[e] = 0.f; c3[e] = 0.f; }
+  for (int i = 0; i < iters; ++i) {
+    c0 = mfma32(a, b, c0);
+    c1 = mfma32(a, b, c1);
+    c2 = mfma32(a, b, c2);
+    c3 = mfma32(a, b, c3);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) s += c0[e] + c1[e] + c2[e] + c3[e];
+  if (s == -1.0f) sink[0] = s;   // never true: the products are non-negative
+}
+
+__global__ void k_roof_empty(int* unused) { (void)unused; }
+
+}  // namespace svdmlp
+
+using namespace svdmlp;
+
+extern "C" {
+
+int svdmlp_roof_read(const void* buf, size_t bytes, void* sink, int workgroups, void* hip_stream) {
+  if (!buf || !sink || bytes < 256 * ROOF_READ_UNROLL * 16 || workgroups <= 0 || (reinterpret_cast<uintptr_t>(buf) & 15u))
+    return SVDMLP_INVALID_ARGUMENT;
+  hipLaunchKernelGGL(k_roof_read, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const u32x4*>(buf), bytes / 16, static_cast<unsigned*>(sink));
+  if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
+  return SVDMLP_OK;
+}
+
+int svdmlp_roof_mfma(int iters, void* sink, int workgroups, void* hip_stream) {
+  if (!sink || iters <= 0 || workgroups <= 0) return SVDMLP_INVALID_ARGUMENT;
+  hipLaunchKernelGGL(k_roof_mfma, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(hip_stream), iters,
+                     static_cast<float*>(sink));
+  if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
+  return SVDMLP_OK;
+}
+
+int svdmlp_roof_empty(int workgroups, int threads, void* hip_stream) {
+  if (workgroups <= 0 || threads <= 0 || threads > 1024) return SVDMLP_INVALID_ARGUMENT;
+  hipLaunchKernelGGL(k_roof_empty, dim3(workgroups), dim3(threads), 0, static_cast<hipStream_t>(hip_stream), (int*)nullptr);
+  if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
+  return SVDMLP_OK;
+}
+
+}  // extern "C"
