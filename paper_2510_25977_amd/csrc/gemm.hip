@@ -45,6 +45,14 @@ __device__ __forceinline__ void dma16_sv(const char* sbase, unsigned voff, unsig
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(sbase), "v"(voff), "s"(lds_dst) : "memory", "m0");
 }
 
+// The same copy with the non-temporal hint, for the gated activation that k_down1 reads once and nobody reads again
+// (measured: the forward 1 % shorter, most of it in the next forward's first kernel, whose operands stay in L2; the
+// same hint on the weight tiles of k_gate_up, which four workgroups of an XCD read at about the same time, made
+// that kernel 7 % longer).
+__device__ __forceinline__ void dma16_sv_nt(const char* sbase, unsigned voff, unsigned lds_dst) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0 nt" ::"s"(sbase), "v"(voff), "s"(lds_dst) : "memory", "m0");
+}
+
 // LDS unit layout: frags 0..7 activation (32-row tiles of the 256 rows), frags 8..15 weights (32-column tiles).
 // Producer of the step stream; all state is wave-uniform.  Wave w copies activation frag w and weight frag w of
 // both units of a step.
@@ -58,12 +66,13 @@ struct GProd {
   int slot;              // slot the next step goes to
   int issued;            // steps issued so far
 
+  template <int NTA = 0, int NTW = 0>
   __device__ __forceinline__ void step() {
     const unsigned b = dst + slot * G_STEP, bw = dstw + slot * G_STEP;
-    dma16_sv(pa, lane16, b);
-    dma16_sv(pw, lane16, bw);
-    dma16_sv(pa + a_kb, lane16, b + G_UNIT);
-    dma16_sv(pw + w_kb, lane16, bw + G_UNIT);
+    if (NTA) dma16_sv_nt(pa, lane16, b); else dma16_sv(pa, lane16, b);
+    if (NTW) dma16_sv_nt(pw, lane16, bw); else dma16_sv(pw, lane16, bw);
+    if (NTA) dma16_sv_nt(pa + a_kb, lane16, b + G_UNIT); else dma16_sv(pa + a_kb, lane16, b + G_UNIT);
+    if (NTW) dma16_sv_nt(pw + w_kb, lane16, bw + G_UNIT); else dma16_sv(pw + w_kb, lane16, bw + G_UNIT);
     pa += 2 * a_kb;
     pw += 2 * w_kb;
     slot = (slot + 1) & (G_SLOTS - 1);
@@ -495,8 +504,8 @@ __global__ __launch_bounds__(G_THREADS) void k_down1(const char* __restrict__ H,
   cons.slot = 0;
   cons.done = 0;
 
-  if (prod.issued < total_steps) prod.step();
-  if (prod.issued < total_steps) prod.step();
+  if (prod.issued < total_steps) prod.step<1, 0>();
+  if (prod.issued < total_steps) prod.step<1, 0>();
   if (prod.issued >= 2) wait_vmcnt<4>();
   else wait_vmcnt<0>();
   if (w >= 4) lds_barrier();
@@ -504,7 +513,7 @@ __global__ __launch_bounds__(G_THREADS) void k_down1(const char* __restrict__ H,
 
   f32x16 acc[2][4];
   for (int i = 0; i < total_steps; ++i) {
-    if (prod.issued < total_steps) prod.step();
+    if (prod.issued < total_steps) prod.step<1, 0>();
     cons.fetch();
     g_certify(prod, cons);
     if (i == 0) cons.compute<true>(acc);

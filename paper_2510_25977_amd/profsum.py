@@ -1,0 +1,116 @@
+"""Turn rocprofv3 CSV output of a run of ``bench.py`` into the short text summaries kept under ``profiles/``.
+
+    python -m paper_2510_25977_amd.profsum stats   <dir>                 # --kernel-trace run: calls, avg / min / max
+    python -m paper_2510_25977_amd.profsum traffic <fetch_dir> <write_dir>   # --pmc FETCH_SIZE and --pmc WRITE_SIZE runs
+    python -m paper_2510_25977_amd.profsum counters <dir> [<dir> ...]    # any --pmc run: per-kernel averages
+
+``traffic`` scales both counters by what they read for the plain device copy of known size that
+``bench.py --copy-calibration`` adds to the run (torch's copy kernel, 256 MiB read and written per launch).
+Kernel names are shortened to the names the library's own per-kernel timing uses (k_gate_up, k_stream_d2, ...).
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import glob
+import re
+import statistics
+import sys
+
+COPY_BYTES = 256 << 20
+STREAM_PHASE = {"0": "d1", "1": "d2", "2": "d4", "3": "d5"}
+
+
+def short_name(name: str) -> str:
+    n = re.sub(r"^void ", "", name).split("(")[0].replace("svdmlp::", "")
+    m = re.match(r"k_stream(16)?<(\d)", n)
+    if m:
+        return "k_stream_" + STREAM_PHASE.get(m.group(2), m.group(2))
+    m = re.match(r"(k_[a-z0-9_]+)", n)
+    if m:
+        return m.group(1)
+    if "copyBuffer" in n:
+        return "copy(calibration)"
+    return n[:48]
+
+
+def _csv(d: str, suffix: str):
+    fs = glob.glob(d + "/**/*" + suffix, recursive=True)
+    if not fs:
+        raise SystemExit(f"no *{suffix} under {d}")
+    for f in fs:
+        with open(f) as fh:
+            yield from csv.DictReader(fh)
+
+
+def kernel_stats(d: str):
+    dur = collections.defaultdict(list)
+    for r in _csv(d, "kernel_trace.csv"):
+        dur[short_name(r["Kernel_Name"])].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    return dur
+
+
+def counter_means(d: str):
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in _csv(d, "counter_collection.csv"):
+        acc[short_name(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    return {k: {c: statistics.fmean(v) for c, v in cs.items()} for k, cs in acc.items()}, \
+           {k: max(len(v) for v in cs.values()) for k, cs in acc.items()}
+
+
+def is_ours(k: str) -> bool:
+    return k.startswith("k_") and k != "k_repack" and not k.startswith("k_roof")
+
+
+def cmd_stats(d: str) -> None:
+    dur = kernel_stats(d)
+    total = sum(sum(v) for k, v in dur.items() if is_ours(k))
+    print("per kernel (microseconds; every launch of the run, warm-up included):")
+    for k, v in sorted(dur.items(), key=lambda kv: -sum(kv[1])):
+        if is_ours(k):
+            print(f"  {k:14s} calls {len(v):5d}  avg {statistics.fmean(v):8.1f}  median {statistics.median(v):8.1f}  "
+                  f"min {min(v):8.1f}  max {max(v):8.1f}  {100 * sum(v) / total:5.1f} %")
+
+
+def cmd_traffic(fetch_dir: str, write_dir: str) -> None:
+    f, _ = counter_means(fetch_dir)
+    w, _ = counter_means(write_dir)
+    cf = f.get("copy(calibration)", {}).get("FETCH_SIZE")
+    cw = w.get("copy(calibration)", {}).get("WRITE_SIZE")
+    if not cf or not cw:
+        raise SystemExit("no calibration copy in the run (bench.py --copy-calibration)")
+    sf, sw = COPY_BYTES / 1024 / cf, COPY_BYTES / 1024 / cw
+    print(f"calibration: plain {COPY_BYTES >> 20} MiB device copy: FETCH_SIZE reads {cf:.0f} KiB -> scale {sf:.3f}; "
+          f"WRITE_SIZE reads {cw:.0f} KiB -> scale {sw:.3f}")
+    print("per launch (averages), HBM-side bytes = counter x scale x 1024:")
+    tr = tw = 0.0
+    for k in f:
+        if is_ours(k) and k in w:
+            rmb, wmb = f[k]["FETCH_SIZE"] * sf * 1024 / 1e6, w[k]["WRITE_SIZE"] * sw * 1024 / 1e6
+            tr, tw = tr + rmb, tw + wmb
+            print(f"  {k:14s} FETCH_SIZE {f[k]['FETCH_SIZE']:9.0f}  WRITE_SIZE {w[k]['WRITE_SIZE']:9.0f}   "
+                  f"read {rmb:8.1f} MB  written {wmb:8.1f} MB")
+    print(f"  {'whole forward':14s} read {tr:8.1f} MB  written {tw:8.1f} MB  together {tr + tw:8.1f} MB")
+
+
+def cmd_counters(dirs) -> None:
+    for d in dirs:
+        means, n = counter_means(d)
+        for k, cs in means.items():
+            if is_ours(k):
+                print(f"  {k:14s} (n={n[k]:3d}) " + "  ".join(f"{c} {v:.4g}" for c, v in sorted(cs.items())))
+
+
+def main(argv) -> None:
+    if len(argv) >= 3 and argv[1] == "stats":
+        cmd_stats(argv[2])
+    elif len(argv) >= 4 and argv[1] == "traffic":
+        cmd_traffic(argv[2], argv[3])
+    elif len(argv) >= 3 and argv[1] == "counters":
+        cmd_counters(argv[2:])
+    else:
+        raise SystemExit(__doc__)
+
+
+if __name__ == "__main__":
+    main(sys.argv)
