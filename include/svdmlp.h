@@ -73,8 +73,11 @@ enum {
                                            per-wave register budget); slower than the four launches as measured */
   SVDMLP_FLAG_TILED_FUSED = 1u << 4,    /* MFMA-tiled path: keep the gated activation in registers (one fused kernel)
                                            instead of staging it through the workspace */
-  SVDMLP_FLAG_TILE_128 = 1u << 5        /* kind LINEAR: both products on 128 x 128 tiles whatever the planner would pick
+  SVDMLP_FLAG_TILE_128 = 1u << 5,       /* kind LINEAR: both products on 128 x 128 tiles whatever the planner would pick
                                            (the small-block point of a block-size comparison, paper Table 3) */
+  SVDMLP_FLAG_PLAN_ROOM = 1u << 6       /* size the workspace for every candidate of the planner, not only its choices,
+                                           so that svdmlp_force_plan can run any of them (tuning and tests; the
+                                           split-K partial buffers grow to 8 / 32 ranges) */
 };
 
 typedef struct {
@@ -141,11 +144,25 @@ const char *svdmlp_status_string(int status);
 
 /* Host only, no device needed: writes into buf (NUL-terminated, at most buf_bytes) one line that names the path a
  * forward of M rows on a context of this description takes, its kernels in launch order and how each is cut over
- * the chip (tile shape, number of tiles, contraction ranges, persistent workgroups): the planner's counterpart of the
- * block-size choice of the paper's Sec. 4.2.2, evaluated for a 256-CU device.  Returns SVDMLP_OK, the status
+ * the chip (tile shape, number of tiles, contraction ranges, persistent workgroups), and for every stage that leaves a
+ * choice the time the planner's cost model gives the chosen candidate (est_us) and the closest alternatives
+ * (kernel/ranges=microseconds): the planner's counterpart of the block-size choice of the paper's Sec. 4.2.2,
+ * evaluated for a 256-CU device.  Returns SVDMLP_OK, the status
  * svdmlp_create would return for desc (the workspace fields are not looked at), or SVDMLP_INVALID_ARGUMENT if M is not
  * in 1..max_M or the line does not fit. */
 int svdmlp_describe(const svdmlp_desc *desc, int64_t M, char *buf, size_t buf_bytes);
+
+/* Override the planner for later forwards of this context on the MFMA-tiled path (bf16 only): the counterpart of
+ * trying another block size in the paper's Table 3.  0 leaves a choice to the planner.
+ *   first_kernel : 1 = first product on 128 x 128 tiles (k_s1), 2 = on 256 x 256 tiles (k_in)
+ *   first_ranges : ranges its contraction over d is cut into, 1 .. 8 (needs first_kernel)
+ *   down_ranges  : ffn ranges of the first phase of the down projection (k_down1), 1 .. 32
+ *   out_kernel   : 1 = last product on 256 x 256 tiles (k_out), 2 = on 128 x 128 tiles (k_s5)
+ * A candidate the kernels cannot run at a forward's extents (svdmlp_describe lists the valid ones) falls back to the
+ * planner's choice; one whose partial sums do not fit the workspace makes svdmlp_forward return SVDMLP_HIP_ERROR
+ * (create the context with SVDMLP_FLAG_PLAN_ROOM to have room for all).  Returns SVDMLP_OK, SVDMLP_INVALID_ARGUMENT
+ * (values out of range) or SVDMLP_UNSUPPORTED (fp32 context). */
+int svdmlp_force_plan(svdmlp_ctx *ctx, int32_t first_kernel, int32_t first_ranges, int32_t down_ranges, int32_t out_kernel);
 
 /* The hipError_t (as int) of the last failing HIP call made for this context (0 if none). */
 int svdmlp_last_hip_error(const svdmlp_ctx *ctx);

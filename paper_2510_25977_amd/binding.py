@@ -24,12 +24,14 @@ SVDMLP_OK = 0
 SVDMLP_INVALID_ARGUMENT, SVDMLP_UNSUPPORTED, SVDMLP_WORKSPACE_TOO_SMALL, SVDMLP_HIP_ERROR, SVDMLP_NO_DEVICE = -1, -2, -3, -4, -5
 SVDMLP_SCRATCH_TOO_SMALL = -6
 FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK, FLAG_STREAM_ONE_KERNEL, FLAG_TILED_FUSED, FLAG_TILE_128 = 1, 2, 4, 8, 16, 32
+FLAG_PLAN_ROOM = 64
+FIRST_S1, FIRST_IN, OUT_256, OUT_128 = 1, 2, 1, 2
 
 EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_destroy", "svdmlp_status_string",
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
            "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio",
            "svdmlp_forward_static_scratch", "svdmlp_static_scratch_bytes",
-           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_empty"]
+           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_empty", "svdmlp_force_plan"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -76,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_roof_mfma.restype = ctypes.c_int
         L.svdmlp_roof_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         L.svdmlp_roof_empty.restype = ctypes.c_int
+        L.svdmlp_force_plan.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        L.svdmlp_force_plan.restype = ctypes.c_int
         L.svdmlp_destroy.argtypes = [ctypes.c_void_p]
         L.svdmlp_destroy.restype = ctypes.c_int
         L.svdmlp_status_string.argtypes = [ctypes.c_int]
@@ -116,7 +120,7 @@ def svdmlp_rank_for_ratio(k: int, n: int, ratio: float, block: int = 128, alpha:
 
 
 def svdmlp_describe(desc: svdmlp_desc, M: int) -> str:
-    buf = ctypes.create_string_buffer(1024)
+    buf = ctypes.create_string_buffer(4096)
     st = lib().svdmlp_describe(ctypes.byref(desc), int(M), buf, len(buf))
     if st != SVDMLP_OK:
         raise SvdMlpError(st, "svdmlp_describe")
@@ -165,6 +169,11 @@ def svdmlp_roof_mfma(iters: int, sink_ptr: int, workgroups: int, stream_ptr: int
 
 def svdmlp_roof_empty(workgroups: int, threads: int, stream_ptr: int = 0) -> None:
     _check(lib().svdmlp_roof_empty(int(workgroups), int(threads), ctypes.c_void_p(stream_ptr)), "svdmlp_roof_empty")
+
+
+def svdmlp_force_plan(ctx, first_kernel: int = 0, first_ranges: int = 0, down_ranges: int = 0, out_kernel: int = 0) -> None:
+    _check(lib().svdmlp_force_plan(ctx, int(first_kernel), int(first_ranges), int(down_ranges), int(out_kernel)),
+           "svdmlp_force_plan")
 
 
 def svdmlp_destroy(ctx) -> None:

@@ -47,6 +47,7 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   p->rd_in = p->rd;
   p->ffn_in = p->ffn;
   p->kind = de->kind; p->dtype = de->dtype; p->flags = de->flags;
+  const bool room = (de->flags & SVDMLP_FLAG_PLAN_ROOM) != 0;
 
   if (de->dtype == SVDMLP_F32) {
     // fp32 intermediates: T [M, 2r] (LINEAR: [M, r]), H [M, ffn], Td [M, rd]
@@ -73,17 +74,16 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
     p->off_wU = take((size_t)r * d * 2);
     p->off_wVd = take((size_t)n * r * 2);
     p->off_T = take((size_t)p->Mpad * r * 2);
-    // fp32 tiles of T per range of d when the first stage cuts its contraction (few tiles)
-    int64_t prow = 0;
-    for (int64_t mt = 1; mt <= p->Mpad / 128; ++mt) {
-      const int64_t s1 = s1_splits(mt, r / 128, d);
-      if (s1 > 1 && s1 * mt * 128 > prow) prow = s1 * mt * 128;
+    // fp32 tiles of T per range of d when the first stage cuts its contraction (few tiles): the largest the planner
+    // picks for any row count up to max_M (with SVDMLP_FLAG_PLAN_ROOM: room for every candidate)
+    size_t pbytes = 0;
+    for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {
+      const StageChoice ch = choose_first(mt * 256, d, r, linear_on_small_tiles(*p), nullptr);
+      const int S = room ? MAX_FIRST_RANGES : ch.ranges;
+      if (S > 1 && (size_t)S * mt * 256 * r * 4 > pbytes) pbytes = (size_t)S * mt * 256 * r * 4;
     }
-    for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {   // ... or k_in does
-      const int64_t si = in_splits(mt * 256, d, r);
-      if (si > 1 && si * mt * 256 > prow) prow = si * mt * 256;
-    }
-    p->off_Tdp = take((size_t)prow * r * 4);
+    p->part_bytes = pbytes;
+    p->off_Tdp = take(pbytes);
     p->off_part = take((size_t)8 << 20);              // streaming path: split-K partial tiles
     p->off_cnt = take(CNT_BYTES);                     // ... and its tickets
     p->total_bytes = off;
@@ -119,7 +119,8 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   p->off_wUd = take((size_t)rd * ffn * 2);
   p->off_wVd = take((size_t)d * rd * 2);
   p->off_T = take((size_t)p->Mpad * 2 * r * 2);
-  // split-K partial sums of Td: rows = splits(M) * padded M, maximised over M <= max_M
+  // split-K partial sums of Td: ranges(M) * padded M rows, maximised over M <= max_M (with SVDMLP_FLAG_PLAN_ROOM:
+  // room for every candidate of the planner, so that a caller can force and time each of them)
   int64_t rows = 0;
   const int64_t nchunks = ffn / 64;
   for (int64_t mt = 1; mt <= p->Mpad / 128; ++mt) {
@@ -128,20 +129,18 @@ int make_plan(const svdmlp_desc* de, Plan* p) {
   }
   if (staged_supported(rd, ffn))
     for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {
-      int64_t rws = (int64_t)gemm_splits(mt, rd / 256, ffn / 32) * mt * 256;
+      const int sp = room ? MAX_DOWN_RANGES : choose_down(mt * 256, rd, ffn, nullptr).ranges;
+      int64_t rws = (int64_t)sp * mt * 256;
       if (rws > rows) rows = rws;
     }
   p->part_rows = rows;
-  // the same buffer first holds the fp32 tiles of T per range of d when k_s1 cuts its contraction (few tiles)
+  // the same buffer first holds the fp32 tiles of T per range of d when the first stage cuts its contraction (few tiles)
   size_t part_bytes = (size_t)rows * rd * 4;
-  for (int64_t mt = 1; mt <= p->Mpad / 128; ++mt) {
-    const int64_t s1 = s1_splits(mt, 2 * r / 128, d);
-    if (s1 > 1 && (size_t)(s1 * mt * 128) * 2 * r * 4 > part_bytes) part_bytes = (size_t)(s1 * mt * 128) * 2 * r * 4;
+  for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {
+    const int S = room ? MAX_FIRST_RANGES : choose_first(mt * 256, d, 2 * r, false, nullptr).ranges;
+    if (S > 1 && (size_t)S * mt * 256 * 2 * r * 4 > part_bytes) part_bytes = (size_t)S * mt * 256 * 2 * r * 4;
   }
-  for (int64_t mt = 1; mt <= p->Mpad / 256; ++mt) {   // ... or k_in does
-    const int64_t si = in_splits(mt * 256, d, 2 * r);
-    if (si > 1 && (size_t)(si * mt * 256) * 2 * r * 4 > part_bytes) part_bytes = (size_t)(si * mt * 256) * 2 * r * 4;
-  }
+  p->part_bytes = part_bytes;
   p->off_Tdp = take(part_bytes);
   p->off_Td = take((size_t)p->Mpad * rd * 2);
   p->off_H = take((size_t)STREAM_MAX_M * ffn * 2);  // streaming path: the ffn-wide activation of its rows
@@ -207,16 +206,42 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
     }
   };
   const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
-  auto first_stage = [&](int64_t ncols) {
-    const int S = linear_on_small_tiles(p) ? 0 : in_splits(M, p.d, ncols);
-    if (S >= 1) {
-      put(" k_in[tile=256x256 tiles=%d ranges=%d]", MT256 * (int)(ncols / 256), S);
-      if (S > 1) put(" k_reduce");
-    } else {
-      const int PT = (int)(ncols / 128), S1 = s1_splits(MT128, PT, p.d);
-      put(" k_s1[tile=128x128 tiles=%d ranges=%d]", MT128 * PT, S1);
-      if (S1 > 1) put(" k_reduce");
+  // every candidate of a stage with the time the planner's cost model gives it (microseconds), the chosen one first
+  auto put_scores = [&](const StageCandidate* c, int n, const StageChoice& ch, const char* const* kname) {
+    put(" est_us=%.1f alternatives:", ch.est_us);
+    // the five cheapest of the others, cheapest first
+    bool used[64] = {};
+    for (int shown = 0; shown < 5; ++shown) {
+      int b = -1;
+      for (int i = 0; i < n && i < 64; ++i) {
+        if (used[i] || (c[i].kernel == ch.kernel && c[i].ranges == ch.ranges)) continue;
+        if (b < 0 || c[i].est_us < c[b].est_us) b = i;
+      }
+      if (b < 0) break;
+      used[b] = true;
+      put(" %s/%d=%.1f", kname[c[b].kernel], c[b].ranges, c[b].est_us);
     }
+    put("]");
+  };
+  static const char* const first_names[3] = {"", "s1", "in"};
+  static const char* const down_names[1] = {"ranges"};
+  static const char* const out_names[3] = {"", "out256", "out128"};
+  auto first_stage = [&](int64_t ncols) {
+    const StageChoice ch = choose_first(M, p.d, ncols, linear_on_small_tiles(p), nullptr);
+    StageCandidate c[2 * MAX_FIRST_RANGES];
+    const int n = linear_on_small_tiles(p) ? 0 : first_candidates((M + 255) / 256 * 256, p.d, ncols, c, 2 * MAX_FIRST_RANGES);
+    if (ch.kernel == FIRST_IN) put(" k_in[tile=256x256 tiles=%d ranges=%d", MT256 * (int)(ncols / 256), ch.ranges);
+    else put(" k_s1[tile=128x128 tiles=%d ranges=%d", MT128 * (int)(ncols / 128), ch.ranges);
+    put_scores(c, n, ch, first_names);
+    if (ch.ranges > 1) put(" k_reduce");
+  };
+  auto last_stage = [&](int64_t n_out, int64_t k) {
+    const StageChoice ch = choose_out(M, n_out, k, linear_on_small_tiles(p), nullptr);
+    StageCandidate c[2];
+    const int n = linear_on_small_tiles(p) ? 0 : out_candidates(M, n_out, k, c, 2);
+    if (ch.kernel == OUT_256) put(" k_out[tile=256x256 tiles=%d", MT256 * (int)(n_out / 256));
+    else put(" k_s5[tile=128x128 tiles=%d", MT128 * (int)(n_out / 128));
+    put_scores(c, n, ch, out_names);
   };
   if (p.dtype == SVDMLP_F32) {
     put("path=1 fp32-debug:%s", p.kind == SVDMLP_GATED ? " k_f32_gemm x5 (SiLU-gate epilogue in the third)" : " k_f32_gemm x2");
@@ -236,8 +261,7 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
   } else if (p.kind == SVDMLP_LINEAR) {
     put("path=6 bf16-linear:");
     first_stage(p.r);
-    if (linear_out_uses_256(M, p.ffn) && !linear_on_small_tiles(p)) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.ffn / 256));
-    else put(" k_s5[tile=128x128 tiles=%d]", MT128 * (int)(p.ffn / 128));
+    last_stage(p.ffn, p.r);
   } else {
     bool stream_path = M <= STREAM_MAX_M;
     if (p.flags & SVDMLP_FLAG_FORCE_TILED) stream_path = false;
@@ -266,10 +290,13 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
       const GuPlan g = gate_up_plan(MT256, p.ffn, p.r, 256);
       put(" k_gate_up[tile=256x256 tiles=%d workgroups=%d full=%d halves=%d xcd_grid=%dx%d]", g.ntiles, g.G, g.nfull,
           g.halves ? 2 * g.rem : 0, g.ngm, g.ngm ? 8 / g.ngm : 0);
-      const int splits = gemm_splits(MT256, p.rd / 256, p.ffn / 32);
-      put(" k_down1[tile=256x256 tiles=%d ranges=%d] k_reduce", MT256 * (int)(p.rd / 256), splits);
-      if (out_uses_256(M, p.d)) put(" k_out[tile=256x256 tiles=%d]", MT256 * (int)(p.d / 256));
-      else put(" k_s5[tile=128x128 tiles=%d]", MT128 * (int)(p.d / 128));
+      const StageChoice dn = choose_down(M, p.rd, p.ffn, nullptr);
+      StageCandidate dc[MAX_DOWN_RANGES];
+      const int dn_n = down_candidates(M, p.rd, p.ffn, dc, MAX_DOWN_RANGES);
+      put(" k_down1[tile=256x256 tiles=%d ranges=%d", MT256 * (int)(p.rd / 256), dn.ranges);
+      put_scores(dc, dn_n, dn, down_names);
+      put(" k_reduce");
+      last_stage(p.d, p.rd);
     } else {
       put("path=2 bf16-tiled-fused:");
       first_stage(2 * p.r);
@@ -393,6 +420,18 @@ int svdmlp_forward_static_scratch(svdmlp_ctx* ctx, const void* X, int64_t M, voi
 }
 
 size_t svdmlp_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int svdmlp_force_plan(svdmlp_ctx* ctx, int32_t first_kernel, int32_t first_ranges, int32_t down_ranges, int32_t out_kernel) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return SVDMLP_INVALID_ARGUMENT;
+  if (first_kernel < 0 || first_kernel > FIRST_IN || out_kernel < 0 || out_kernel > OUT_128) return SVDMLP_INVALID_ARGUMENT;
+  if (first_ranges < 0 || first_ranges > MAX_FIRST_RANGES || down_ranges < 0 || down_ranges > MAX_DOWN_RANGES)
+    return SVDMLP_INVALID_ARGUMENT;
+  if (first_ranges && !first_kernel) return SVDMLP_INVALID_ARGUMENT;   // ranges belong to a kernel
+  if (c->plan.dtype != SVDMLP_BF16) return SVDMLP_UNSUPPORTED;
+  c->force = PlanForce{first_kernel, first_ranges, down_ranges, out_kernel};
+  return SVDMLP_OK;
+}
 
 static void prof_release(Ctx* c) {
   Prof& p = c->prof;

@@ -145,6 +145,7 @@ struct Plan {
   size_t total_bytes;
   int64_t Mpad;       // max_M rounded up to 256
   int64_t part_rows;  // rows reserved for split-K partial sums of Td
+  size_t part_bytes;  // bytes of the partial-sum buffer at off_Tdp
   // f32: element offsets
   size_t f32_T, f32_H, f32_Td;
 };
@@ -153,12 +154,28 @@ int make_plan(const svdmlp_desc* desc, Plan* plan);  // returns a status code
 
 // number of ffn splits the tiled path uses for a given number of 128-row tiles
 int tiled_splits(int64_t mtiles128, int64_t nchunks);
-// number of ranges of d the first stage (k_s1) uses for mt128 x pt tiles of 128 x 128
-int s1_splits(int64_t mt128, int64_t pt, int64_t d);
 // extents the staged tiled path (gemm.hip) handles
 bool staged_supported(int64_t rd, int64_t ffn);
-// number of ffn ranges k_down1 uses for a given number of 256-row tiles, 256-wide rank tiles and unit pairs
-int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps);
+
+// ---- the planner's choices per stage of the tiled path (planner.hip) -----------------------------
+enum { FIRST_S1 = 1, FIRST_IN = 2 };   // first product on 128 x 128 tiles (k_s1) or 256 x 256 tiles (k_in)
+enum { OUT_256 = 1, OUT_128 = 2 };     // last product on 256 x 256 tiles (k_out) or 128 x 128 tiles (k_s5)
+// A caller's override of the choices (svdmlp_force_plan); 0 = leave it to the planner.
+struct PlanForce { int first_kernel, first_ranges, down_ranges, out_kernel; };
+struct StageChoice { int kernel, ranges; double est_us; };
+// One candidate of a stage with the time the cost model gives it; valid = the kernels take it at these extents.
+struct StageCandidate { int kernel, ranges; double est_us; bool valid; };
+bool first_valid(int kernel, int S, int64_t M, int64_t d, int64_t ncols);
+bool down_valid(int splits, int64_t mt256, int64_t qt, int64_t nsteps);
+// ncols = rank columns of the first product (2 r gated, r linear); small_only: kind LINEAR with SVDMLP_FLAG_TILE_128
+int first_candidates(int64_t M, int64_t d, int64_t ncols, StageCandidate* out, int cap);
+StageChoice choose_first(int64_t M, int64_t d, int64_t ncols, bool small_only, const PlanForce* f);
+int down_candidates(int64_t M, int64_t rd, int64_t ffn, StageCandidate* out, int cap);
+StageChoice choose_down(int64_t M, int64_t rd, int64_t ffn, const PlanForce* f);
+// n = row length of the output, k = its contraction length
+int out_candidates(int64_t M, int64_t n, int64_t k, StageCandidate* out, int cap);
+StageChoice choose_out(int64_t M, int64_t n, int64_t k, bool small_only, const PlanForce* f);
+constexpr int MAX_FIRST_RANGES = 8, MAX_DOWN_RANGES = 32;
 
 // ---- launchers (each returns hipError_t as int; 0 = success) ---------------------------------
 struct Ctx;
@@ -171,19 +188,11 @@ GuPlan gate_up_plan(int MT256, int64_t ffn, int64_t r, int ncu);
 int launch_gate_up(const Ctx* c, int MT256, hipStream_t st);
 int launch_down1(const Ctx* c, int MT256, int splits, hipStream_t st);
 int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st);
-// Whether a last product with rows of length n (Y = Td Vd of the gated forward, O = T V of the single layer) runs on
-// k_out (256 x 256 tiles) rather than k_s5 (128 x 128): the wide tile needs n % 256 == 0 and more than 64 tiles, a
-// quarter of the CUs (measured at n = 2048 .. 16384: below that the small kernel's four times as many workgroups
-// are up to 30 % faster, at 112-128 tiles the two are level, beyond the wide tile wins).
-inline bool out_uses_256(int64_t M, int64_t n) { return n % 256 == 0 && ((M + 255) / 256) * (n / 256) > 64; }
-inline bool linear_out_uses_256(int64_t M, int64_t n) { return out_uses_256(M, n); }
 // kind LINEAR with SVDMLP_FLAG_TILE_128: k_s1 and k_s5 whatever the row count
 inline bool linear_on_small_tiles(const Plan& p) { return p.kind == SVDMLP_LINEAR && (p.flags & SVDMLP_FLAG_TILE_128) != 0; }
 int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
-bool in_supported(int64_t M, int64_t d, int64_t ncols);
-int in_splits(int64_t M, int64_t d, int64_t ncols);
 int launch_reduce(const Ctx* c, const float* part, char* out, int splits, int MT32, int nq, hipStream_t st);
-int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_strip, hipStream_t st);
+int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_strip, int S, hipStream_t st);
 int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 int launch_out_generic(const Ctx* c, const char* act, const char* w, int64_t M, void* Y, int MT256, int64_t n, int64_t k,
                        hipStream_t st);
@@ -232,6 +241,7 @@ struct Ctx {
   int n_cus = 0;                                 // compute units of the device the context was created on
   int device = -1;                               // ... and its ordinal
   char* static_scratch = nullptr;                // that device's copy of the library's static scratch array
+  PlanForce force = {0, 0, 0, 0};                // svdmlp_force_plan
   mutable Prof prof;
 };
 

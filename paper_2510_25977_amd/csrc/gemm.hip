@@ -734,42 +734,26 @@ __global__ __launch_bounds__(G_THREADS) void k_out(const char* __restrict__ Td, 
   }
 }
 
-int gemm_splits(int64_t mt256, int64_t qt, int64_t nsteps) {
-  // at most one workgroup per CU on 256 CUs (a few workgroups too many would cost a second round); every range keeps at
-  // least four steps
-  int64_t s = 256 / (mt256 * qt);
-  if (s > nsteps / 4) s = nsteps / 4;
-  // more ranges mean more fp32 partial tiles to write and add; with very few tiles they still pay
-  const int64_t cap = mt256 * qt <= 4 ? 32 : 16;
-  if (s > cap) s = cap;
-  // One 256-wide rank tile (down rank up to 256): the kernel reads the whole activation for half the arithmetic and is
-  // bound by HBM bytes, a good part of them its own partial tiles.  Then as few ranges as still give 128 workgroups
-  // (which together can pull in what HBM delivers), but not fewer than eight (r = r_down = 256, M = 4096: the forward
-  // 172 -> 163 us with 8 instead of 16 ranges; with fewer than 128 workgroups it loses).
-  if (qt == 1) {
-    int64_t need = (128 + mt256 - 1) / mt256;
-    if (need < 8) need = 8;
-    if (s > need) s = need;
-  }
-  if (s < 1) s = 1;
-  return (int)s;
-}
-
 GuPlan gate_up_plan(int MT256, int64_t ffn, int64_t r, int ncu) {
   GuPlan g;
   const int NT = (int)(ffn / 256);
-  // XCD grid: ngm row groups x 8 / ngm column groups, mx = MT256 / ngm row tiles per XCD.  The fewest row groups (most
-  // row tiles per XCD, fewest XCDs streaming the same weight columns) whose strips (256 x 2r bf16 per row tile) fit in
-  // half of an XCD's 4 MiB L2; if none fits, the most row groups that divide the tiles; plain order if nothing divides.
+  // XCD grid: ngm row groups x 8 / ngm column groups, mx = MT256 / ngm row tiles per XCD.  The 32 workgroups of an XCD
+  // work on mx row tiles x 32 / mx column tiles at a time and march through the contraction together, so per
+  // contraction block the XCD's L2 fetches mx strips' and 32 / mx weight tiles' worth of operands for 64 operands'
+  // worth of copies: the grid with the smallest mx + 32 / mx has the fewest L2 misses (4 x 8 or 8 x 4: 19 %).  A round
+  // touches more than an L2 holds at any rank from 512 on, so nothing is kept from one round to the next and the size
+  // of the strips does not enter (measured at r = 1024: 8 x 1 grid, whose strips fit L2, reads 537 MB, 4 x 2 reads
+  // less and is faster).  Ties go to more row groups (smaller strips per XCD).  Plain order if nothing divides.
   g.mx = 0;
   g.ngm = 0;
-  const long long strip = 256LL * 2 * r * 2;
-  for (int gr = 1; gr <= 8; gr *= 2) {
+  double best = 1e30;
+  for (int gr = 8; gr >= 1; gr /= 2) {
     if (MT256 % gr || NT % (8 / gr)) continue;
-    g.mx = MT256 / gr;
-    g.ngm = gr;
-    if ((long long)g.mx * strip <= (2LL << 20)) break;
+    const int mx = MT256 / gr;
+    const double a = mx < 32 ? mx : 32, cost = a + 32.0 / a;
+    if (cost < best) { best = cost; g.mx = mx; g.ngm = gr; }
   }
+  (void)r;
   if (ncu <= 0) ncu = 256;
   g.ntiles = MT256 * NT;
   g.G = g.ntiles < ncu ? g.ntiles : ncu;  // persistent: one workgroup per CU
@@ -826,36 +810,13 @@ int launch_out(const Ctx* c, int64_t M, void* Y, int MT256, hipStream_t st) {
   return launch_out_generic(c, c->ws + p.off_Td, c->ws + p.off_wVd, M, Y, MT256, p.d, p.rd, st);
 }
 
-// ncols = rank columns of the product (2 r gated, r linear); r_strip = columns per strip of T.
-// 0: k_s1 does the first stage; 1: k_in over the whole contraction; S > 1: k_in with the contraction cut into S ranges.
-// The choice is by estimated time, from measured figures: a round of k_s1 (one 128 x 128 tile per CU) over a
-// contraction of 4096 takes 45 us, a round of k_in (256 x 256) over 2048 takes 50 us (four times the work in 2.2 times
-// the time, which is why it is preferred when its tiles fill the chip); a cut contraction adds a launch (5 us) and
-// the fp32 tiles of every range, written and read back once at about 5 TB/s.
-int in_splits(int64_t M, int64_t d, int64_t ncols) {
-  M = (M + 255) / 256 * 256;   // the answer depends on the number of row tiles only (the workspace is sized from it)
-  // 32-bit byte offsets into X
-  if (ncols % 256 || d % 64 || M * d * 2 >= (int64_t(1) << 32)) return 0;
-  const int64_t wgs1 = (M / 128) * (ncols / 128);
-  const int64_t S1 = s1_splits(M / 128, ncols / 128, d);
-  auto cut_cost = [&](int64_t S) { return S > 1 ? 5.0 + (double)S * M * ncols * 8.0 / 5.0e6 : 0.0; };
-  const double t_s1 = (double)((wgs1 * S1 + 255) / 256) * 45.0 * ((double)d / S1) / 4096.0 + cut_cost(S1);
-  const int64_t tiles = (M / 256) * (ncols / 256);
-  int best = 0;
-  double best_t = t_s1;
-  for (int64_t S = 1; S <= 8; ++S) {
-    if (d / S < 512) break;   // at least eight steps per range
-    const double t = (double)((tiles * S + 255) / 256) * 50.0 * ((double)d / S) / 2048.0 + cut_cost(S);
-    if (t < best_t) { best_t = t; best = (int)S; }
-  }
-  return best;
-}
-bool in_supported(int64_t M, int64_t d, int64_t ncols) { return in_splits(M, d, ncols) >= 1; }
-int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_strip, hipStream_t st) {
+// ncols = rank columns of the product (2 r gated, r linear); r_strip = columns per strip of T; S = ranges of d
+// (S > 1: fp32 tiles per range, added by k_reduce).
+int launch_in(const Ctx* c, const void* X, int64_t M, int64_t ncols, int64_t r_strip, int S, hipStream_t st) {
   const Plan& p = c->plan;
   const int MT = (int)((M + 255) / 256), PT = (int)(ncols / 256);
-  const int S = in_splits(M, p.d, ncols);
-  if (S < 1) return (int)hipErrorInvalidValue;
+  if (!first_valid(FIRST_IN, S, M, p.d, ncols)) return (int)hipErrorInvalidValue;
+  if (S > 1 && (size_t)S * MT * 256 * ncols * 4 > p.part_bytes) return (int)hipErrorInvalidValue;
   hipLaunchKernelGGL(k_in, dim3(MT * PT * S), dim3(G_THREADS), 0, st, (const uint16_t*)X, (int)M, (int)p.d, c->ws + p.off_wU,
                      (int)r_strip, c->ws + p.off_T, MT, PT, S, reinterpret_cast<float*>(c->ws + p.off_Tdp));
   int e = (int)hipGetLastError();

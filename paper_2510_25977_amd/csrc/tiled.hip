@@ -644,16 +644,6 @@ static int launch_fused(const Ctx* c, int MT128, int splits, int QS, hipStream_t
   return (int)hipGetLastError();
 }
 
-// Ranges of d for k_s1: fill the chip when the 128 x 128 tiles alone do not, keeping at least 8 steps per range.
-int s1_splits(int64_t mt128, int64_t pt, int64_t d) {
-  const int64_t wgs = mt128 * pt;
-  if (wgs >= 160) return 1;
-  int64_t s = 256 / wgs;
-  if (s > d / 512) s = d / 512;
-  if (s > 8) s = 8;
-  return s < 1 ? 1 : (int)s;
-}
-
 int launch_reduce(const Ctx* c, const float* part, char* out, int splits, int MT32, int nq, hipStream_t st) {
   (void)c;
   const long long threads = (long long)MT32 * nq * 2 * 64;
@@ -663,14 +653,17 @@ int launch_reduce(const Ctx* c, const float* part, char* out, int splits, int MT
   return (int)hipGetLastError();
 }
 
-// First stage T = X [Ug|Uu] (ncols = 2 r_strip rank columns in two strips): k_in when its 256 x 256 tiles fill the
-// chip, else k_s1, with its contraction cut into ranges (+ k_reduce) when there are few tiles.
+// First stage T = X [Ug|Uu] (ncols = 2 r_strip rank columns in two strips): the planner's choice between k_in
+// (256 x 256 tiles) and k_s1 (128 x 128), either with its contraction cut into ranges (+ k_reduce) when there are few
+// tiles.
 static int first_stage(const Ctx* c, const void* X, int64_t M, int64_t r_strip, hipStream_t st) {
   const Plan& p = c->plan;
   char* ws = c->ws;
-  if (!linear_on_small_tiles(p) && in_supported(M, p.d, 2 * r_strip)) return launch_in(c, X, M, 2 * r_strip, r_strip, st);
+  const StageChoice ch = choose_first(M, p.d, 2 * r_strip, linear_on_small_tiles(p), &c->force);
+  if (ch.kernel == FIRST_IN) return launch_in(c, X, M, 2 * r_strip, r_strip, ch.ranges, st);
   const int MT128 = (int)((M + 127) / 128), PT = (int)(2 * r_strip / 128);
-  const int S = s1_splits(MT128, PT, p.d);
+  const int S = ch.ranges;
+  if (S > 1 && (size_t)S * MT128 * 128 * 2 * r_strip * 4 > p.part_bytes) return (int)hipErrorInvalidValue;
   hipLaunchKernelGGL(k_s1, dim3(MT128 * PT * S), dim3(256), 0, st, (const uint16_t*)X, (int)M, (int)p.d, ws + p.off_wU,
                      (int)r_strip, ws + p.off_T, PT, S, reinterpret_cast<float*>(ws + p.off_Tdp), MT128);
   int e = (int)hipGetLastError();
@@ -690,7 +683,8 @@ static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st)
   e = launch_gate_up(c, MT256, st);
   prof_mark(c, ps, 1, 1, st);
   if (e) return e;
-  const int splits = gemm_splits(MT256, p.rd / 256, p.ffn / 32);
+  const int splits = choose_down(M, p.rd, p.ffn, &c->force).ranges;
+  if ((size_t)splits * MT256 * 256 * p.rd * 4 > p.part_bytes) return (int)hipErrorInvalidValue;
   prof_mark(c, ps, 2, 0, st);
   e = launch_down1(c, MT256, splits, st);
   prof_mark(c, ps, 2, 1, st);
@@ -701,7 +695,7 @@ static int staged_tail(const Ctx* c, int64_t M, void* Y, int ps, hipStream_t st)
   prof_mark(c, ps, 3, 1, st);
   if (e) return e;
   prof_mark(c, ps, 4, 0, st);
-  if (out_uses_256(M, p.d)) {
+  if (choose_out(M, p.d, p.rd, false, &c->force).kernel == OUT_256) {
     e = launch_out(c, M, Y, MT256, st);
   } else {
     const int CT = (int)(p.d / 128);
@@ -719,10 +713,10 @@ int bf16_linear_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   const Plan& p = c->plan;
   char* ws = c->ws;
   const int MT128 = (int)((M + 127) / 128), MT256 = (int)((M + 255) / 256);
-  const int PT = (int)(p.r / 128);
   const bool small = linear_on_small_tiles(p);
-  const bool out256 = !small && linear_out_uses_256(M, p.ffn);
-  const char* const names[2] = {!small && in_supported(M, p.d, p.r) ? "k_in" : "k_s1", out256 ? "k_out" : "k_s5"};
+  const bool out256 = choose_out(M, p.ffn, p.r, small, &c->force).kernel == OUT_256;
+  const char* const names[2] = {choose_first(M, p.d, p.r, small, &c->force).kernel == FIRST_IN ? "k_in" : "k_s1",
+                                out256 ? "k_out" : "k_s5"};
   const int ps = prof_open_forward(c, 2, names);
   int e;
   prof_mark(c, ps, 0, 0, st);
@@ -746,12 +740,10 @@ int bf16_tiled_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStrea
   const Plan& p = c->plan;
   char* ws = c->ws;
   const int MT128 = (int)((M + 127) / 128);
-  const int PT = (int)(2 * p.r / 128);
   int e;
-  const bool big = in_supported(M, p.d, 2 * p.r);
-  const char* const s1name = big ? "k_in" : "k_s1";
+  const char* const s1name = choose_first(M, p.d, 2 * p.r, false, &c->force).kernel == FIRST_IN ? "k_in" : "k_s1";
   const char* const names_fused[4] = {s1name, "k_fused", "k_reduce", "k_s5"};
-  const char* const names_staged[5] = {s1name, "k_gate_up", "k_down1", "k_reduce", out_uses_256(M, p.d) ? "k_out" : "k_s5"};
+  const char* const names_staged[5] = {s1name, "k_gate_up", "k_down1", "k_reduce", choose_out(M, p.d, p.rd, false, &c->force).kernel == OUT_256 ? "k_out" : "k_s5"};
   const bool staged = staged_supported(p.rd, p.ffn) && !(p.flags & SVDMLP_FLAG_TILED_FUSED);
   const int ps = staged ? prof_open_forward(c, 5, names_staged) : prof_open_forward(c, 4, names_fused);
   prof_mark(c, ps, 0, 0, st);

@@ -159,6 +159,27 @@ def test_static_scratch_forward_checks_its_arguments_without_a_device(lib):
     lib.svdmlp_destroy(out)
 
 
+def test_force_plan_checks_its_arguments_and_plan_room_grows_the_workspace(lib):
+    out = ctypes.c_void_p()
+    d = desc(max_M=4096, d=4096, ffn=14336, r=512, r_down=512)
+    assert lib.svdmlp_create(ctypes.byref(d), ctypes.byref(out)) == 0
+    fp = lib.svdmlp_force_plan
+    assert fp(out, 0, 0, 0, 0) == 0 and fp(out, B.FIRST_IN, 4, 16, B.OUT_128) == 0 and fp(out, B.FIRST_S1, 0, 0, 0) == 0
+    for bad in ((3, 0, 0, 0), (-1, 0, 0, 0), (1, 9, 0, 0), (0, 2, 0, 0), (0, 0, 33, 0), (0, 0, -1, 0), (0, 0, 0, 3)):
+        assert fp(out, *bad) == B.SVDMLP_INVALID_ARGUMENT, bad
+    assert fp(None, 0, 0, 0, 0) == B.SVDMLP_INVALID_ARGUMENT
+    lib.svdmlp_destroy(out)
+    d32 = desc(dtype=B.SVDMLP_F32)
+    assert lib.svdmlp_create(ctypes.byref(d32), ctypes.byref(out)) == 0
+    assert fp(out, 0, 0, 4, 0) == B.SVDMLP_UNSUPPORTED
+    lib.svdmlp_destroy(out)
+    # room for every candidate: 32 ranges of the down projection's partial sums instead of the planner's 8
+    plain = B.svdmlp_workspace_bytes(d)
+    d.flags |= B.FLAG_PLAN_ROOM
+    roomy = B.svdmlp_workspace_bytes(d)
+    assert 20 * 4096 * 512 * 4 <= roomy - plain <= 24 * 4096 * 512 * 4
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")
@@ -166,67 +187,89 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
         B.lib()
 
 
-def test_describe_names_the_plan_of_every_baseline_config():
-    """svdmlp_describe is host-only: the planner's choices for the BASELINE configurations, pinned so that a change
-    of a heuristic shows up here (tile shapes, contraction ranges, persistent workgroups, half-tile round)."""
+def plan_of(d, M):
+    """The plan description without the cost model's figures (est_us and the alternatives of a stage)."""
+    return re.sub(r" est_us=[^\]]*", "", B.svdmlp_describe(d, M))
+
+
+def test_describe_prints_the_cost_model_scores_of_each_stage():
+    """Every stage that leaves a choice shows the estimated time of the chosen candidate and of the closest others,
+    and the chosen one is the cheapest the model lists (the choice is made by the model, not by a rule beside it)."""
     pre = desc(max_M=4096, d=4096, ffn=14336, r=512, r_down=512)
     s = B.svdmlp_describe(pre, 4096)
+    stages = re.findall(r"(k_s1|k_in|k_down1|k_out|k_s5)\[[^\]]*? est_us=([0-9.]+) alternatives:([^\]]*)\]", s)
+    assert [k for k, _, _ in stages] == ["k_s1", "k_down1", "k_out"], s
+    for kernel, est, alts in stages:
+        others = [float(x.split("=")[1]) for x in alts.split()]
+        assert others, (kernel, s)
+        assert float(est) <= min(others), (kernel, s)
+    # the first stage weighs both kernels and several cuts of the contraction
+    first_alts = stages[0][2]
+    assert "in/" in first_alts and "s1/2=" in first_alts
+    assert "out128/1=" in stages[2][2]
+
+
+def test_describe_names_the_plan_of_every_baseline_config():
+    """svdmlp_describe is host-only: the planner's choices for the BASELINE configurations, pinned so that a change
+    of the cost model shows up here (tile shapes, contraction ranges, persistent workgroups, half-tile round)."""
+    pre = desc(max_M=4096, d=4096, ffn=14336, r=512, r_down=512)
+    s = plan_of(pre, 4096)
     assert s.startswith("path=5 bf16-tiled-staged:")
     assert "k_s1[tile=128x128 tiles=256 ranges=1]" in s
     assert "k_gate_up[tile=256x256 tiles=896 workgroups=256 full=768 halves=256 xcd_grid=4x2]" in s
     assert "k_down1[tile=256x256 tiles=32 ranges=8] k_reduce k_out[tile=256x256 tiles=256]" in s
     # decode shape: one row tile, both split phases fill the chip
-    s = B.svdmlp_describe(pre, 16)
+    s = plan_of(pre, 16)
     assert s.startswith("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=64 ranges=4] k_stream_d2[tiles=448]")
     assert "k_stream_d4[tile=16 tiles=32 ranges=8] k_stream_d5[tiles=128 row_groups=1]" in s
-    assert B.svdmlp_describe(pre, 32) == s
+    assert plan_of(pre, 32) == s
     # two row tiles: 32-column tiles, each row tile with workgroups of its own in the two cut phases and in the last one
-    s = B.svdmlp_describe(pre, 33)
+    s = plan_of(pre, 33)
     assert s.startswith("path=3 bf16-streaming: row_tiles=2 k_stream_d1[tiles=32 row_groups=2 ranges=4] k_stream_d2[tiles=448]")
     assert "k_stream_d4[tiles=16 row_groups=2 ranges=8] k_stream_d5[tiles=128 row_groups=2]" in s
-    assert B.svdmlp_describe(pre, 64) == s
+    assert plan_of(pre, 64) == s
     # four row tiles: 8 MB of [Ug|Uu] are worth fetching four times to shorten the partial sums' read-back, 15 MB of Ud twice
-    s = B.svdmlp_describe(pre, 128)
+    s = plan_of(pre, 128)
     assert s.startswith("path=3 bf16-streaming: row_tiles=4 k_stream_d1[tiles=32 row_groups=4 ranges=2] k_stream_d2[tiles=448]")
     assert "k_stream_d4[tiles=16 row_groups=2 ranges=8] k_stream_d5[tiles=128 row_groups=2]" in s
-    assert B.svdmlp_describe(pre, 129).startswith("path=5")
+    assert plan_of(pre, 129).startswith("path=5")
     # config 2 (M = 128) streams, small factors: row-tile groups in every phase that has too few tiles;
     # forced onto the tiled path it has one row tile
     small = desc(max_M=128, d=2048, ffn=8192, r=256, r_down=256)
-    s = B.svdmlp_describe(small, 128)
+    s = plan_of(small, 128)
     assert s.startswith("path=3 bf16-streaming: row_tiles=4 k_stream_d1[tiles=16 row_groups=4 ranges=4] k_stream_d2[tiles=256]")
     assert "k_stream_d4[tiles=8 row_groups=4 ranges=8] k_stream_d5[tiles=64 row_groups=4]" in s
     small.flags |= B.FLAG_FORCE_TILED
     # fewer tiles than half the CUs: every tile of k_gate_up as two 128-row halves
-    assert "k_gate_up[tile=256x256 tiles=32 workgroups=32 full=0 halves=64" in B.svdmlp_describe(small, 128)
+    assert "k_gate_up[tile=256x256 tiles=32 workgroups=32 full=0 halves=64" in plan_of(small, 128)
     # wide config: 8 row tiles x 108 column tiles = 3 full rounds + 96 tiles as 192 halves
     wide = desc(max_M=2048, d=5120, ffn=27648, r=1024, r_down=1024)
-    s = B.svdmlp_describe(wide, 2048)
+    s = plan_of(wide, 2048)
     assert "k_gate_up[tile=256x256 tiles=864 workgroups=256 full=768 halves=192" in s
     # fused variant on request, and for extents the staged one does not take
     pre.flags |= B.FLAG_TILED_FUSED
-    assert B.svdmlp_describe(pre, 4096).startswith("path=2 bf16-tiled-fused:")
+    assert plan_of(pre, 4096).startswith("path=2 bf16-tiled-fused:")
     odd = desc(max_M=512, d=256, ffn=384, r=192, r_down=128)   # ffn and r_down run rounded up to 512 and 256
-    assert B.svdmlp_describe(odd, 512).startswith("path=5")
+    assert plan_of(odd, 512).startswith("path=5")
     # both ranks within one 128-wide tile: the fused variant by itself (the staged one would pad r_down to 256 and is
     # bound by the round trip of the activation at so little arithmetic per element)
     tiny = desc(max_M=4096, d=4096, ffn=14336, r=128, r_down=128)
-    assert B.svdmlp_describe(tiny, 4096).startswith("path=2 bf16-tiled-fused:")
-    assert "k_stream_d4[tile=16 tiles=8 " in B.svdmlp_describe(tiny, 16)      # the streaming path runs r_down = 128 unpadded
+    assert plan_of(tiny, 4096).startswith("path=2 bf16-tiled-fused:")
+    assert "k_stream_d4[tile=16 tiles=8 " in plan_of(tiny, 16)      # the streaming path runs r_down = 128 unpadded
     # single factored layer at the paper's kernel-evaluation shape: the first stage cuts d when tiles are few
     lin = desc(kind=B.SVDMLP_LINEAR, max_M=32768, d=8192, ffn=16384, r=4096, r_down=0)
-    assert "k_in[tile=256x256 tiles=64 ranges=4] k_reduce k_out" in B.svdmlp_describe(lin, 1024)
-    assert "k_in[tile=256x256 tiles=256 ranges=1] k_out[tile=256x256 tiles=1024]" in B.svdmlp_describe(lin, 4096)
+    assert "k_in[tile=256x256 tiles=64 ranges=4] k_reduce k_out" in plan_of(lin, 1024)
+    assert "k_in[tile=256x256 tiles=256 ranges=1] k_out[tile=256x256 tiles=1024]" in plan_of(lin, 4096)
     # up to 128 rows the layer streams its weights (phases D1 and D5 of the streaming path), unless re-reading the
     # activation for every weight tile would cost more than the tiles (this shape beyond 64 rows)
-    assert B.svdmlp_describe(lin, 16).startswith("path=7 bf16-linear-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=256 ranges=1] k_stream_d5[tiles=512")
-    assert B.svdmlp_describe(lin, 64).startswith("path=7") and B.svdmlp_describe(lin, 65).startswith("path=6")
-    assert B.svdmlp_describe(desc(kind=B.SVDMLP_LINEAR, max_M=128, d=4096, ffn=4096, r=1024, r_down=0), 128).startswith("path=7")
+    assert plan_of(lin, 16).startswith("path=7 bf16-linear-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=256 ranges=1] k_stream_d5[tiles=512")
+    assert plan_of(lin, 64).startswith("path=7") and plan_of(lin, 65).startswith("path=6")
+    assert plan_of(desc(kind=B.SVDMLP_LINEAR, max_M=128, d=4096, ffn=4096, r=1024, r_down=0), 128).startswith("path=7")
     # the small-block point of the block-size comparison: both products on 128 x 128 tiles on request
     lin.flags |= B.FLAG_TILE_128
-    assert "k_s1[tile=128x128 tiles=1024 ranges=1] k_s5[tile=128x128 tiles=4096]" in B.svdmlp_describe(lin, 4096)
+    assert "k_s1[tile=128x128 tiles=1024 ranges=1] k_s5[tile=128x128 tiles=4096]" in plan_of(lin, 4096)
     f32 = desc(dtype=B.SVDMLP_F32, max_M=10, d=96, ffn=200, r=24, r_down=40)
-    assert B.svdmlp_describe(f32, 10).startswith("path=1")
+    assert plan_of(f32, 10).startswith("path=1")
     # errors
     with pytest.raises(B.SvdMlpError) as e:
         B.svdmlp_describe(pre, 5000)
@@ -245,13 +288,13 @@ def test_ranks_are_rounded_up_to_the_tiles():
     assert B.svdmlp_workspace_bytes(desc(max_M=300, d=1024, ffn=1024, r=257, r_down=768)) > base
     # staged variant: down rank to a multiple of 256; fused variant (on request, or ffn not a multiple of 256): to 128, 256,
     # 512 or a multiple of 512
-    assert "k_down1[tile=256x256 tiles=6 ranges" in B.svdmlp_describe(desc(max_M=300, d=1024, ffn=1024, r=200, r_down=600), 300)
+    assert "k_down1[tile=256x256 tiles=6 ranges" in plan_of(desc(max_M=300, d=1024, ffn=1024, r=200, r_down=600), 300)
     # ffn is internal to the gated forward: rounded up to a multiple of 256 as well (1100 -> 1280 = 5 column tiles)
-    s = B.svdmlp_describe(desc(max_M=300, d=1024, ffn=1100, r=200, r_down=600), 300)
+    s = plan_of(desc(max_M=300, d=1024, ffn=1100, r=200, r_down=600), 300)
     assert s.startswith("path=5 bf16-tiled-staged:") and "k_gate_up[tile=256x256 tiles=10 " in s
     fused = desc(max_M=300, d=1024, ffn=1100, r=200, r_down=600)
     fused.flags |= B.FLAG_TILED_FUSED
-    assert B.svdmlp_describe(fused, 300).startswith("path=2 bf16-tiled-fused:")
+    assert plan_of(fused, 300).startswith("path=2 bf16-tiled-fused:")
     lin = desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=640, r=100, r_down=0)
     assert B.svdmlp_workspace_bytes(lin) == B.svdmlp_workspace_bytes(desc(kind=B.SVDMLP_LINEAR, max_M=300, d=512, ffn=640, r=128, r_down=0))
 

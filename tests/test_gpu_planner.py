@@ -1,0 +1,120 @@
+"""The planner's choices against the clock: every candidate of every stage that leaves a choice (first product: kernel
+and ranges of d; down projection: ffn ranges; last product: tile size) is forced in turn through svdmlp_force_plan and
+timed with the library's per-kernel events; the candidate the cost model picks must be within a few percent of the
+fastest one (the counterpart of the block-size sweep of the paper's Sec. 5.3, Table 3, where the model of Eq. 10 - 11
+picks the block)."""
+import re
+import statistics
+
+import pytest
+import torch
+
+from paper_2510_25977_amd import binding as B
+from paper_2510_25977_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+STEPS = 30
+
+
+def kernel_times_us(mlp, X, Y):
+    for _ in range(6):
+        mlp(X, Y)
+    torch.cuda.synchronize()
+    runs = []
+    for _ in range(3):
+        B.svdmlp_profile_begin(mlp.ctx, STEPS)
+        for _ in range(STEPS):
+            mlp(X, Y)
+        k, _ = B.svdmlp_profile_end(mlp.ctx)
+        runs.append(k)
+    return {n: statistics.median(r[n] for r in runs) * 1e3 for n in runs[0]}
+
+
+@pytest.mark.parametrize("name,kw", [("prefill", dict(r=256)), ("prefill", dict(r=512)), ("prefill", dict(r=1024)),
+                                     ("wide", {}), ("mlp_small", {})])
+def test_chosen_plan_is_within_five_percent_of_the_best_candidate(name, kw):
+    gi = synth.make_workload(name, **kw)
+    dm = gi.dims
+    dev = torch.device("cuda:0")
+    f = {k: v.to(dev) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=dm["M"], flags=B.FLAG_PLAN_ROOM | B.FLAG_FORCE_TILED, keep_factors=False, **f)
+    X = gi.X.to(dev)
+    Y = torch.empty_like(X)
+    text = B.svdmlp_describe(mlp.desc, dm["M"])
+    auto = kernel_times_us(mlp, X, Y)
+    first_name = "k_in" if "k_in" in auto else "k_s1"
+    last_name = "k_out" if "k_out" in auto else "k_s5"
+    chosen = {"first": auto[first_name], "down": auto["k_down1"] + auto["k_reduce"], "out": auto[last_name]}
+    best = dict(chosen)
+    tried = {"first": 0, "down": 0, "out": 0}
+    for kern in (B.FIRST_S1, B.FIRST_IN):
+        for S in (1, 2, 3, 4, 6, 8):
+            B.svdmlp_force_plan(mlp.ctx, kern, S, 0, 0)
+            k = kernel_times_us(mlp, X, Y)
+            ran = "k_in" if "k_in" in k else "k_s1"
+            if (ran == "k_in") != (kern == B.FIRST_IN):
+                continue          # not a valid candidate at these extents: the planner's own choice ran
+            best["first"] = min(best["first"], k[ran])
+            tried["first"] += 1
+    for s in (1, 2, 4, 6, 8, 12, 16, 24, 32):
+        B.svdmlp_force_plan(mlp.ctx, 0, 0, s, 0)
+        k = kernel_times_us(mlp, X, Y)
+        best["down"] = min(best["down"], k["k_down1"] + k["k_reduce"])
+        tried["down"] += 1
+    for o in (B.OUT_256, B.OUT_128):
+        B.svdmlp_force_plan(mlp.ctx, 0, 0, 0, o)
+        k = kernel_times_us(mlp, X, Y)
+        ran = "k_out" if "k_out" in k else "k_s5"
+        if (ran == "k_out") != (o == B.OUT_256):
+            continue
+        best["out"] = min(best["out"], k[ran])
+        tried["out"] += 1
+    B.svdmlp_force_plan(mlp.ctx, 0, 0, 0, 0)
+    again = kernel_times_us(mlp, X, Y)
+    mlp.close()
+    assert set(again) == set(auto)                      # the override is gone
+    assert tried["first"] >= 4 and tried["down"] >= 6 and tried["out"] >= 1, tried
+    # per stage: within 10 % (+ 0.5 us of timer noise) of the fastest candidate; the three stages together within 5 %
+    for stage in chosen:
+        assert chosen[stage] <= 1.10 * best[stage] + 0.5, (stage, chosen, best, text)
+    assert sum(chosen.values()) <= 1.05 * sum(best.values()) + 0.5, (chosen, best, text)
+    # the model's estimate of what it chose is in the right place (it ranks candidates; it is not a simulator)
+    est = [float(x) for x in re.findall(r"est_us=([0-9.]+)", text)]
+    assert len(est) == 3
+    for e, stage in zip(est, ("first", "down", "out")):
+        assert 0.6 * chosen[stage] <= e <= 1.5 * chosen[stage], (stage, e, chosen)
+
+
+def test_forced_candidates_compute_the_same_result():
+    """Whatever candidate runs, the forward is the same function: outputs of forced plans against the automatic one
+    (different contraction cuts add in a different order, so equal up to fp32 summation order, then bf16 rounding)."""
+    gi = synth.make_gated(700, 1024, 4096, 256, 512, stream=83)
+    dev = torch.device("cuda:0")
+    f = {k: v.to(dev) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=700, flags=B.FLAG_PLAN_ROOM | B.FLAG_FORCE_TILED, **f)
+    X = gi.X.to(dev)
+    ref = mlp(X).float()
+    scale = float(ref.abs().max())
+    for plan in ((B.FIRST_S1, 1, 1, B.OUT_128), (B.FIRST_S1, 2, 3, B.OUT_256), (B.FIRST_IN, 1, 7, 0), (B.FIRST_IN, 2, 32, B.OUT_256),
+                 (0, 0, 16, B.OUT_128)):
+        B.svdmlp_force_plan(mlp.ctx, *plan)
+        Y = mlp(X).float()
+        torch.cuda.synchronize()
+        assert float((Y - ref).abs().max()) <= 1e-2 * scale, plan
+    # without SVDMLP_FLAG_PLAN_ROOM a forced candidate either fits the partial-sum buffer the planner's own choices
+    # need (then it runs and gives the same result) or the forward refuses it loudly; never a silent overrun
+    tight = B.SvdMlp(max_M=700, flags=B.FLAG_FORCE_TILED, **f)
+    B.svdmlp_force_plan(tight.ctx, 0, 0, 32, 0)
+    try:
+        Y = tight(X).float()
+        torch.cuda.synchronize()
+        assert float((Y - ref).abs().max()) <= 1e-2 * scale
+    except B.SvdMlpError as e:
+        assert e.status == B.SVDMLP_HIP_ERROR
+    B.svdmlp_force_plan(tight.ctx, 0, 0, 0, 0)
+    Y = tight(X).float()
+    torch.cuda.synchronize()
+    assert torch.equal(Y, ref)
+    tight.close()
+    mlp.close()
