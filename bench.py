@@ -246,6 +246,15 @@ def measure_roofs(dev, quick=True):
     out["mfma_bf16"] = {"flop": fl, "ms": t["median"], "TFLOPs": fl / t["median"] / 1e9, "TFLOPs_best": fl / t["min"] / 1e9,
                         "note": "v_mfma_f32_32x32x16_bf16, constant register operands, two waves per SIMD"}
 
+    # SiLU on one wave of each SIMD under the MFMAs of the other: each half alone, then both
+    mi, vi = 6000, 160     # 12000 MFMAs (384 k clocks of matrix core) and 5120 SiLU evaluations per lane
+    co = {}
+    for name, a, b in (("mfma_only", mi, 0), ("silu_only", 0, vi), ("both", mi, vi)):
+        co[name + "_ms"] = time_batches(lambda: B.svdmlp_roof_coexec(a, b, sink.data_ptr(), cus, s), 3, 2, 5)["median"]
+    co["overlap"] = (co["mfma_only_ms"] + co["silu_only_ms"] - co["both_ms"]) / min(co["mfma_only_ms"], co["silu_only_ms"])
+    co["note"] = "overlap 1 = the shorter half hides completely under the longer one, 0 = they run one after the other"
+    out["silu_under_partner_mfma"] = co
+
     def chain():
         for _ in range(4):
             B.svdmlp_roof_empty(256, 512, s)

@@ -31,7 +31,7 @@ EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
            "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio",
            "svdmlp_forward_static_scratch", "svdmlp_static_scratch_bytes",
-           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_empty", "svdmlp_force_plan"]
+           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_empty", "svdmlp_force_plan", "svdmlp_roof_coexec"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_roof_read.restype = ctypes.c_int
         L.svdmlp_roof_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
         L.svdmlp_roof_mfma.restype = ctypes.c_int
+        L.svdmlp_roof_coexec.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+        L.svdmlp_roof_coexec.restype = ctypes.c_int
         L.svdmlp_roof_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         L.svdmlp_roof_empty.restype = ctypes.c_int
         L.svdmlp_force_plan.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
@@ -165,6 +167,11 @@ def svdmlp_roof_read(buf_ptr: int, nbytes: int, sink_ptr: int, workgroups: int, 
 def svdmlp_roof_mfma(iters: int, sink_ptr: int, workgroups: int, stream_ptr: int = 0) -> None:
     _check(lib().svdmlp_roof_mfma(int(iters), ctypes.c_void_p(sink_ptr), int(workgroups), ctypes.c_void_p(stream_ptr)),
            "svdmlp_roof_mfma")
+
+
+def svdmlp_roof_coexec(mfma_iters: int, valu_iters: int, sink_ptr: int, workgroups: int, stream_ptr: int = 0) -> None:
+    _check(lib().svdmlp_roof_coexec(int(mfma_iters), int(valu_iters), ctypes.c_void_p(sink_ptr), int(workgroups),
+                                    ctypes.c_void_p(stream_ptr)), "svdmlp_roof_coexec")
 
 
 def svdmlp_roof_empty(workgroups: int, threads: int, stream_ptr: int = 0) -> None:

@@ -51,6 +51,46 @@ __global__ __launch_bounds__(512) void k_roof_mfma(int iters, float* __restrict_
   if (s == -1.0f) sink[0] = s;   // never true: the products are non-negative
 }
 
+// Waves 0..3 of a workgroup (one per SIMD) issue MFMAs as in k_roof_mfma; waves 4..7, their SIMD partners, evaluate
+// SiLU (multiply, exp2, add, reciprocal, multiply: two of the five on the transcendental unit) on 32 registers per
+// lane, round after round.  Either half can be switched off, so three launches tell whether vector-ALU work of one
+// wave runs under the MFMAs of the other wave of its SIMD.
+__global__ __launch_bounds__(512) void k_roof_coexec(int mfma_iters, int valu_iters, float* __restrict__ sink) {
+  const int lane = threadIdx.x % 64, w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+  if (w < 4) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      a[s] = (__bf16)(0.001f * (float)((lane + s) % 7));
+      b[s] = (__bf16)(0.002f * (float)((lane * 3 + s) % 5));
+    }
+    f32x16 c0, c1;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { c0[e] = 0.f; c1[e] = 0.f; }
+    for (int i = 0; i < mfma_iters; ++i) {
+      c0 = mfma32(a, b, c0);
+      c1 = mfma32(a, b, c1);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += c0[e] + c1[e];
+    if (s == -1.0f) sink[0] = s;
+  } else {
+    float g[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) g[e] = 0.01f * (float)(lane + e);
+    for (int i = 0; i < valu_iters; ++i) {
+#pragma unroll
+      for (int e = 0; e < 32; ++e)
+        g[e] = g[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g[e] * -1.44269504088896f)) + 0.25f;
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) s += g[e];
+    if (s == -1.0f) sink[1] = s;
+  }
+}
+
 __global__ void k_roof_empty(int* unused) { (void)unused; }
 
 }  // namespace svdmlp
@@ -72,6 +112,14 @@ int svdmlp_roof_mfma(int iters, void* sink, int workgroups, void* hip_stream) {
   if (!sink || iters <= 0 || workgroups <= 0) return SVDMLP_INVALID_ARGUMENT;
   hipLaunchKernelGGL(k_roof_mfma, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(hip_stream), iters,
                      static_cast<float*>(sink));
+  if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
+  return SVDMLP_OK;
+}
+
+int svdmlp_roof_coexec(int mfma_iters, int valu_iters, void* sink, int workgroups, void* hip_stream) {
+  if (!sink || mfma_iters < 0 || valu_iters < 0 || workgroups <= 0) return SVDMLP_INVALID_ARGUMENT;
+  hipLaunchKernelGGL(k_roof_coexec, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(hip_stream), mfma_iters,
+                     valu_iters, static_cast<float*>(sink));
   if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
   return SVDMLP_OK;
 }
