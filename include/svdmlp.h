@@ -60,7 +60,9 @@ enum {
   SVDMLP_WORKSPACE_TOO_SMALL = -3,
   SVDMLP_HIP_ERROR = -4,          /* a HIP runtime call failed; see svdmlp_last_hip_error */
   SVDMLP_NO_DEVICE = -5,          /* no HIP device, or the current device is not gfx950 */
-  SVDMLP_SCRATCH_TOO_SMALL = -6   /* svdmlp_forward_static_scratch: the extents need more than the static array holds */
+  SVDMLP_SCRATCH_TOO_SMALL = -6,  /* svdmlp_forward_static_scratch: the extents need more than the static array holds */
+  SVDMLP_OUT_OF_HOST_MEMORY = -7, /* a host allocation failed (context, event pool) */
+  SVDMLP_TIMED_OUT = -8           /* svdmlp_check: a bounded wait inside the one-kernel streaming variant ran out */
 };
 
 /* Bits of svdmlp_desc.flags (testing and benchmarking aids; 0 = automatic choice). */
@@ -134,6 +136,19 @@ int svdmlp_forward_static_scratch(svdmlp_ctx *ctx, const void *X, int64_t M, voi
 
 /* Size in bytes of that static array (host only). */
 size_t svdmlp_static_scratch_bytes(void);
+
+/* The one-kernel streaming variant (SVDMLP_FLAG_STREAM_ONE_KERNEL) waits inside the kernel, with a bound; if a wait
+ * runs out, the workgroups stop computing, the output rows of that forward are filled with NaN, and an error word in the
+ * workspace is set.  svdmlp_check reads that word (a synchronous 4-byte copy from the device: call it after the
+ * forward's stream has been synchronised, never under graph capture) and clears it: SVDMLP_OK, SVDMLP_TIMED_OUT, or
+ * SVDMLP_HIP_ERROR if the copy fails.  Contexts that never ran that variant return SVDMLP_OK without touching the
+ * device. */
+int svdmlp_check(svdmlp_ctx *ctx);
+
+/* Testing aid for that error path: the number of polls a wait inside the one-kernel variant may take before it gives
+ * up (-1 = the kernel's own bound, about a million).  With 0 every wait that is not already satisfied gives up at
+ * once, so the kernel still ends normally, on its error path, without anything having to hang. */
+int svdmlp_debug_set_poll_limit(svdmlp_ctx *ctx, int32_t polls);
 
 /* Release the context's host memory.  Does not free or touch device memory; the caller must make
  * sure no forward is still running.  svdmlp_destroy(NULL) returns SVDMLP_OK. */

@@ -12,17 +12,14 @@ from typing import Optional
 
 import torch
 
-import os
-
 HERE = Path(__file__).resolve().parent
-# SVDMLP_LIB lets a developer point the binding at an experimental build of the same ABI.
-LIB_PATH = Path(os.environ["SVDMLP_LIB"]) if os.environ.get("SVDMLP_LIB") else HERE / "libsvdmlp.so"
+LIB_PATH = HERE / "libsvdmlp.so"      # the in-tree build, nothing else
 
 SVDMLP_BF16, SVDMLP_F32 = 0, 1
 SVDMLP_GATED, SVDMLP_LINEAR = 0, 1
 SVDMLP_OK = 0
 SVDMLP_INVALID_ARGUMENT, SVDMLP_UNSUPPORTED, SVDMLP_WORKSPACE_TOO_SMALL, SVDMLP_HIP_ERROR, SVDMLP_NO_DEVICE = -1, -2, -3, -4, -5
-SVDMLP_SCRATCH_TOO_SMALL = -6
+SVDMLP_SCRATCH_TOO_SMALL, SVDMLP_OUT_OF_HOST_MEMORY, SVDMLP_TIMED_OUT = -6, -7, -8
 FLAG_FORCE_TILED, FLAG_FORCE_STREAM, FLAG_SKIP_ARCH_CHECK, FLAG_STREAM_ONE_KERNEL, FLAG_TILED_FUSED, FLAG_TILE_128 = 1, 2, 4, 8, 16, 32
 FLAG_PLAN_ROOM = 64
 FIRST_S1, FIRST_IN, OUT_256, OUT_128 = 1, 2, 1, 2
@@ -31,7 +28,7 @@ EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
            "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio",
            "svdmlp_forward_static_scratch", "svdmlp_static_scratch_bytes",
-           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_empty", "svdmlp_force_plan", "svdmlp_roof_coexec"]
+           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_empty", "svdmlp_force_plan", "svdmlp_roof_coexec", "svdmlp_check", "svdmlp_debug_set_poll_limit"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -80,6 +77,10 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_roof_coexec.restype = ctypes.c_int
         L.svdmlp_roof_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         L.svdmlp_roof_empty.restype = ctypes.c_int
+        L.svdmlp_debug_set_poll_limit.argtypes = [ctypes.c_void_p, ctypes.c_int32]
+        L.svdmlp_debug_set_poll_limit.restype = ctypes.c_int
+        L.svdmlp_check.argtypes = [ctypes.c_void_p]
+        L.svdmlp_check.restype = ctypes.c_int
         L.svdmlp_force_plan.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         L.svdmlp_force_plan.restype = ctypes.c_int
         L.svdmlp_destroy.argtypes = [ctypes.c_void_p]
@@ -181,6 +182,10 @@ def svdmlp_roof_empty(workgroups: int, threads: int, stream_ptr: int = 0) -> Non
 def svdmlp_force_plan(ctx, first_kernel: int = 0, first_ranges: int = 0, down_ranges: int = 0, out_kernel: int = 0) -> None:
     _check(lib().svdmlp_force_plan(ctx, int(first_kernel), int(first_ranges), int(down_ranges), int(out_kernel)),
            "svdmlp_force_plan")
+
+
+def svdmlp_check(ctx) -> None:
+    _check(lib().svdmlp_check(ctx), "svdmlp_check")
 
 
 def svdmlp_destroy(ctx) -> None:

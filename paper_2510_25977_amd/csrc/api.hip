@@ -179,6 +179,8 @@ const char* svdmlp_status_string(int status) {
     case SVDMLP_HIP_ERROR: return "HIP runtime error";
     case SVDMLP_NO_DEVICE: return "no gfx950 device";
     case SVDMLP_SCRATCH_TOO_SMALL: return "extents beyond the library's static scratch array";
+    case SVDMLP_OUT_OF_HOST_MEMORY: return "out of host memory";
+    case SVDMLP_TIMED_OUT: return "a bounded wait inside a kernel timed out";
     default: return "unknown status";
   }
 }
@@ -245,9 +247,9 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
   };
   if (p.dtype == SVDMLP_F32) {
     put("path=1 fp32-debug:%s", p.kind == SVDMLP_GATED ? " k_f32_gemm x5 (SiLU-gate epilogue in the third)" : " k_f32_gemm x2");
-  } else if (p.kind == SVDMLP_LINEAR && ((linear_stream_pays(M, p.d, p.r, p.ffn) && !(p.flags & (SVDMLP_FLAG_FORCE_TILED | SVDMLP_FLAG_TILE_128))) ||
+  } else if (p.kind == SVDMLP_LINEAR && ((linear_stream_pays(M, p.d, p.r, p.ffn) && stream_supported(p, M) && !(p.flags & (SVDMLP_FLAG_FORCE_TILED | SVDMLP_FLAG_TILE_128))) ||
                                          (p.flags & SVDMLP_FLAG_FORCE_STREAM))) {
-    if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+    if (!stream_supported(p, M)) return SVDMLP_UNSUPPORTED;
     const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;
     const int t1 = (int)(p.r / 32), t5 = (int)(p.ffn / 32);
     if (M <= 32 && p.d % 32 == 0 && p.r / 16 <= 2048)
@@ -263,10 +265,10 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
     first_stage(p.r);
     last_stage(p.ffn, p.r);
   } else {
-    bool stream_path = M <= STREAM_MAX_M;
+    bool stream_path = stream_supported(p, M);
     if (p.flags & SVDMLP_FLAG_FORCE_TILED) stream_path = false;
     if (p.flags & SVDMLP_FLAG_FORCE_STREAM) {
-      if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+      if (!stream_supported(p, M)) return SVDMLP_UNSUPPORTED;
       stream_path = true;
     }
     if (stream_path) {
@@ -333,7 +335,7 @@ int svdmlp_create(const svdmlp_desc* desc, svdmlp_ctx** out) {
     n_cus = prop.multiProcessorCount;
   }
   Ctx* c = new (std::nothrow) Ctx;
-  if (!c) return SVDMLP_INVALID_ARGUMENT;
+  if (!c) return SVDMLP_OUT_OF_HOST_MEMORY;
   c->desc = *desc;
   c->plan = p;
   c->ws = static_cast<char*>(desc->workspace);
@@ -370,23 +372,25 @@ int svdmlp_forward(svdmlp_ctx* ctx, const void* X, int64_t M, void* Y, void* hip
     c->last_path = 1;
     e = f32_forward(c, X, M, Y, st);
   } else if (c->plan.kind == SVDMLP_LINEAR) {
-    bool stream_path = linear_stream_pays(M, c->plan.d, c->plan.r, c->plan.ffn) && !(c->plan.flags & (SVDMLP_FLAG_FORCE_TILED | SVDMLP_FLAG_TILE_128));
+    bool stream_path = linear_stream_pays(M, c->plan.d, c->plan.r, c->plan.ffn) && stream_supported(c->plan, M) &&
+                       !(c->plan.flags & (SVDMLP_FLAG_FORCE_TILED | SVDMLP_FLAG_TILE_128));
     if (c->plan.flags & SVDMLP_FLAG_FORCE_STREAM) {
-      if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+      if (!stream_supported(c->plan, M)) return SVDMLP_UNSUPPORTED;
       stream_path = true;
     }
     c->last_path = stream_path ? 7 : 6;
     e = stream_path ? bf16_linear_stream_forward(c, X, M, Y, st) : bf16_linear_forward(c, X, M, Y, st);
   } else {
-    bool stream_path = M <= STREAM_MAX_M;
+    bool stream_path = stream_supported(c->plan, M);   // else the tiled path, which takes any row count
     if (c->plan.flags & SVDMLP_FLAG_FORCE_TILED) stream_path = false;
     if (c->plan.flags & SVDMLP_FLAG_FORCE_STREAM) {
-      if (M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+      if (!stream_supported(c->plan, M)) return SVDMLP_UNSUPPORTED;
       stream_path = true;
     }
     const bool one_kernel = stream_path && M <= 32 && (c->plan.flags & SVDMLP_FLAG_STREAM_ONE_KERNEL) && bf16_decode_supported(c, M);
     const bool staged = staged_supported(c->plan.rd, c->plan.ffn) && !(c->plan.flags & SVDMLP_FLAG_TILED_FUSED);
     c->last_path = stream_path ? (one_kernel ? 4 : 3) : (staged ? 5 : 2);
+    if (one_kernel) c->ran_one_kernel = true;
     e = !stream_path ? bf16_tiled_forward(c, X, M, Y, st)
                      : one_kernel ? bf16_decode_forward(c, X, M, Y, st) : bf16_stream_forward(c, X, M, Y, st);
   }
@@ -404,7 +408,7 @@ int svdmlp_forward_static_scratch(svdmlp_ctx* ctx, const void* X, int64_t M, voi
   if (M == 0) return SVDMLP_OK;
   if (!X || !Y || X == Y || M > c->plan.max_M) return SVDMLP_INVALID_ARGUMENT;
   if (!aligned16(X) || !aligned16(Y)) return SVDMLP_INVALID_ARGUMENT;
-  if (c->plan.dtype != SVDMLP_BF16 || c->plan.kind != SVDMLP_GATED || M > STREAM_MAX_M) return SVDMLP_UNSUPPORTED;
+  if (c->plan.dtype != SVDMLP_BF16 || c->plan.kind != SVDMLP_GATED || !stream_supported(c->plan, M)) return SVDMLP_UNSUPPORTED;
   if (stream_static_scratch_need(c->plan, M) > STATIC_SCRATCH_BYTES) return SVDMLP_SCRATCH_TOO_SMALL;
   if (c->desc.flags & SVDMLP_FLAG_SKIP_ARCH_CHECK) return SVDMLP_NO_DEVICE;  // host-only context: nothing to run on
   int dev = -1;
@@ -420,6 +424,26 @@ int svdmlp_forward_static_scratch(svdmlp_ctx* ctx, const void* X, int64_t M, voi
 }
 
 size_t svdmlp_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int svdmlp_debug_set_poll_limit(svdmlp_ctx* ctx, int32_t polls) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c || polls < -1) return SVDMLP_INVALID_ARGUMENT;
+  c->poll_limit = polls;
+  return SVDMLP_OK;
+}
+
+int svdmlp_check(svdmlp_ctx* ctx) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return SVDMLP_INVALID_ARGUMENT;
+  if (!c->ran_one_kernel) return SVDMLP_OK;
+  unsigned word = 0;
+  char* err = decode_error_word(c);
+  if (hipMemcpy(&word, err, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return SVDMLP_HIP_ERROR; }
+  if (!word) return SVDMLP_OK;
+  word = 0;
+  if (hipMemcpy(err, &word, sizeof(word), hipMemcpyHostToDevice) != hipSuccess) { (void)hipGetLastError(); return SVDMLP_HIP_ERROR; }
+  return SVDMLP_TIMED_OUT;
+}
 
 int svdmlp_force_plan(svdmlp_ctx* ctx, int32_t first_kernel, int32_t first_ranges, int32_t down_ranges, int32_t out_kernel) {
   Ctx* c = reinterpret_cast<Ctx*>(ctx);
@@ -457,7 +481,7 @@ int svdmlp_profile_begin(svdmlp_ctx* ctx, int max_forwards) {
   Prof& p = c->prof;
   const int n = max_forwards * PROF_MAXK * 2;
   p.ev = new (std::nothrow) hipEvent_t[n];
-  if (!p.ev) return SVDMLP_INVALID_ARGUMENT;
+  if (!p.ev) return SVDMLP_OUT_OF_HOST_MEMORY;
   for (int i = 0; i < n; ++i) {
     if (hipEventCreate(&p.ev[i]) != hipSuccess) {
       for (int j = 0; j < i; ++j) (void)hipEventDestroy(p.ev[j]);

@@ -210,6 +210,7 @@ int stream_row_groups_whole(int rt, int tiles);
 int stream_splits16(int tiles, int KB2, int mt);
 int stream_tiles16(int64_t M);
 bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd);   // rows the weight-streaming path takes (four 32-row tiles)
+bool stream_supported(const Plan& p, int64_t M);   // rows and ticket capacity the weight-streaming path takes
 int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 // ... with T, H, Td, the partial tiles and the tickets in the library's static device array (stream.hip)
 constexpr size_t STATIC_SCRATCH_BYTES = (size_t)16 << 20;
@@ -220,6 +221,7 @@ int bf16_linear_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, 
 bool linear_stream_pays(int64_t M, int64_t d, int64_t r, int64_t n);
 int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStream_t st);
 bool bf16_decode_supported(const Ctx* c, int64_t M);
+char* decode_error_word(const Ctx* c);   // device address of the sticky error word of the one-kernel variant
 
 // Optional per-kernel timing: HIP events recorded on the caller's stream around every kernel launch of
 // a forward (only while a profile is open; see svdmlp_profile_begin in svdmlp.h).
@@ -242,6 +244,8 @@ struct Ctx {
   int device = -1;                               // ... and its ordinal
   char* static_scratch = nullptr;                // that device's copy of the library's static scratch array
   PlanForce force = {0, 0, 0, 0};                // svdmlp_force_plan
+  int poll_limit = -1;                           // svdmlp_debug_set_poll_limit (-1: the kernel's own bound)
+  bool ran_one_kernel = false;                   // a forward took the one-kernel streaming variant (svdmlp_check)
   mutable Prof prof;
 };
 

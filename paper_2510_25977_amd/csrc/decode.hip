@@ -48,6 +48,7 @@ struct DqArgs {
   int KB1, KBr, KBf, KBq;                // contraction blocks of 16: d, r, ffn, rd
   int t1, S1, t2, t4, S4, t5;            // tiles and ranges per phase
   int n1, n2, n4, n5;                    // items per phase
+  int poll_limit;                        // polls a wait may take before it gives up (POLL_LIMIT; tests shrink it)
 };
 
 __device__ __forceinline__ f32x4 mfma16q(bf16x8 a, bf16x8 b, f32x4 c) {
@@ -71,7 +72,7 @@ struct DqShared {
 __device__ __forceinline__ bool dq_wait(DqShared& sh, const DqArgs& a, int which, unsigned target) {
   if (threadIdx.x == 0) {
     int ok = 0;
-    for (int polls = 0; polls < POLL_LIMIT; ++polls) {
+    for (int polls = 0; polls < a.poll_limit; ++polls) {
       if (__hip_atomic_load(a.ctr + which * CTR_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) { ok = 1; break; }
       __builtin_amdgcn_s_sleep(1);
     }
@@ -257,6 +258,13 @@ __device__ __forceinline__ void dq_whole_phase(DqShared& sh, const DqArgs& a, in
     if (dq_wait(sh, a, DEP, (unsigned)(GATE ? a.t1 : a.t4))) known |= 1u << DEP;
     else failed = true;
   }
+  if (!GATE) {
+    // the last phase also looks at the error word: a wait that ran out anywhere makes this forward's output NaN
+    if (threadIdx.x == 0) sh.last = (int)__hip_atomic_load(a.ctr + C_ERR * CTR_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (sh.last) failed = true;
+    __syncthreads();
+  }
   f32x16 acc[NACC];
 #pragma unroll
   for (int n = 0; n < NACC; ++n)
@@ -314,7 +322,7 @@ __device__ __forceinline__ void dq_whole_phase(DqShared& sh, const DqArgs& a, in
         for (int gq = 0; gq < 2; ++gq) {
           bf16x4 o;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) o[q] = (__bf16)v[0][4 * gq + q];
+          for (int q = 0; q < 4; ++q) o[q] = failed ? (__bf16)__builtin_nanf("") : (__bf16)v[0][4 * gq + q];   // a forward whose wait ran out is visibly wrong
           *reinterpret_cast<bf16x4*>(y + 8 * gq) = o;
         }
       }
@@ -387,6 +395,8 @@ static bool plan_decode(const Plan& p, int64_t M, DqArgs* a) {
   return true;
 }
 
+char* decode_error_word(const Ctx* c) { return c->ws + c->plan.off_cnt + (size_t)C_ERR * CTR_STRIDE * sizeof(unsigned); }
+
 bool bf16_decode_supported(const Ctx* c, int64_t M) {
   DqArgs a;
   return c->n_cus >= 8 && plan_decode(c->plan, M, &a);
@@ -405,6 +415,7 @@ int bf16_decode_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   a.tick1 = reinterpret_cast<int*>(ws + p.off_cnt + CNT_ONE_KERNEL_BYTES);   // the ticket lines of the four-launch path
   a.tick4 = a.tick1 + 2048 * TICKET_STRIDE;
   a.M = (int)M; a.d = (int)p.d; a.r = (int)p.r;
+  a.poll_limit = c->poll_limit >= 0 ? c->poll_limit : POLL_LIMIT;
   static const char* const names[1] = {"k_decode"};
   const int ps = prof_open_forward(c, 1, names);
   const int G = c->n_cus > 0 ? (c->n_cus < 256 ? c->n_cus : 256) : 256;     // one workgroup per CU; any number works

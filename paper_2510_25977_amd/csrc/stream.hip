@@ -49,6 +49,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
   constexpr int NT = NACC * RT;               // accumulator tiles of a wave in all: tile n RT + rt
   constexpr int NTP = NA * RT;                // ... per pass
   // ... staged in LDS per round (32 KiB each).  D2 has more workgroups than CUs: 64 KiB lets two of them share a CU
+  // (the other phases have at most one workgroup per CU and stage up to four tiles, 128 KiB, in one round)
   constexpr int NB = (PH == PH_D2) ? 2 : (NTP < 4 ? NTP : 4);
   constexpr int ROUNDS = NTP / NB;
   // staging of accumulator tiles: [tile][wave][registers 4 p .. 4 p + 3][lane], 16 bytes per lane
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
           if (BOTH) acc[NA - 1][rt] = mfma32(wu[u], au[u][rt], acc[NA - 1][rt]);
         }
     };
-    constexpr int UMAX = (RT * NA <= 2) ? 4 : 2;   // what the register budget (two workgroups per CU) allows
+    constexpr int UMAX = (RT * NA <= 2) ? 4 : 2;   // weight frags in flight per wave that the register budget allows
     int kb = k0;
     if (UMAX >= 4)
       for (; kb + 4 <= k1; kb += 4) step(std::integral_constant<int, UMAX >= 4 ? 4 : 1>{}, kb);
@@ -513,6 +514,22 @@ int bf16_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, hipStre
   const StreamBufs b = {ws + p.off_T, ws + p.off_H, ws + p.off_Td, reinterpret_cast<float*>(ws + p.off_part),
                         reinterpret_cast<int*>(ws + p.off_cnt + CNT_ONE_KERNEL_BYTES)};
   return stream_forward_on(c, b, X, M, Y, st);
+}
+
+// Whether the weight-streaming path takes a forward of M rows of this plan: up to 128 rows, and no more units (output
+// tile x row-tile group) in either split phase than there are ticket lines (2048 per phase: ranks beyond 32768).
+bool stream_supported(const Plan& p, int64_t M) {
+  if (M < 1 || M > STREAM_MAX_M) return false;
+  const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;
+  if (p.kind == SVDMLP_LINEAR) {
+    if (M <= 32 && p.d % 32 == 0 && p.r / 16 <= 2048) return true;   // 16-column tiles
+    const int t1 = (int)(p.r / 32);
+    return t1 * stream_row_groups(rt, t1, (int)(p.d / 16), true) <= 2048;
+  }
+  if (stream_uses_tile16(M, p.d, p.ffn, p.r, p.rd)) return true;     // its own limits are part of that predicate
+  const int t1 = (int)(2 * p.r / 32), t4 = (int)(p.rd / 32);
+  return t1 * stream_row_groups(rt, t1, (int)(p.d / 16), true) <= 2048 &&
+         t4 * stream_row_groups(rt, t4, (int)(p.ffn / 16), false) <= 2048;
 }
 
 static int stream_forward_on(const Ctx* c, const StreamBufs& b, const void* X, int64_t M, void* Y, hipStream_t st) {

@@ -180,6 +180,20 @@ def test_force_plan_checks_its_arguments_and_plan_room_grows_the_workspace(lib):
     assert 20 * 4096 * 512 * 4 <= roomy - plain <= 24 * 4096 * 512 * 4
 
 
+def test_small_batches_fall_back_to_the_tiled_path_when_the_streaming_path_has_no_room():
+    """The weight-streaming path has 2048 ticket lines per split phase; a context whose rank needs more (beyond 32768)
+    is still legal, and its small batches take the MFMA-tiled path instead of failing at the first forward."""
+    big = desc(max_M=128, d=65536, ffn=65536, r=40960, r_down=40960)
+    for M in (1, 16, 33, 128):
+        assert plan_of(big, M).startswith("path=5"), M
+    big.flags |= B.FLAG_FORCE_STREAM
+    with pytest.raises(B.SvdMlpError) as e:
+        B.svdmlp_describe(big, 16)
+    assert e.value.status == B.SVDMLP_UNSUPPORTED
+    ok = desc(max_M=128, d=65536, ffn=65536, r=16384, r_down=16384)
+    assert plan_of(ok, 16).startswith("path=3") and plan_of(ok, 128).startswith("path=3")
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")

@@ -745,6 +745,34 @@ def test_one_kernel_decode_successive_forwards_with_different_inputs():
     assert torch.equal(Y, outs[1]) and torch.equal(Y, outs[5])
 
 
+def test_one_kernel_decode_reports_a_wait_that_ran_out():
+    """Error path of the one-kernel variant, forced from the host: with a poll limit of zero every wait that is not
+    already satisfied gives up at once.  The kernel still ends normally; the forward's output is NaN (never silently
+    partial), svdmlp_check reports the time-out once and clears it, and the next forward with the normal bound is right."""
+    gi = synth.make_gated(8, 512, 1408, 192, 256, stream=58)
+    d = dev()
+    f = {k: v.to(d) for k, v in gi.factors().items()}
+    mlp = B.SvdMlp(max_M=8, flags=B.FLAG_STREAM_ONE_KERNEL, **f)
+    X = gi.X.to(d)
+    good = mlp(X).clone()
+    torch.cuda.synchronize()
+    assert mlp.last_path == 4
+    B.svdmlp_check(mlp.ctx)                                   # nothing to report
+    L = B.lib()
+    assert L.svdmlp_debug_set_poll_limit(mlp.ctx, 0) == 0
+    bad = mlp(X).clone()
+    torch.cuda.synchronize()
+    assert L.svdmlp_check(mlp.ctx) == B.SVDMLP_TIMED_OUT
+    assert L.svdmlp_check(mlp.ctx) == B.SVDMLP_OK             # reported once, then cleared
+    assert bool(torch.isnan(bad.float()).all()), "a forward whose wait ran out must not look like a result"
+    assert L.svdmlp_debug_set_poll_limit(mlp.ctx, -1) == 0
+    again = mlp(X)
+    torch.cuda.synchronize()
+    B.svdmlp_check(mlp.ctx)
+    assert torch.equal(again, good)
+    mlp.close()
+
+
 def test_contexts_on_two_streams_run_concurrently_without_interference():
     """Two contexts (a streaming-path one and a tiled-path one), each with its own workspace, enqueue forwards on two
     streams at the same time; every output equals, bit for bit, what the same context gives when it runs alone."""
