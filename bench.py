@@ -540,7 +540,7 @@ def main():
         kname = "k_stream_d2" if args.workload == "decode" and "k_stream_d2" in cand else max(cand, key=cand.get)
         k_ms = kernels.get(kname, 0.0)
         k_bytes = kbytes[kname]
-        traffic = measured_traffic(kname, "decode_m16_kernel_trace_pmc.txt") if (M, d, ffn, r) == (16, 4096, 14336, 512) else None
+        traffic = measured_traffic(kname, "decode_m16_all_kernels.txt") if (M, d, ffn, r) == (16, 4096, 14336, 512) else None
         if traffic:
             traffic["algorithmic_MB"] = k_bytes / 1e6
         out["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": k_bytes / k_ms / 1e6 if k_ms else None,
@@ -569,8 +569,10 @@ def main():
         k_ms = kernels.get(kname, 0.0)
         k_flops = kflops[kname]
         traffic = None
+        if args.workload == "wide" and M == 2048 and not args.fused:
+            traffic = measured_traffic(kname, "wide_all_kernels.txt")
         if args.workload == "prefill" and M == 4096 and not args.fused:
-            traffic = measured_traffic(kname, f"prefill_r{r}_pmc_traffic_mfma.txt")
+            traffic = measured_traffic(kname, f"prefill_r{r}_all_kernels.txt")
         if traffic:
             traffic["algorithmic_MB"] = kalg[kname] / 1e6
             traffic["times_algorithmic"] = (traffic["read_MB"] + traffic["written_MB"]) / (kalg[kname] / 1e6)

@@ -3,6 +3,8 @@
     python -m paper_2510_25977_amd.profsum stats   <dir>                 # --kernel-trace run: calls, avg / min / max
     python -m paper_2510_25977_amd.profsum traffic <fetch_dir> <write_dir>   # --pmc FETCH_SIZE and --pmc WRITE_SIZE runs
     python -m paper_2510_25977_amd.profsum counters <dir> [<dir> ...]    # any --pmc run: per-kernel averages
+    python -m paper_2510_25977_amd.profsum derived <dir> [<dir> ...]     # --pmc runs that together hold the counters
+                                                                         # below: per-kernel derived figures
 
 ``traffic`` scales both counters by what they read for the plain device copy of known size that
 ``bench.py --copy-calibration`` adds to the run (torch's copy kernel, 256 MiB read and written per launch).
@@ -101,6 +103,47 @@ def cmd_counters(dirs) -> None:
                 print(f"  {k:14s} (n={n[k]:3d}) " + "  ".join(f"{c} {v:.4g}" for c, v in sorted(cs.items())))
 
 
+N_CU, N_XCD = 256, 8
+
+
+def cmd_derived(dirs) -> None:
+    """Per kernel, from counters spread over several runs (averages per launch):
+       cycles        GRBM_GUI_ACTIVE / 8 XCDs: active clocks of the launch
+       mfma_busy     SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x 256 CUs) / cycles
+       coexec        SQ_VALU_MFMA_COEXEC_CYCLES / SQ_VALU_MFMA_BUSY_CYCLES: share of the matrix-core time with a vector-ALU
+                     instruction issued beside it
+       lds_conflict  SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE
+       l2_miss       TCC_MISS / (TCC_HIT + TCC_MISS), stores included
+       fetch         TCP_TCC_READ_REQ x 128 B / (256 CUs x cycles): bytes per clock a CU pulls in from L2
+       latency       TCP_TCC_READ_REQ_LATENCY / TCP_TCC_READ_REQ, clocks
+       in_flight     fetch x latency / 128 B: 128-byte lines a CU has outstanding at L2 on average (Little's law)"""
+    acc = collections.defaultdict(dict)
+    for d in dirs:
+        means, _ = counter_means(d)
+        for k, cs in means.items():
+            acc[k].update(cs)
+    print("derived per kernel (see `profsum derived --help` text in the module for the formulas):")
+    for k, c in acc.items():
+        if not is_ours(k) or "GRBM_GUI_ACTIVE" not in c:
+            continue
+        cyc = c["GRBM_GUI_ACTIVE"] / N_XCD
+        out = [f"cycles {cyc:9.0f}"]
+        if "SQ_VALU_MFMA_BUSY_CYCLES" in c:
+            busy = c["SQ_VALU_MFMA_BUSY_CYCLES"]
+            out.append(f"mfma_busy {busy / (4 * N_CU) / cyc:5.3f}")
+            if busy and "SQ_VALU_MFMA_COEXEC_CYCLES" in c:
+                out.append(f"coexec {c['SQ_VALU_MFMA_COEXEC_CYCLES'] / busy:5.3f}")
+        if c.get("SQ_LDS_IDX_ACTIVE"):
+            out.append(f"lds_conflict {c.get('SQ_LDS_BANK_CONFLICT', 0.0) / c['SQ_LDS_IDX_ACTIVE']:5.3f}")
+        if "TCC_HIT_sum" in c and c["TCC_HIT_sum"] + c["TCC_MISS_sum"] > 0:
+            out.append(f"l2_miss {c['TCC_MISS_sum'] / (c['TCC_HIT_sum'] + c['TCC_MISS_sum']):5.3f}")
+        if c.get("TCP_TCC_READ_REQ_sum"):
+            fetch = c["TCP_TCC_READ_REQ_sum"] * 128.0 / (N_CU * cyc)
+            lat = c["TCP_TCC_READ_REQ_LATENCY_sum"] / c["TCP_TCC_READ_REQ_sum"]
+            out.append(f"fetch {fetch:5.1f} B/clk/CU  latency {lat:6.0f} clk  in_flight {fetch * lat / 128.0:5.1f} lines/CU")
+        print(f"  {k:14s} " + "  ".join(out))
+
+
 def main(argv) -> None:
     if len(argv) >= 3 and argv[1] == "stats":
         cmd_stats(argv[2])
@@ -108,6 +151,8 @@ def main(argv) -> None:
         cmd_traffic(argv[2], argv[3])
     elif len(argv) >= 3 and argv[1] == "counters":
         cmd_counters(argv[2:])
+    elif len(argv) >= 3 and argv[1] == "derived":
+        cmd_derived(argv[2:])
     else:
         raise SystemExit(__doc__)
 

@@ -72,21 +72,54 @@ def test_sqrt_sigma_factors_truncation_error_and_balance():
 
 
 
-def test_tile_model_of_the_compute_unit():
-    """The tile-shape model behind the kernels' block sizes (counterpart of the paper's Eq. 10-11 on a CDNA4 CU),
-    checked against the figures the design quotes and against rocprofv3 measurements of the default workload
-    (profiles/prefill_r512_pmc_traffic_mfma.txt): MFMA-busy fraction 0.31 for the 128 x 128 first stage and 0.53-0.54
-    for the 256 x 256 gate/up kernel at the operand rates measured there."""
+def _derived_rows():
+    """(profile, kernel, {figure: value}) of every 'derived per kernel' line under profiles/ (rocprofv3 counters of
+    bench.py runs, summarised by paper_2510_25977_amd.profsum)."""
+    import re
+    from pathlib import Path
+    rows = []
+    for f in sorted((Path(__file__).resolve().parent.parent / "profiles").glob("*_all_kernels.txt")):
+        block = f.read_text().split("derived per kernel", 1)[1].split("raw counters", 1)[0]
+        for line in block.splitlines()[1:]:
+            m = re.match(r"\s+(k_\w+)\s+(.*)", line)
+            if not m:
+                continue
+            figs = {k: float(v) for k, v in re.findall(r"(\w+)\s+([0-9.]+)", m.group(2))}
+            rows.append((f.name, m.group(1), figs))
+    return rows
+
+
+def test_tile_model_of_the_compute_unit_against_the_profiles():
+    """The tile-shape model behind the kernels' block sizes (counterpart of the paper's Eq. 10-11 on a CDNA4 CU): a
+    tile needs (rows + cols) x 32 operand bytes per contraction block of 16 and feeds rows x cols / 1024 MFMAs of 32
+    clocks on four matrix cores, so a kernel that pulls `fetch` bytes per clock into its CU can keep the matrix cores
+    busy for the fraction fetch / (bytes per MFMA / 8).  Checked against two INDEPENDENT sets of counters of the
+    committed profiles: fetch comes from the L1's request counter (TCP_TCC_READ_REQ x 128 B over the active clocks),
+    the busy fraction from the sequencer (SQ_VALU_MFMA_BUSY_CYCLES)."""
     assert cm.tile_operand_bytes_per_mfma(256, 256) == 256
     assert cm.tile_operand_bytes_per_mfma(128, 256) == 384
     assert cm.tile_operand_bytes_per_mfma(128, 128) == 512
     assert cm.tile_operand_rate_at_mfma_peak(256, 256) == 32
     assert cm.tile_operand_rate_at_mfma_peak(128, 128) == 64
-    # measured: k_s1 pulls ~20 B/clk per CU (4.325e6 requests x 128 B over 256 CUs x 1.06e5 clk) and is 0.308 MFMA-busy
-    assert abs(cm.tile_mfma_fraction(128, 128, 20.0) - 0.31) < 0.01
-    # measured: k_gate_up pulls 17-18 B/clk and is 0.53-0.54 MFMA-busy
-    assert 0.52 < cm.tile_mfma_fraction(256, 256, 17.5) < 0.56
-    assert cm.tile_mfma_fraction(256, 256, 44.0) == 1.0          # the copy rate from L2 alone would not bound it
+    assert cm.tile_mfma_fraction(256, 256, 44.0) == 1.0
     # register file: 256 x 256 is the largest tile with two waves per SIMD; the paper's SBUF limit in this chip's terms
     assert cm.tile_fits_register_file(256, 256) and not cm.tile_fits_register_file(256, 512)
     assert cm.tile_accumulator_bytes(256, 256) == 256 * 1024
+    tile = {"k_s1": (128, 128), "k_gate_up": (256, 256), "k_down1": (256, 256), "k_out": (256, 256)}
+    checked = 0
+    for prof, kernel, f in _derived_rows():
+        if kernel not in tile or not prof.startswith(("prefill", "wide")):
+            continue
+        predicted = cm.tile_mfma_fraction(*tile[kernel], f["fetch"])
+        # the fused gate/up kernel also spends matrix-core-idle time on the SiLU burst, so it sits a little below
+        assert abs(predicted - f["mfma_busy"]) <= 0.07, (prof, kernel, predicted, f)
+        checked += 1
+    assert checked >= 15
+    # what bounds `fetch`: a CU never has more than about 70 lines of 128 B outstanding at L2 (Little's law on the
+    # same counters), so fetch <= 70 x 128 B / latency; the kernels that wait for operands sit at 45 - 70
+    for prof, kernel, f in _derived_rows():
+        if "in_flight" in f:
+            assert f["in_flight"] <= 72.0, (prof, kernel, f)
+            assert abs(f["in_flight"] - cm.lines_in_flight(f["fetch"], f["latency"])) <= 0.6
+    assert cm.fetch_rate_bound(latency_clk=250.0) > 32 > cm.fetch_rate_bound(latency_clk=300.0)   # 256 x 256 tiles need 32 B/clk
+    assert 13.0 < cm.fetch_rate_bound(latency_clk=600.0) < 15.0    # all 256 CUs at HBM latency: ~7 TB/s at 2.1 GHz
