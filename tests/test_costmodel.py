@@ -115,11 +115,12 @@ def test_tile_model_of_the_compute_unit_against_the_profiles():
         assert abs(predicted - f["mfma_busy"]) <= 0.07, (prof, kernel, predicted, f)
         checked += 1
     assert checked >= 15
-    # what bounds `fetch`: a CU never has more than about 70 lines of 128 B outstanding at L2 (Little's law on the
-    # same counters), so fetch <= 70 x 128 B / latency; the kernels that wait for operands sit at 45 - 70
+    # what bounds `fetch`: lines of 128 B a CU has outstanding at L2 (Little's law on the same counters).  The kernels
+    # that wait for operands sit at 58 - 69 in every profile but one (84), nothing is ever above that: fetch is about
+    # 68 x 128 B / latency
     for prof, kernel, f in _derived_rows():
         if "in_flight" in f:
-            assert f["in_flight"] <= 72.0, (prof, kernel, f)
+            assert f["in_flight"] <= 90.0, (prof, kernel, f)
             assert abs(f["in_flight"] - cm.lines_in_flight(f["fetch"], f["latency"])) <= 0.6
     assert cm.fetch_rate_bound(latency_clk=250.0) > 32 > cm.fetch_rate_bound(latency_clk=300.0)   # 256 x 256 tiles need 32 B/clk
     assert 13.0 < cm.fetch_rate_bound(latency_clk=600.0) < 15.0    # all 256 CUs at HBM latency: ~7 TB/s at 2.1 GHz
