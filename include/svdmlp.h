@@ -37,9 +37,15 @@ typedef struct svdmlp_ctx svdmlp_ctx; /* opaque; host memory only */
 
 /* Storage type of X, the six factors and Y.
  *   BF16: bf16 in HBM, fp32 accumulation on the matrix cores, intermediates
- *         (the rank-r strips and the ffn-wide activation) rounded to bf16
- *         round-to-nearest-even, mirroring the paper's 16-bit cached strip
+ *         (the rank-r strips T and Td, the ffn-wide activation H) and Y rounded to
+ *         bf16 round-to-nearest-even, mirroring the paper's 16-bit cached strip
  *         with 4-byte accumulation (Sec. 2.2 "Matmul tiling", Sec. 4.2.1 "Caching").
+ *         The MFMA-tiled path in its default (staged) variant rounds once more:
+ *         SiLU(G) to bf16 before it is multiplied by the up product (the squashed
+ *         gate tile waits in 16-bit pairs while the up tile takes its registers);
+ *         the fused tiled variant and the weight-streaming path form SiLU(G) * P
+ *         in fp32.  So one context's results for M <= 128 and M > 128 differ by
+ *         up to that rounding (about 2^-9 relative per element of H).
  *   F32 : debug path, fp32 storage and fp32 arithmetic everywhere, no matrix cores. */
 enum { SVDMLP_BF16 = 0, SVDMLP_F32 = 1 };
 
