@@ -42,34 +42,41 @@ def test_chosen_plan_is_within_five_percent_of_the_best_candidate(name, kw):
     X = gi.X.to(dev)
     Y = torch.empty_like(X)
     text = B.svdmlp_describe(mlp.desc, dm["M"])
+    for _ in range(60):                       # let the clocks settle before anything is compared
+        mlp(X, Y)
     auto = kernel_times_us(mlp, X, Y)
     first_name = "k_in" if "k_in" in auto else "k_s1"
     last_name = "k_out" if "k_out" in auto else "k_s5"
-    chosen = {"first": auto[first_name], "down": auto["k_down1"] + auto["k_reduce"], "out": auto[last_name]}
-    best = dict(chosen)
-    tried = {"first": 0, "down": 0, "out": 0}
+    # what the planner chose, from its own description
+    m = re.search(r"k_(s1|in)\[tile=\S+ tiles=\d+ ranges=(\d+)", text)
+    chosen_first = (B.FIRST_IN if m.group(1) == "in" else B.FIRST_S1, int(m.group(2)))
+    chosen_down = int(re.search(r"k_down1\[tile=\S+ tiles=\d+ ranges=(\d+)", text).group(1))
+    chosen_out = B.OUT_256 if re.search(r" k_out\[", text) else B.OUT_128
+    # every candidate, the chosen ones among them, forced and timed under the same conditions
+    first, down, out = {}, {}, {}
     for kern in (B.FIRST_S1, B.FIRST_IN):
-        for S in (1, 2, 3, 4, 6, 8):
+        for S in sorted({1, 2, 3, 4, 6, 8, chosen_first[1]}):
             B.svdmlp_force_plan(mlp.ctx, kern, S, 0, 0)
             k = kernel_times_us(mlp, X, Y)
             ran = "k_in" if "k_in" in k else "k_s1"
             if (ran == "k_in") != (kern == B.FIRST_IN):
                 continue          # not a valid candidate at these extents: the planner's own choice ran
-            best["first"] = min(best["first"], k[ran])
-            tried["first"] += 1
-    for s in (1, 2, 4, 6, 8, 12, 16, 24, 32):
-        B.svdmlp_force_plan(mlp.ctx, 0, 0, s, 0)
+            first[(kern, S)] = k[ran]
+    for s_ in sorted({1, 2, 4, 6, 8, 12, 16, 24, 32, chosen_down}):
+        B.svdmlp_force_plan(mlp.ctx, 0, 0, s_, 0)
         k = kernel_times_us(mlp, X, Y)
-        best["down"] = min(best["down"], k["k_down1"] + k["k_reduce"])
-        tried["down"] += 1
+        down[s_] = k["k_down1"] + k.get("k_reduce", 0.0)
     for o in (B.OUT_256, B.OUT_128):
         B.svdmlp_force_plan(mlp.ctx, 0, 0, 0, o)
         k = kernel_times_us(mlp, X, Y)
         ran = "k_out" if "k_out" in k else "k_s5"
         if (ran == "k_out") != (o == B.OUT_256):
             continue
-        best["out"] = min(best["out"], k[ran])
-        tried["out"] += 1
+        out[o] = k[ran]
+    assert first_name == ("k_in" if chosen_first[0] == B.FIRST_IN else "k_s1") and last_name == ("k_out" if chosen_out == B.OUT_256 else "k_s5")
+    chosen = {"first": first[chosen_first], "down": down[chosen_down], "out": out[chosen_out]}
+    best = {"first": min(first.values()), "down": min(down.values()), "out": min(out.values())}
+    tried = {"first": len(first), "down": len(down), "out": len(out)}
     B.svdmlp_force_plan(mlp.ctx, 0, 0, 0, 0)
     again = kernel_times_us(mlp, X, Y)
     mlp.close()
