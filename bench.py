@@ -245,6 +245,13 @@ def measure_roofs(dev, quick=True):
     fl = cus * 8 * 4 * iters * 32768
     out["mfma_bf16"] = {"flop": fl, "ms": t["median"], "TFLOPs": fl / t["median"] / 1e9, "TFLOPs_best": fl / t["min"] / 1e9,
                         "note": "v_mfma_f32_32x32x16_bf16, constant register operands, two waves per SIMD"}
+    # the same issue loop on other operand values: the matrix cores' clock is power-limited and their power follows the
+    # number of operand bits that toggle, so zeros run at the full clock and data like real activations and weights slower
+    for name, mode, note in (("mfma_bf16_zero_operands", B.ROOF_OPERANDS_ZERO, "all-zero register operands"),
+                             ("mfma_bf16_random_operands", B.ROOF_OPERANDS_RANDOM,
+                              "register operands uniform in (-1, 1), different in every lane: the roof of a product of real data")):
+        t = time_batches(lambda: B.svdmlp_roof_mfma_operands(iters, mode, sink.data_ptr(), cus, s), 3, 2, 5)
+        out[name] = {"flop": fl, "ms": t["median"], "TFLOPs": fl / t["median"] / 1e9, "TFLOPs_best": fl / t["min"] / 1e9, "note": note}
 
     # SiLU on one wave of each SIMD under the MFMAs of the other: each half alone, then both
     mi, vi = 6000, 160     # 12000 MFMAs (384 k clocks of matrix core) and 5120 SiLU evaluations per lane
@@ -525,6 +532,7 @@ def main():
         out["measured_roofs"] = roofs
         if args.workload != "decode":
             out["frac_of_measured_mfma_peak"] = flops / ms / 1e9 / roofs["mfma_bf16"]["TFLOPs"]
+            out["frac_of_measured_mfma_peak_random_operands"] = flops / ms / 1e9 / roofs["mfma_bf16_random_operands"]["TFLOPs"]
     if args.workload != "decode":
         out["ms_per_step_with_kernel_events"] = ms_ev
 
@@ -584,6 +592,8 @@ def main():
         if roofs is not None and k_ms:
             out["roofline"]["measured_peak"] = roofs["mfma_bf16"]["TFLOPs"]
             out["roofline"]["frac_of_measured_peak"] = k_flops / k_ms / 1e9 / roofs["mfma_bf16"]["TFLOPs"]
+            out["roofline"]["measured_peak_random_operands"] = roofs["mfma_bf16_random_operands"]["TFLOPs"]
+            out["roofline"]["frac_of_measured_peak_random_operands"] = k_flops / k_ms / 1e9 / roofs["mfma_bf16_random_operands"]["TFLOPs"]
 
     if dec is not None:
         out["decode"] = dec

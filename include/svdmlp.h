@@ -227,6 +227,10 @@ int64_t svdmlp_rank_for_ratio(int64_t k, int64_t n, double ratio, int64_t block,
  *   svdmlp_roof_mfma : `workgroups` workgroups of eight waves, each wave issuing 4 * iters
  *                      v_mfma_f32_32x32x16_bf16 on register operands (four independent accumulators).
  *                      FLOP = workgroups * 8 * 4 * iters * 32768; sink is 4 bytes, never written.
+ *   svdmlp_roof_mfma_operands: the same kernel with a choice of operand VALUES, because the sustained clock of the
+ *                      matrix cores depends on how many operand bits toggle: operands = 0 all zero, 1 a few small
+ *                      values repeating over the lanes (what svdmlp_roof_mfma uses), 2 pseudo-random values uniform
+ *                      in (-1, 1), different in every lane.  The last one is the roof for a product of real data.
  *   svdmlp_roof_coexec: eight waves per workgroup; waves 0..3 issue 2 * mfma_iters MFMAs each, their SIMD partners
  *                      4..7 evaluate SiLU on 32 registers per lane valu_iters times.  With either count 0 that half
  *                      idles: three launches show whether vector-ALU work hides under the partner's MFMAs.
@@ -234,6 +238,7 @@ int64_t svdmlp_rank_for_ratio(int64_t k, int64_t n, double ratio, int64_t block,
  *   svdmlp_roof_empty: a kernel of `workgroups` x `threads` that does nothing (chains of dependent launches). */
 int svdmlp_roof_read(const void *buf, size_t bytes, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_mfma(int iters, void *sink, int workgroups, void *hip_stream);
+int svdmlp_roof_mfma_operands(int iters, int operands, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_coexec(int mfma_iters, int valu_iters, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_empty(int workgroups, int threads, void *hip_stream);
 

@@ -3,7 +3,11 @@
 // "fraction of the roof" can be read against a measured roof as well.
 //   read   : every lane streams 16-byte loads over a buffer (larger than the 256 MB memory-side cache) -> HBM GB/s
 //   mfma   : every wave issues v_mfma_f32_32x32x16_bf16 on register-resident operands, four independent accumulators
-//            -> matrix-core TFLOP/s at the clock the chip sustains under that load
+//            -> matrix-core TFLOP/s at the clock the chip sustains under that load.  The clock is power-limited and
+//            the power of the matrix cores depends on how many operand bits toggle, so the rate depends on the
+//            VALUES: all-zero operands run at the full clock, operands drawn like activations and weights (uniform
+//            in (-1, 1), every mantissa bit alive) about 30 % slower.  The second figure is the roof a GEMM on real
+//            data can reach on this machine.
 //   empty  : a kernel that does nothing, for timing chains of dependent launches (the floor of a forward that is a
 //            sequence of short kernels, as the weight-streaming path is)
 #include "common.h"
@@ -28,27 +32,42 @@ __global__ __launch_bounds__(256) void k_roof_read(const u32x4* __restrict__ src
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = acc[0];
 }
 
-__global__ __launch_bounds__(512) void k_roof_mfma(int iters, float* __restrict__ sink) {
+// operands: 0 all zero, 1 a few small values that repeat over the lanes (few bits toggle), 2 pseudo-random values
+// uniform in (-1, 1), different in every lane, wave and workgroup
+__global__ __launch_bounds__(512) void k_roof_mfma(int iters, int operands, float* __restrict__ sink) {
   const int lane = threadIdx.x % 64;
-  bf16x8 a, b;
+  bf16x8 a0, a1, b0, b1;
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    a[s] = (__bf16)(0.001f * (float)((lane + s) % 7));
-    b[s] = (__bf16)(0.002f * (float)((lane * 3 + s) % 5));
+    float x0 = 0.f, x1 = 0.f, y0 = 0.f, y1 = 0.f;
+    if (operands == 1) {
+      x0 = x1 = 0.001f * (float)((lane + s) % 7);
+      y0 = y1 = 0.002f * (float)((lane * 3 + s) % 5);
+    } else if (operands == 2) {
+      unsigned h = ((unsigned)blockIdx.x * 512u + threadIdx.x) * 8u + (unsigned)s + 1u;
+      float u[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {  // four rounds of an integer hash, one value each
+        h *= 2654435761u; h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        u[q] = (float)(int)h * (1.0f / 2147483648.0f);
+      }
+      x0 = u[0]; x1 = u[1]; y0 = u[2]; y1 = u[3];
+    }
+    a0[s] = (__bf16)x0; a1[s] = (__bf16)x1; b0[s] = (__bf16)y0; b1[s] = (__bf16)y1;
   }
   f32x16 c0, c1, c2, c3;
 #pragma unroll
   for (int e = 0; e < 16; ++e) { c0[e] = 0.f; c1[e] = 0.f; c2[e] = 0.f; c3[e] = 0.f; }
   for (int i = 0; i < iters; ++i) {
-    c0 = mfma32(a, b, c0);
-    c1 = mfma32(a, b, c1);
-    c2 = mfma32(a, b, c2);
-    c3 = mfma32(a, b, c3);
+    c0 = mfma32(a0, b0, c0);
+    c1 = mfma32(a1, b0, c1);
+    c2 = mfma32(a0, b1, c2);
+    c3 = mfma32(a1, b1, c3);
   }
   float s = 0.f;
 #pragma unroll
   for (int e = 0; e < 16; ++e) s += c0[e] + c1[e] + c2[e] + c3[e];
-  if (s == -1.0f) sink[0] = s;   // never true: the products are non-negative
+  if (s == -1.0f) sink[0] = s;   // keeps the accumulators alive; the sums are not -1 for any of the three operand sets
 }
 
 // Waves 0..3 of a workgroup (one per SIMD) issue MFMAs as in k_roof_mfma; waves 4..7, their SIMD partners, evaluate
@@ -108,12 +127,16 @@ int svdmlp_roof_read(const void* buf, size_t bytes, void* sink, int workgroups, 
   return SVDMLP_OK;
 }
 
-int svdmlp_roof_mfma(int iters, void* sink, int workgroups, void* hip_stream) {
-  if (!sink || iters <= 0 || workgroups <= 0) return SVDMLP_INVALID_ARGUMENT;
-  hipLaunchKernelGGL(k_roof_mfma, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(hip_stream), iters,
+int svdmlp_roof_mfma_operands(int iters, int operands, void* sink, int workgroups, void* hip_stream) {
+  if (!sink || iters <= 0 || workgroups <= 0 || operands < 0 || operands > 2) return SVDMLP_INVALID_ARGUMENT;
+  hipLaunchKernelGGL(k_roof_mfma, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(hip_stream), iters, operands,
                      static_cast<float*>(sink));
   if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
   return SVDMLP_OK;
+}
+
+int svdmlp_roof_mfma(int iters, void* sink, int workgroups, void* hip_stream) {
+  return svdmlp_roof_mfma_operands(iters, 1, sink, workgroups, hip_stream);
 }
 
 int svdmlp_roof_coexec(int mfma_iters, int valu_iters, void* sink, int workgroups, void* hip_stream) {
