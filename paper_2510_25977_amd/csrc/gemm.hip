@@ -41,6 +41,13 @@ constexpr int G_THREADS = 512;
 
 // 16 bytes per lane, global -> LDS, with a wave-uniform 64-bit base in SGPRs and a 32-bit per-lane offset:
 // no vector ALU work per copy.  M0 carries the (wave-uniform) LDS destination; lane l lands at M0 + 16 l.
+// The compiler does not look into the asm, so it does not know that the instruction reads the base SGPRs as a memory
+// address: a base that a vector instruction has just written (v_readfirstlane, or v_readlane when the compiler
+// restores a spilled SGPR) must be five wait states old by then, and nothing here waits (a leading s_nop was
+// measured: +2 % on k_gate_up, whose memory phases start with these copies).  An experimental build whose register
+// pressure put such a restore right before a store took a memory fault, so the build step checks the generated
+// assembly of this file for that pattern (build.py, check_sgpr_hazards) and fails if it finds one; the same holds
+// for the stores below.
 __device__ __forceinline__ void dma16_sv(const char* sbase, unsigned voff, unsigned lds_dst) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(sbase), "v"(voff), "s"(lds_dst) : "memory", "m0");
 }

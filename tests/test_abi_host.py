@@ -360,3 +360,41 @@ def test_rank_for_ratio_follows_the_rank_rule():
     for bad in [(0, 8, 0.1, 128, 0.5), (8, -1, 0.1, 128, 0.5), (8, 8, 1.0, 128, 0.5), (8, 8, -0.1, 128, 0.5), (8, 8, 0.1, 0, 0.5),
                 (8, 8, 0.1, 128, 1.5), (8, 8, float("nan"), 128, 0.5)]:
         assert B.lib().svdmlp_rank_for_ratio(*bad) == -1
+
+
+def test_build_step_catches_an_sgpr_written_by_a_vector_instruction_right_before_a_handwritten_store():
+    """The hand-written copies and stores take their base address in SGPRs inside an asm statement, where the compiler
+    cannot see the five wait states that a vector-written SGPR needs before a memory instruction reads it.  The build
+    checks the generated assembly; this pins the checker on the pattern that once faulted (a spilled SGPR restored by
+    v_readlane directly before the store) and on the variants that are fine."""
+    from paper_2510_25977_amd import build as bld
+    bad = """
+	v_cvt_pk_bf16_f32 v83, v83, v84
+	v_readlane_b32 s5, v245, 2
+	;;#ASMSTART
+	global_store_dwordx4 v240, v[80:83], s[4:5] nt
+	s_nop 1
+	;;#ASMEND
+"""
+    assert len(bld.check_sgpr_hazards(bad)) == 1
+    # five wait states in between (s_nop 3 = four, plus one other instruction): fine
+    assert bld.check_sgpr_hazards(bad.replace(";;#ASMSTART", "s_nop 3\n\tv_mov_b32 v1, v2\n\t;;#ASMSTART")) == []
+    # four are not enough
+    assert len(bld.check_sgpr_hazards(bad.replace(";;#ASMSTART", "s_nop 3\n\t;;#ASMSTART"))) == 1
+    # another register, a scalar write, or the compiler's own store (outside an asm statement) are not findings
+    assert bld.check_sgpr_hazards(bad.replace("s5, v245", "s7, v245")) == []
+    assert bld.check_sgpr_hazards(bad.replace("v_readlane_b32 s5, v245, 2", "s_add_u32 s5, s5, 1")) == []
+    assert bld.check_sgpr_hazards(bad.replace(";;#ASMSTART", "").replace(";;#ASMEND", "")) == []
+    # the copy into LDS: its own s_mov / s_nop count as two of the five
+    dma = """
+	v_readfirstlane_b32 s34, v3
+	s_add_i32 s9, s9, 1
+	s_add_i32 s9, s9, 1
+	;;#ASMSTART
+	s_mov_b32 m0, s96
+	s_nop 0
+	global_load_lds_dwordx4 v240, s[34:35]
+	;;#ASMEND
+"""
+    assert len(bld.check_sgpr_hazards(dma)) == 1
+    assert bld.check_sgpr_hazards(dma.replace("s_add_i32 s9, s9, 1\n\ts_add_i32 s9, s9, 1", "s_nop 2")) == []
