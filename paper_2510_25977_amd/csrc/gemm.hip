@@ -9,9 +9,11 @@
 //
 // Why not keep H in registers: a workgroup that owns every rank column of its rows (so that H never has to be
 // stored) has room for only 128 rows, and then each byte brought into the CU feeds too few MFMAs.  A CU pulls
-// operands in at a bounded rate (measured: 44 B/clk from L2 at best, about 20 B/clk at these kernels' L2 miss rates,
-// where eight waves of MFMAs on a 256 x 256 tile take 32 B/clk): the operand bytes per MFMA decide the speed.  A 256 x 256 tile needs 16 KiB of operands per
-// 64 MFMAs, a quarter of what the 128-row fused tile needs per MFMA.  The price is one write and one read of H.
+// operands in at a bounded rate (measured: 44 B/clk from L2 at best, 20 - 25 B/clk at these kernels' L2 miss rates),
+// and the matrix cores, whose clock is power-limited, take 256 x 256 tiles of real data at about 22 B/clk (they would
+// take 32 B/clk on all-zero operands): with 16 KiB of operands per 64 MFMAs the 256 x 256 tile is just fed, the
+// 128-row fused tile, which needs two to four times the bytes per MFMA, is not.  The price is one write and one read
+// of H.
 //
 // Both kernels are one machine: eight waves, two per SIMD, 128 accumulator registers per lane; wave w owns rows
 // 128 (w / 4).. and columns 64 (w % 4).. of the tile.  Operands arrive as 1 KiB frags (common.h).  A "unit" is one
