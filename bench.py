@@ -253,6 +253,14 @@ def measure_roofs(dev, quick=True):
         t = time_batches(lambda: B.svdmlp_roof_mfma_operands(iters, mode, sink.data_ptr(), cus, s), 3, 2, 5)
         out[name] = {"flop": fl, "ms": t["median"], "TFLOPs": fl / t["median"] / 1e9, "TFLOPs_best": fl / t["min"] / 1e9, "note": note}
 
+    # the phase skeleton of the 256 x 256 tile kernels on LDS-resident operands, nothing copied
+    steps = 4000
+    flp = cus * 8 * 16 * steps * 32768
+    for name, mode in (("tile_skeleton_zero_operands", B.ROOF_OPERANDS_ZERO), ("tile_skeleton_random_operands", B.ROOF_OPERANDS_RANDOM)):
+        t = time_batches(lambda: B.svdmlp_roof_pingpong(steps, mode, sink.data_ptr(), cus, s), 3, 2, 5)
+        out[name] = {"flop": flp, "ms": t["median"], "TFLOPs": flp / t["median"] / 1e9, "TFLOPs_best": flp / t["min"] / 1e9,
+                     "note": "eight waves in two alternating phases (12 LDS frag reads / 16 MFMAs), two barriers per step, no copies"}
+
     # SiLU on one wave of each SIMD under the MFMAs of the other: each half alone, then both
     mi, vi = 6000, 160     # 12000 MFMAs (384 k clocks of matrix core) and 5120 SiLU evaluations per lane
     co = {}

@@ -231,6 +231,11 @@ int64_t svdmlp_rank_for_ratio(int64_t k, int64_t n, double ratio, int64_t block,
  *                      matrix cores depends on how many operand bits toggle: operands = 0 all zero, 1 a few small
  *                      values repeating over the lanes (what svdmlp_roof_mfma uses), 2 pseudo-random values uniform
  *                      in (-1, 1), different in every lane.  The last one is the roof for a product of real data.
+ *   svdmlp_roof_pingpong: the phase skeleton of the 256 x 256 tile kernels with nothing to copy: `workgroups`
+ *                      workgroups of eight waves, the two waves of a SIMD alternating between reading twelve operand
+ *                      frags from LDS and sixteen MFMAs, two barriers per step, `steps` steps; LDS filled once with
+ *                      operands as above (0 zeros, 1 few values, 2 random).  FLOP = workgroups * 8 * 16 * steps * 32768;
+ *                      sink is 4 bytes, never written.
  *   svdmlp_roof_coexec: eight waves per workgroup; waves 0..3 issue 2 * mfma_iters MFMAs each, their SIMD partners
  *                      4..7 evaluate SiLU on 32 registers per lane valu_iters times.  With either count 0 that half
  *                      idles: three launches show whether vector-ALU work hides under the partner's MFMAs.
@@ -239,6 +244,7 @@ int64_t svdmlp_rank_for_ratio(int64_t k, int64_t n, double ratio, int64_t block,
 int svdmlp_roof_read(const void *buf, size_t bytes, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_mfma(int iters, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_mfma_operands(int iters, int operands, void *sink, int workgroups, void *hip_stream);
+int svdmlp_roof_pingpong(int steps, int operands, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_coexec(int mfma_iters, int valu_iters, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_empty(int workgroups, int threads, void *hip_stream);
 

@@ -28,7 +28,7 @@ EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
            "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio",
            "svdmlp_forward_static_scratch", "svdmlp_static_scratch_bytes",
-           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_mfma_operands", "svdmlp_roof_empty", "svdmlp_force_plan", "svdmlp_roof_coexec", "svdmlp_check", "svdmlp_debug_set_poll_limit"]
+           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_mfma_operands", "svdmlp_roof_pingpong", "svdmlp_roof_empty", "svdmlp_force_plan", "svdmlp_roof_coexec", "svdmlp_check", "svdmlp_debug_set_poll_limit"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_roof_mfma.restype = ctypes.c_int
         L.svdmlp_roof_mfma_operands.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
         L.svdmlp_roof_mfma_operands.restype = ctypes.c_int
+        L.svdmlp_roof_pingpong.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+        L.svdmlp_roof_pingpong.restype = ctypes.c_int
         L.svdmlp_roof_coexec.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
         L.svdmlp_roof_coexec.restype = ctypes.c_int
         L.svdmlp_roof_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
@@ -178,6 +180,11 @@ ROOF_OPERANDS_ZERO, ROOF_OPERANDS_CONSTANT, ROOF_OPERANDS_RANDOM = 0, 1, 2
 def svdmlp_roof_mfma_operands(iters: int, operands: int, sink_ptr: int, workgroups: int, stream_ptr: int = 0) -> None:
     _check(lib().svdmlp_roof_mfma_operands(int(iters), int(operands), ctypes.c_void_p(sink_ptr), int(workgroups),
                                            ctypes.c_void_p(stream_ptr)), "svdmlp_roof_mfma_operands")
+
+
+def svdmlp_roof_pingpong(steps: int, operands: int, sink_ptr: int, workgroups: int, stream_ptr: int = 0) -> None:
+    _check(lib().svdmlp_roof_pingpong(int(steps), int(operands), ctypes.c_void_p(sink_ptr), int(workgroups),
+                                      ctypes.c_void_p(stream_ptr)), "svdmlp_roof_pingpong")
 
 
 def svdmlp_roof_coexec(mfma_iters: int, valu_iters: int, sink_ptr: int, workgroups: int, stream_ptr: int = 0) -> None:

@@ -38,9 +38,37 @@ def test_mfma_roof_depends_on_operand_values():
     assert rnd < 0.9 * zero, (zero, rnd)
 
 
+def test_tile_skeleton_without_copies_reaches_the_matrix_cores_rate():
+    """Barriers and LDS reads of the two-phase tile skeleton cost next to nothing: on zeros it runs at the published
+    peak, on random operands at the rate the register-operand loop reaches on random operands (within 10 %)."""
+    dev = torch.device("cuda:0")
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    s = torch.cuda.current_stream().cuda_stream
+    steps = 2000
+    rate = {}
+    for mode in (B.ROOF_OPERANDS_ZERO, B.ROOF_OPERANDS_RANDOM):
+        best = 0.0
+        for _ in range(6):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            B.svdmlp_roof_pingpong(steps, mode, sink.data_ptr(), cus, s)
+            b.record()
+            b.synchronize()
+            best = max(best, cus * 8 * 16 * steps * 32768 / (a.elapsed_time(b) * 1e-3) / 1e12)
+        rate[mode] = best
+    assert int(sink.abs().sum().item()) == 0
+    assert rate[B.ROOF_OPERANDS_ZERO] > 0.9 * mfma_tflops(B.ROOF_OPERANDS_ZERO), rate
+    assert rate[B.ROOF_OPERANDS_RANDOM] > 0.9 * mfma_tflops(B.ROOF_OPERANDS_RANDOM), rate
+    assert rate[B.ROOF_OPERANDS_RANDOM] < 0.9 * rate[B.ROOF_OPERANDS_ZERO], rate
+
+
 def test_roof_entry_points_check_their_arguments():
     sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     for bad in (dict(iters=0, operands=1), dict(iters=10, operands=3), dict(iters=10, operands=-1)):
         with pytest.raises(B.SvdMlpError) as e:
             B.svdmlp_roof_mfma_operands(bad["iters"], bad["operands"], sink.data_ptr(), 4)
+        assert e.value.status == B.SVDMLP_INVALID_ARGUMENT
+        with pytest.raises(B.SvdMlpError) as e:
+            B.svdmlp_roof_pingpong(bad["iters"], bad["operands"], sink.data_ptr(), 4)
         assert e.value.status == B.SVDMLP_INVALID_ARGUMENT
