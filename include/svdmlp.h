@@ -240,13 +240,16 @@ int64_t svdmlp_rank_for_ratio(int64_t k, int64_t n, double ratio, int64_t block,
  *                      4..7 evaluate SiLU on 32 registers per lane valu_iters times.  With either count 0 that half
  *                      idles: three launches show whether vector-ALU work hides under the partner's MFMAs.
  *                      sink is 8 bytes, never written.
- *   svdmlp_roof_empty: a kernel of `workgroups` x `threads` that does nothing (chains of dependent launches). */
+ *   svdmlp_roof_empty: a kernel of `workgroups` x `threads` that does nothing (chains of dependent launches).
+ *   svdmlp_roof_empty_chain: `launches` such kernels enqueued back to back from one call (no caller overhead between
+ *                      them): what a dependent launch costs on the device. */
 int svdmlp_roof_read(const void *buf, size_t bytes, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_mfma(int iters, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_mfma_operands(int iters, int operands, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_pingpong(int steps, int operands, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_coexec(int mfma_iters, int valu_iters, void *sink, int workgroups, void *hip_stream);
 int svdmlp_roof_empty(int workgroups, int threads, void *hip_stream);
+int svdmlp_roof_empty_chain(int launches, int workgroups, int threads, void *hip_stream);
 
 /* ABI version of this header (bumped on any incompatible change). */
 int svdmlp_abi_version(void);

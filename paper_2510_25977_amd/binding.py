@@ -28,7 +28,7 @@ EXPORTS = ["svdmlp_workspace_bytes", "svdmlp_create", "svdmlp_forward", "svdmlp_
            "svdmlp_last_hip_error", "svdmlp_last_path", "svdmlp_abi_version", "svdmlp_profile_begin",
            "svdmlp_profile_end", "svdmlp_profile_kernel_name", "svdmlp_describe", "svdmlp_rank_for_ratio",
            "svdmlp_forward_static_scratch", "svdmlp_static_scratch_bytes",
-           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_mfma_operands", "svdmlp_roof_pingpong", "svdmlp_roof_empty", "svdmlp_force_plan", "svdmlp_roof_coexec", "svdmlp_check", "svdmlp_debug_set_poll_limit"]
+           "svdmlp_roof_read", "svdmlp_roof_mfma", "svdmlp_roof_mfma_operands", "svdmlp_roof_pingpong", "svdmlp_roof_empty", "svdmlp_roof_empty_chain", "svdmlp_force_plan", "svdmlp_roof_coexec", "svdmlp_check", "svdmlp_debug_set_poll_limit"]
 
 
 class svdmlp_desc(ctypes.Structure):
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.svdmlp_roof_coexec.restype = ctypes.c_int
         L.svdmlp_roof_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         L.svdmlp_roof_empty.restype = ctypes.c_int
+        L.svdmlp_roof_empty_chain.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        L.svdmlp_roof_empty_chain.restype = ctypes.c_int
         L.svdmlp_debug_set_poll_limit.argtypes = [ctypes.c_void_p, ctypes.c_int32]
         L.svdmlp_debug_set_poll_limit.restype = ctypes.c_int
         L.svdmlp_check.argtypes = [ctypes.c_void_p]
@@ -194,6 +196,11 @@ def svdmlp_roof_coexec(mfma_iters: int, valu_iters: int, sink_ptr: int, workgrou
 
 def svdmlp_roof_empty(workgroups: int, threads: int, stream_ptr: int = 0) -> None:
     _check(lib().svdmlp_roof_empty(int(workgroups), int(threads), ctypes.c_void_p(stream_ptr)), "svdmlp_roof_empty")
+
+
+def svdmlp_roof_empty_chain(launches: int, workgroups: int, threads: int, stream_ptr: int = 0) -> None:
+    _check(lib().svdmlp_roof_empty_chain(int(launches), int(workgroups), int(threads), ctypes.c_void_p(stream_ptr)),
+           "svdmlp_roof_empty_chain")
 
 
 def svdmlp_force_plan(ctx, first_kernel: int = 0, first_ranges: int = 0, down_ranges: int = 0, out_kernel: int = 0) -> None:

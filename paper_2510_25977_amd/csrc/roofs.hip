@@ -249,4 +249,12 @@ int svdmlp_roof_empty(int workgroups, int threads, void* hip_stream) {
   return SVDMLP_OK;
 }
 
+int svdmlp_roof_empty_chain(int launches, int workgroups, int threads, void* hip_stream) {
+  if (launches <= 0 || workgroups <= 0 || threads <= 0 || threads > 1024) return SVDMLP_INVALID_ARGUMENT;
+  for (int i = 0; i < launches; ++i)
+    hipLaunchKernelGGL(k_roof_empty, dim3(workgroups), dim3(threads), 0, static_cast<hipStream_t>(hip_stream), (int*)nullptr);
+  if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
+  return SVDMLP_OK;
+}
+
 }  // extern "C"
