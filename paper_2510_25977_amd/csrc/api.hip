@@ -252,10 +252,12 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
     if (!stream_supported(p, M)) return SVDMLP_UNSUPPORTED;
     const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;
     const int t1 = (int)(p.r / 32), t5 = (int)(p.ffn / 32);
-    if (M <= 32 && p.d % 32 == 0 && p.r / 16 <= 2048)
-      put("path=7 bf16-linear-streaming: row_tiles=%d k_stream_d1[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt,
-          2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t5, stream_row_groups_whole(rt, t5));
-    else {
+    if (M <= 32 && p.d % 32 == 0 && p.r / 16 <= 2048) {
+      put("path=7 bf16-linear-streaming: row_tiles=%d k_stream_d1[tile=16 tiles=%d ranges=%d]", rt,
+          2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)));
+      if (stream_last_uses_tile16(true, t5)) put(" k_stream_d5[tile=16 tiles=%d]", 2 * t5);
+      else put(" k_stream_d5[tiles=%d row_groups=%d]", t5, stream_row_groups_whole(rt, t5));
+    } else {
       const int g1 = stream_row_groups(rt, t1, (int)(p.d / 16), true);
       put("path=7 bf16-linear-streaming: row_tiles=%d k_stream_d1[tiles=%d row_groups=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt,
           t1, g1, stream_splits(t1 * g1, (int)(p.d / 16), rt / g1), t5, stream_row_groups_whole(rt, t5));
@@ -274,11 +276,13 @@ int svdmlp_describe(const svdmlp_desc* desc, int64_t M, char* buf, size_t buf_by
     if (stream_path) {
       const int rt = M <= 32 ? 1 : M <= 64 ? 2 : 4;
       const int t1 = (int)(2 * p.r / 32), t2 = (int)(p.ffn / 32), t4 = (int)(p.rd / 32), t5 = (int)(p.d / 32);
-      if (stream_uses_tile16(M, p.d, p.ffn, p.r, p.rd))   // the two split phases on 16-column tiles
+      if (stream_uses_tile16(M, p.d, p.ffn, p.r, p.rd)) {   // the two split phases (and a short last one) on 16-column tiles
         put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tile=16 tiles=%d ranges=%d] k_stream_d2[tiles=%d]"
-            " k_stream_d4[tile=16 tiles=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt, 2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t2,
-            2 * t4, stream_splits16(2 * t4, (int)(p.ffn / 32), stream_tiles16(M)), t5, stream_row_groups_whole(rt, t5));
-      else {
+            " k_stream_d4[tile=16 tiles=%d ranges=%d]", rt, 2 * t1, stream_splits16(2 * t1, (int)(p.d / 32), stream_tiles16(M)), t2,
+            2 * t4, stream_splits16(2 * t4, (int)(p.ffn / 32), stream_tiles16(M)));
+        if (stream_last_uses_tile16(true, t5)) put(" k_stream_d5[tile=16 tiles=%d]", 2 * t5);
+        else put(" k_stream_d5[tiles=%d row_groups=%d]", t5, stream_row_groups_whole(rt, t5));
+      } else {
         const int g1 = stream_row_groups(rt, t1, (int)(p.d / 16), true), g4 = stream_row_groups(rt, t4, (int)(p.ffn / 16), false);
         put("path=3 bf16-streaming: row_tiles=%d k_stream_d1[tiles=%d row_groups=%d ranges=%d] k_stream_d2[tiles=%d]"
             " k_stream_d4[tiles=%d row_groups=%d ranges=%d] k_stream_d5[tiles=%d row_groups=%d]", rt, t1, g1,

@@ -207,6 +207,7 @@ constexpr int STREAM_MAX_M = 128;
 int stream_splits(int tiles, int KB, int rt);
 int stream_row_groups(int rt, int tiles, int KB, bool first);   // first: phase D1 (else D4)
 int stream_row_groups_whole(int rt, int tiles);
+bool stream_last_uses_tile16(bool tile16, int tiles32);   // the last product on 16-column tiles as well
 int stream_splits16(int tiles, int KB2, int mt);
 int stream_tiles16(int64_t M);
 bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd);   // rows the weight-streaming path takes (four 32-row tiles)

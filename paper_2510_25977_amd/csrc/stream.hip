@@ -257,8 +257,9 @@ __global__ __launch_bounds__(SW * 64) void k_stream(StreamArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// D1 and D4: the same products on 16 x 16 x 32 MFMAs, one 16-column output tile per workgroup group.
-// These two phases split their contraction over workgroups, and what the split costs (the partial tile written
+// D1, D4 (and D5 while it has fewer than 256 tiles of 32 columns): the same products on 16 x 16 x 32 MFMAs, one
+// 16-column output tile per workgroup group.
+// D1 and D4 split their contraction over workgroups, and what the split costs (the partial tile written
 // through, and above all the read-back of all S partial tiles by one workgroup, past its L2 and through one CU's
 // bounded fetch rate) goes with the tile size: a 16 x 16 fp32 tile is 1 KiB instead of 4 KiB, and twice as many
 // tiles need half as many ranges.  The weight frags are the same ones (32 rows x 16 k, lane-major): a 16-row
@@ -272,7 +273,7 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 
 template <int PH, int MT>   // MT = 16-row tiles of the batch (M <= 16 MT <= 32)
 __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
-  static_assert(PH == PH_D1 || PH == PH_D4, "only the phases that split their contraction over workgroups");
+  static_assert(PH == PH_D1 || PH == PH_D4 || PH == PH_D5, "the phases with a short row of output tiles");
   static_assert(MT == 1 || MT == 2, "one 32-row activation tile");
   __shared__ f32x4 red[SW][MT][64];
   __shared__ int s_last;
@@ -387,6 +388,20 @@ __global__ __launch_bounds__(SW * 64) void k_stream16(StreamArgs a) {
   } else if (w != 0) {
     return;
   }
+  if (PH == PH_D5) {
+    // lane (m, g) holds columns 16 tile + 4 g .. + 3 of row 16 mt + m: eight bytes of Y
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = 16 * mt + i;
+      if (row < a.M) {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[mt][e];
+        *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(a.out) + (size_t)row * a.ldx + 16 * tile + 4 * g) = o;
+      }
+    }
+    return;
+  }
   // The tile is contraction block `frag` of the next product's activation, in chain order: element s of frag lane
   // (row, h) is column 8 (s / 4) + 4 h + s % 4, i.e. the four values of lane (m, g = h), then those of lane (m, g = 2 + h).
   // Per 32-row tile: lanes 0..31 of this wave write the frag lanes of its rows 0..15, lanes 32..63 those of its rows
@@ -441,6 +456,11 @@ bool stream_uses_tile16(int64_t M, int64_t d, int64_t ffn, int64_t r, int64_t rd
   // save (the 32-column tiles with row-tile groups of their own measure faster there)
   return M <= 32 && d % 32 == 0 && ffn % 32 == 0 && 2 * r / 16 <= 2048 && rd / 16 <= 2048;
 }
+
+// The last product on 16-column tiles too: while the 32-column tiles would leave CUs without a workgroup (a phase
+// streams its weights at the chip's rate only if every CU pulls: 128 of 256 CUs reach 3.6 of 7.1 TB/s).  Measured at
+// the decode shape (128 -> 256 workgroups for 4 MB of Vd): the forward 0.9 us shorter at 1..16 rows, 0.55 us at 32.
+bool stream_last_uses_tile16(bool tile16, int tiles32) { return tile16 && tiles32 < 256; }
 
 // Row-tile groups of the two split phases (k_stream; `rt` row tiles in the batch, `tiles` 32-column tiles, KB
 // contraction blocks).  With all row tiles in one workgroup the weights are fetched once, but the workgroup that adds
@@ -591,7 +611,12 @@ static int stream_forward_on(const Ctx* c, const StreamBufs& b, const void* X, i
                  (int)p.d, (int)p.r, 0, fTd, 0, 1};
   a.rtw = stream_row_groups_whole(rt, a.tiles);
   prof_mark(c, ps, 3, 0, st);
-  launch_stream<PH_D5>(rt / a.rtw, a, st);
+  if (stream_last_uses_tile16(t16, a.tiles)) {
+    a.tiles *= 2;
+    launch_stream16<PH_D5>(mt16, a, st);
+  } else {
+    launch_stream<PH_D5>(rt / a.rtw, a, st);
+  }
   prof_mark(c, ps, 3, 1, st);
   return (int)hipGetLastError();
 }
@@ -709,7 +734,12 @@ int bf16_linear_stream_forward(const Ctx* c, const void* X, int64_t M, void* Y, 
                  (int)p.ffn, (int)p.r, 0, fT, 0, 1};
   a.rtw = stream_row_groups_whole(rt, a.tiles);
   prof_mark(c, ps, 1, 0, st);
-  launch_stream<PH_D5>(rt / a.rtw, a, st);
+  if (stream_last_uses_tile16(t16, a.tiles)) {
+    a.tiles *= 2;
+    launch_stream16<PH_D5>(mt16, a, st);
+  } else {
+    launch_stream<PH_D5>(rt / a.rtw, a, st);
+  }
   prof_mark(c, ps, 1, 1, st);
   return (int)hipGetLastError();
 }

@@ -232,10 +232,10 @@ def test_describe_names_the_plan_of_every_baseline_config():
     assert "k_s1[tile=128x128 tiles=256 ranges=1]" in s
     assert "k_gate_up[tile=256x256 tiles=896 workgroups=256 full=768 halves=256 xcd_grid=4x2]" in s
     assert "k_down1[tile=256x256 tiles=32 ranges=8] k_reduce k_out[tile=256x256 tiles=256]" in s
-    # decode shape: one row tile, both split phases fill the chip
+    # decode shape: one row tile, both split phases fill the chip, and so does the last product on 16-column tiles
     s = plan_of(pre, 16)
     assert s.startswith("path=3 bf16-streaming: row_tiles=1 k_stream_d1[tile=16 tiles=64 ranges=4] k_stream_d2[tiles=448]")
-    assert "k_stream_d4[tile=16 tiles=32 ranges=8] k_stream_d5[tiles=128 row_groups=1]" in s
+    assert "k_stream_d4[tile=16 tiles=32 ranges=8] k_stream_d5[tile=16 tiles=256]" in s
     assert plan_of(pre, 32) == s
     # two row tiles: 32-column tiles, each row tile with workgroups of its own in the two cut phases and in the last one
     s = plan_of(pre, 33)
