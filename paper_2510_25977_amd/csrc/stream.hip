@@ -1,7 +1,8 @@
 // bf16 weight-streaming (decode) path: M <= 128 rows, weight-bandwidth bound.
 //
-// Each of the four products of the factored MLP (paper Alg. 2) is one launch of k_stream (D1 and D4 up to 32 rows:
-// k_stream16, 16-column tiles; from 33 rows on the row tiles of D1, D4 and D5 may get workgroups of their own):
+// Each of the four products of the factored MLP (paper Alg. 2) is one launch of k_stream (up to 32 rows D1, D4 and,
+// while it has fewer than 256 tiles of 32 columns, D5: k_stream16, 16-column tiles; from 33 rows on the row tiles of
+// D1, D4 and D5 may get workgroups of their own):
 //   D1  T^T  = [Ug|Uu]^T X^T          split-K over d
 //   D2  H^T  = SiLU(Vg^T Tg^T) .* (Vu^T Tu^T)
 //   D4  Td^T = Ud^T H^T               split-K over ffn
