@@ -398,3 +398,34 @@ def test_build_step_catches_an_sgpr_written_by_a_vector_instruction_right_before
 """
     assert len(bld.check_sgpr_hazards(dma)) == 1
     assert bld.check_sgpr_hazards(dma.replace("s_add_i32 s9, s9, 1\n\ts_add_i32 s9, s9, 1", "s_nop 2")) == []
+
+
+def test_roof_entry_points_reject_bad_arguments_before_any_launch(lib):
+    """The roof microbenchmarks validate their arguments on the host: nothing is enqueued for a null sink, a count
+    that is not positive, an operand set outside 0..2, more than 1024 threads or a misaligned buffer."""
+    sink, buf = ctypes.c_void_p(0x4000), ctypes.c_void_p(0x10000)
+    bad = B.SVDMLP_INVALID_ARGUMENT
+    for fn in (lib.svdmlp_roof_mfma_operands, lib.svdmlp_roof_pingpong):
+        fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+        assert fn(0, 1, sink, 4, None) == bad
+        assert fn(8, 3, sink, 4, None) == bad
+        assert fn(8, -1, sink, 4, None) == bad
+        assert fn(8, 1, None, 4, None) == bad
+        assert fn(8, 1, sink, 0, None) == bad
+    lib.svdmlp_roof_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    assert lib.svdmlp_roof_mfma(0, sink, 4, None) == bad
+    assert lib.svdmlp_roof_mfma(8, None, 4, None) == bad
+    lib.svdmlp_roof_coexec.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    assert lib.svdmlp_roof_coexec(-1, 1, sink, 4, None) == bad
+    assert lib.svdmlp_roof_coexec(1, 1, None, 4, None) == bad
+    lib.svdmlp_roof_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    assert lib.svdmlp_roof_empty(0, 64, None) == bad
+    assert lib.svdmlp_roof_empty(4, 2048, None) == bad
+    lib.svdmlp_roof_empty_chain.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    assert lib.svdmlp_roof_empty_chain(0, 4, 64, None) == bad
+    assert lib.svdmlp_roof_empty_chain(4, 4, 0, None) == bad
+    lib.svdmlp_roof_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    assert lib.svdmlp_roof_read(None, 1 << 20, sink, 4, None) == bad
+    assert lib.svdmlp_roof_read(buf, 1024, sink, 4, None) == bad                       # less than one block
+    assert lib.svdmlp_roof_read(ctypes.c_void_p(0x10004), 1 << 20, sink, 4, None) == bad   # not 16-byte aligned
+    assert lib.svdmlp_roof_read(buf, 1 << 20, None, 4, None) == bad
