@@ -603,21 +603,33 @@ __global__ __launch_bounds__(256) void k_s5(const char* __restrict__ Td, const c
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();
+  // Epilogue through LDS (the ring is free now): a lane holds one column of sixteen rows, which as direct stores is
+  // two bytes per lane and 64 store instructions per wave.  The tile is laid out row-major in LDS as bf16 (rows 272
+  // bytes apart: the 16 bytes of padding spread the rows over the banks), then every lane moves 16 bytes at a time:
+  // sixteen lanes cover the 256 contiguous bytes of a row of Y.
+  constexpr int YS = 128 * 2 + 16;
+  static_assert(128 * YS <= NU5 * UNIT_BYTES, "the tile fits the ring");
+  __syncthreads();   // every wave has read its last frags
   const int il = lane % 32, h = lane / 32;
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      const int c = 128 * ct + 64 * wq + 32 * b + il;
+      const int cl = 64 * wq + 32 * b + il;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int m = 128 * mt + 64 * wp + 32 * a + 8 * (e / 4) + 4 * h + (e % 4);
-        if (m < M) {
-          __bf16 v = (__bf16)acc[a][b][e];
-          Y[(size_t)m * d + c] = *reinterpret_cast<uint16_t*>(&v);
-        }
+        const int ml = 64 * wp + 32 * a + 8 * (e / 4) + 4 * h + (e % 4);
+        *reinterpret_cast<__bf16*>(lds + ml * YS + 2 * cl) = (__bf16)acc[a][b][e];
       }
     }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int chunk = i * 256 + (int)threadIdx.x, row = chunk / 16, cc = chunk % 16;
+    const int m = 128 * mt + row;
+    if (m < M)
+      *reinterpret_cast<u32x4*>(Y + (size_t)m * d + 128 * ct + 8 * cc) = *reinterpret_cast<const u32x4*>(lds + row * YS + 16 * cc);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
