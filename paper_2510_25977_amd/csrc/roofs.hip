@@ -39,7 +39,8 @@ __global__ __launch_bounds__(256) void k_roof_read(const u32x4* __restrict__ src
 
 // operands: 0 all zero, 1 a few small values that repeat over the lanes (few bits toggle), 2 pseudo-random values
 // uniform in (-1, 1), different in every lane, wave and workgroup
-__global__ __launch_bounds__(512) void k_roof_mfma(int iters, int operands, float* __restrict__ sink) {
+template <int operands>   // a template parameter so that a kernel trace names the operand set
+__global__ __launch_bounds__(512) void k_roof_mfma(int iters, float* __restrict__ sink) {
   const int lane = threadIdx.x % 64;
   bf16x8 a0, a1, b0, b1;
 #pragma unroll
@@ -117,7 +118,8 @@ __global__ __launch_bounds__(512) void k_roof_coexec(int mfma_iters, int valu_it
 
 // The phase skeleton of gemm.hip on LDS-resident operands (see the list at the top).  Wave w owns rows 128 (w / 4)..
 // and columns 64 (w % 4).. of a 256 x 256 tile; a step is two contraction blocks; four 32 KiB slots are read in turn.
-__global__ __launch_bounds__(512) void k_roof_pingpong(int steps, int operands, float* __restrict__ sink) {
+template <int operands>
+__global__ __launch_bounds__(512) void k_roof_pingpong(int steps, float* __restrict__ sink) {
   __shared__ __attribute__((aligned(1024))) char lds[4 * 32 * FRAG_BYTES];
   const int lane = threadIdx.x % 64, w = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const int wm = w / 4, wn = w % 4;
@@ -216,8 +218,12 @@ int svdmlp_roof_read(const void* buf, size_t bytes, void* sink, int workgroups, 
 
 int svdmlp_roof_mfma_operands(int iters, int operands, void* sink, int workgroups, void* hip_stream) {
   if (!sink || iters <= 0 || workgroups <= 0 || operands < 0 || operands > 2) return SVDMLP_INVALID_ARGUMENT;
-  hipLaunchKernelGGL(k_roof_mfma, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(hip_stream), iters, operands,
-                     static_cast<float*>(sink));
+  const dim3 grid(workgroups), block(512);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* out = static_cast<float*>(sink);
+  if (operands == 0) hipLaunchKernelGGL(k_roof_mfma<0>, grid, block, 0, st, iters, out);
+  else if (operands == 1) hipLaunchKernelGGL(k_roof_mfma<1>, grid, block, 0, st, iters, out);
+  else hipLaunchKernelGGL(k_roof_mfma<2>, grid, block, 0, st, iters, out);
   if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
   return SVDMLP_OK;
 }
@@ -228,8 +234,12 @@ int svdmlp_roof_mfma(int iters, void* sink, int workgroups, void* hip_stream) {
 
 int svdmlp_roof_pingpong(int steps, int operands, void* sink, int workgroups, void* hip_stream) {
   if (!sink || steps <= 0 || workgroups <= 0 || operands < 0 || operands > 2) return SVDMLP_INVALID_ARGUMENT;
-  hipLaunchKernelGGL(k_roof_pingpong, dim3(workgroups), dim3(512), 0, static_cast<hipStream_t>(hip_stream), steps, operands,
-                     static_cast<float*>(sink));
+  const dim3 grid(workgroups), block(512);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* out = static_cast<float*>(sink);
+  if (operands == 0) hipLaunchKernelGGL(k_roof_pingpong<0>, grid, block, 0, st, steps, out);
+  else if (operands == 1) hipLaunchKernelGGL(k_roof_pingpong<1>, grid, block, 0, st, steps, out);
+  else hipLaunchKernelGGL(k_roof_pingpong<2>, grid, block, 0, st, steps, out);
   if (hipGetLastError() != hipSuccess) return SVDMLP_HIP_ERROR;
   return SVDMLP_OK;
 }

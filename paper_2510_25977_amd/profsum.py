@@ -3,6 +3,8 @@
     python -m paper_2510_25977_amd.profsum stats   <dir>                 # --kernel-trace run: calls, avg / min / max
     python -m paper_2510_25977_amd.profsum traffic <fetch_dir> <write_dir>   # --pmc FETCH_SIZE and --pmc WRITE_SIZE runs
     python -m paper_2510_25977_amd.profsum counters <dir> [<dir> ...]    # any --pmc run: per-kernel averages
+    python -m paper_2510_25977_amd.profsum roofs   <dir>                 # --kernel-trace run of `bench.py --roofs`: the
+                                                                         # roof kernels' durations and the rates they mean
     python -m paper_2510_25977_amd.profsum derived <dir> [<dir> ...]     # --pmc runs that together hold the counters
                                                                          # below: per-kernel derived figures
 
@@ -20,6 +22,7 @@ import statistics
 import sys
 
 COPY_BYTES = 256 << 20
+N_CU, N_XCD = 256, 8
 STREAM_PHASE = {"0": "d1", "1": "d2", "2": "d4", "3": "d5"}
 
 
@@ -28,6 +31,9 @@ def short_name(name: str) -> str:
     m = re.match(r"k_stream(16)?<(\d)", n)
     if m:
         return "k_stream_" + STREAM_PHASE.get(m.group(2), m.group(2))
+    m = re.match(r"(k_roof_(?:mfma|pingpong))<(\d)", n)
+    if m:
+        return m.group(1) + "_" + {"0": "zero", "1": "constant", "2": "random"}[m.group(2)] + "_operands"
     m = re.match(r"(k_[a-z0-9_]+)", n)
     if m:
         return m.group(1)
@@ -74,6 +80,23 @@ def cmd_stats(d: str) -> None:
                   f"min {min(v):8.1f}  max {max(v):8.1f}  {100 * sum(v) / total:5.1f} %")
 
 
+def cmd_roofs(d: str) -> None:
+    """Durations of the roof kernels of one `bench.py --roofs` run by the profiler's clock, and the MFMA rates they
+    mean (bench.py's iteration counts: 8000 iterations x 4 MFMAs per wave for k_roof_mfma, 4000 steps x 16 MFMAs for
+    k_roof_pingpong; eight waves per workgroup, one workgroup per CU, 32768 FLOP per MFMA)."""
+    dur = kernel_stats(d)
+    flop = {"k_roof_mfma": N_CU * 8 * 4 * 8000 * 32768, "k_roof_pingpong": N_CU * 8 * 16 * 4000 * 32768}
+    print("roof kernels (microseconds; every launch of the run):")
+    for k, v in sorted(dur.items()):
+        if not k.startswith("k_roof"):
+            continue
+        line = f"  {k:40s} calls {len(v):5d}  median {statistics.median(v):10.1f}  min {min(v):10.1f}"
+        for base, fl in flop.items():
+            if k.startswith(base + "_"):
+                line += f"   {fl / statistics.median(v) / 1e6:7.0f} TFLOP/s (median), {fl / min(v) / 1e6:7.0f} (best)"
+        print(line)
+
+
 def cmd_traffic(fetch_dir: str, write_dir: str) -> None:
     f, _ = counter_means(fetch_dir)
     w, _ = counter_means(write_dir)
@@ -101,9 +124,6 @@ def cmd_counters(dirs) -> None:
         for k, cs in means.items():
             if is_ours(k):
                 print(f"  {k:14s} (n={n[k]:3d}) " + "  ".join(f"{c} {v:.4g}" for c, v in sorted(cs.items())))
-
-
-N_CU, N_XCD = 256, 8
 
 
 def cmd_derived(dirs) -> None:
@@ -151,6 +171,8 @@ def main(argv) -> None:
         cmd_traffic(argv[2], argv[3])
     elif len(argv) >= 3 and argv[1] == "counters":
         cmd_counters(argv[2:])
+    elif len(argv) >= 3 and argv[1] == "roofs":
+        cmd_roofs(argv[2])
     elif len(argv) >= 3 and argv[1] == "derived":
         cmd_derived(argv[2:])
     else:
